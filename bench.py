@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the SmoothRot W4A4 linear hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One "step" = the online hot path of the two prefill linears of the benchmark
+configuration (X fp16 [2048, 4096]; W [4096, 4096] and W [4096, 14336]):
+    sr_fwht_quant_act(X) -> sr_w4a4_gemm(N = 4096)
+    sr_fwht_quant_act(X) -> sr_w4a4_gemm(N = 14336)
+Inputs are resident in HBM; the step rotates over several distinct input / weight
+sets so that no call finds its operands in the 256 MB Infinity Cache.
+The offline rows (calibration absmax, weight fold) and the decode shapes are
+timed separately and reported in the same JSON line under "extra".
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, TOP/s
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, GB/s
+
+M, K = 2048, 4096
+NS = (4096, 14336)
+CLIP, ALPHA = 0.9, 0.5
+SETS = 8                     # distinct (X, Wq) sets rotated through: 8 * (16.8 + 37.7) MB > 256 MB
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the decode / offline side measurements")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2506_05413_amd as sr
+    import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    # ---------------- offline preparation (timed separately) -----------------------------
+    calib = [torch.from_numpy(wl.cfg2_calib_chunk(i)).to(dev) for i in range(16)]   # 16 x 16.8 MB = 268 MB
+    absmax = torch.zeros(K, dtype=torch.float32, device=dev)
+    for c in calib:
+        sr.sr_calib_absmax(c, absmax)
+    torch.cuda.synchronize()
+
+    def ev_time(fn, iters):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(iters):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / iters        # seconds per call
+
+    extra = {}
+    scratch = torch.zeros(K, dtype=torch.float32, device=dev)
+    if not args.no_extra:
+        for _ in range(2):
+            t = ev_time(lambda i: sr.sr_calib_absmax(calib[i % 16], scratch), 32)
+        extra["calib_absmax"] = {"GB/s": round(M * K * 2 / t / 1e9, 1), "us": round(t * 1e6, 2),
+                                 "frac_hbm": round(M * K * 2 / t / 1e9 / PEAK_HBM_GBS, 4),
+                                 "workload": "fp16 [2048,4096] chunks, 16 distinct (268 MB)"}
+
+    Xs = [torch.from_numpy(wl.cfg2_X(seed=1 + 10 * s)).to(dev) for s in range(SETS)]
+    Wq, Ws, inv_s = {}, {}, None
+    for N in NS:
+        W = torch.from_numpy(wl.cfg2_W(N)).to(dev)
+        ws_bytes = sr.sr_fold_workspace_bytes(K, N)
+        work = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        outs = sr.sr_fold_smooth_rotate_quant(W, absmax, ALPHA, 1.0, workspace=work)
+        torch.cuda.synchronize()
+        if not args.no_extra:
+            t = ev_time(lambda i: sr.sr_fold_smooth_rotate_quant(W, absmax, ALPHA, 1.0, *outs, workspace=work), 5)
+            extra["fold_N%d" % N] = {"us": round(t * 1e6, 1), "GB/s": round((K * N * 2.5) / t / 1e9, 1)}
+        # weight sets: the same codes rolled along N, so every set is a distinct buffer with identical statistics
+        Wq[N] = [torch.roll(outs[0], s * 16, 0).contiguous() for s in range(SETS)]
+        Ws[N] = [torch.roll(outs[1], s * 16, 0).contiguous() for s in range(SETS)]
+        inv_s = outs[2]
+        del W, work
+
+    Xq = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
+    xs = torch.empty(M, dtype=torch.float32, device=dev)
+    Y = {N: torch.empty((M, N), dtype=torch.float16, device=dev) for N in NS}
+
+    def step(i):
+        s = i % SETS
+        for N in NS:
+            sr.sr_fwht_quant_act(Xs[s], inv_s, CLIP, Xq, xs)
+            sr.sr_w4a4_gemm(Xq, xs, Wq[N][s], Ws[N][s], sr.SR_F16, Y[N])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # ---------------- timed region: exactly `steps` steps -------------------------------
+    # HIP events bracket the dominant kernel (the N = 14336 GEMM) of every step, on the stream it runs on.
+    gemm_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        s = i % SETS
+        sr.sr_fwht_quant_act(Xs[s], inv_s, CLIP, Xq, xs)
+        sr.sr_w4a4_gemm(Xq, xs, Wq[4096][s], Ws[4096][s], sr.SR_F16, Y[4096])
+        sr.sr_fwht_quant_act(Xs[s], inv_s, CLIP, Xq, xs)
+        gemm_ev[i][0].record()
+        sr.sr_w4a4_gemm(Xq, xs, Wq[14336][s], Ws[14336][s], sr.SR_F16, Y[14336])
+        gemm_ev[i][1].record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    ops_per_step = sum(2.0 * M * N * K for N in NS)
+    tops = ops_per_step / (dt / args.steps) / 1e12
+    gemm_ms = sorted(a.elapsed_time(b) for a, b in gemm_ev)
+    gemm_avg_s = sum(gemm_ms) / len(gemm_ms) * 1e-3
+    gemm_ops = 2.0 * M * 14336 * K
+    roofline = {"bound": "mfma", "kernel": "gemm_w4a4_kernel (M=2048, N=14336, K=4096)",
+                "achieved": round(gemm_ops / gemm_avg_s / 1e12, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                "frac": round(gemm_ops / gemm_avg_s / 1e12 / PEAK_INT8_TOPS, 4), "traffic": None,
+                "avg_launch_us": round(gemm_avg_s * 1e6, 2), "median_launch_us": round(gemm_ms[len(gemm_ms) // 2] * 1e3, 2)}
+
+    # ---------------- per-kernel side measurements (same buffers, event-timed) ------------
+    if not args.no_extra:
+        t = ev_time(lambda i: sr.sr_fwht_quant_act(Xs[i % SETS], inv_s, CLIP, Xq, xs), 64)
+        b = M * K * 2.5 + M * 4
+        extra["fwht_quant_K4096"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
+                                     "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+        for N in NS:
+            t = ev_time(lambda i: sr.sr_w4a4_gemm(Xq, xs, Wq[N][i % SETS], Ws[N][i % SETS], sr.SR_F16, Y[N]), 64)
+            extra["gemm_N%d" % N] = {"us": round(t * 1e6, 2), "TOPS": round(2.0 * M * N * K / t / 1e12, 1),
+                                     "frac_mfma": round(2.0 * M * N * K / t / 1e12 / PEAK_INT8_TOPS, 4)}
+        # decode: M in {1,4,16}, K=4096 -> N=14336, weights streamed from >512 MB of distinct copies
+        copies = [Wq[14336][0].clone() for _ in range(20)]
+        wsc = Ws[14336][0]
+        for Md in (1, 4, 16):
+            Xd = Xs[0][:Md].contiguous()
+            xq_d, xs_d = sr.sr_fwht_quant_act(Xd, inv_s, CLIP)
+            Yd = torch.empty((Md, 14336), dtype=torch.float16, device=dev)
+            for _ in range(2):
+                t = ev_time(lambda i: sr.sr_w4a4_gemm(xq_d, xs_d, copies[i % 20], wsc, sr.SR_F16, Yd), 100)
+            b = 14336 * K / 2 + Md * K / 2 + 2 * Md * 14336
+            extra["decode_M%d_4096x14336" % Md] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
+                                                    "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+        del copies
+
+    # ---------------- CPU baseline: the oracle on a bounded sample ------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import smoothrot_oracle as o
+        rows = 128
+        Xh = Xs[0][:rows].cpu().numpy()
+        inv_h = inv_s.cpu().numpy()
+        cws = {N: o.unpack_int4(Wq[N][0].cpu().numpy()) for N in NS}
+        wsh = {N: Ws[N][0].cpu().numpy() for N in NS}
+        o.gemm_i32_c(np.zeros((1, 64), np.int8), np.zeros((1, 64), np.int8))     # load the C library
+        t0 = time.perf_counter()
+        for N in NS:
+            act = o.fwht_quant_act(Xh, inv_h, CLIP)
+            acc = o.gemm_i32_c(act["codes"], cws[N])
+            o.dequant_out(acc, act["x_scale"], wsh[N])
+        tc = time.perf_counter() - t0
+        cpu = {"value": round(sum(2.0 * rows * N * K for N in NS) / tc / 1e12, 5), "unit": "TOPS",
+               "cores": o.c_threads(), "kind": "oracle",
+               "sample": "%d of %d token rows through both linears (rotate+quantise, int GEMM, dequantise); %.1f s" % (rows, M, tc)}
+
+    line = {
+        "metric": "W4A4 linear TOPS (prefill; FWHT + INT4 quantise + INT4 GEMM + dequant)",
+        "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int4 codes on int8 MFMA, int32 accumulate; fp32 rotation",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: prefill X fp16 [2048,4096], two linears N=4096 and N=14336, "
+                               "alpha=0.5, act clip 0.9, H_4096; step = 2 x (sr_fwht_quant_act + sr_w4a4_gemm)",
+                   "M": M, "K": K, "N": list(NS), "input_sets_rotated": SETS},
+        "frac_int8_mfma_peak": round(tops / PEAK_INT8_TOPS, 4),
+        "roofline": roofline, "cpu_baseline": cpu, "extra": extra,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

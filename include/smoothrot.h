@@ -1,0 +1,152 @@
+/*
+ * smoothrot.h -- C ABI of the MI355X (gfx950) SmoothRot W4A4 linear-layer library.
+ *
+ * SmoothRot (arXiv 2506.05413) smooths the input channels of a linear layer with
+ * calibrated factors s, rotates them with a Hadamard matrix H, and runs the layer
+ * with 4-bit weights and 4-bit activations:
+ *
+ *     Y = X W = (X diag(1/s) H) (H^T diag(s) W / n)          [paper, Eq. (2), A = (H Lambda)^-1]
+ *
+ * The calls below are the four operations of that layer.  Two are offline
+ * (calibration, weight fold), two are the online hot path (rotate + quantise the
+ * activations, INT4 x INT4 GEMM with dequantising epilogue).
+ *
+ * Conventions that hold for every call
+ * ------------------------------------
+ *  - Every data pointer is DEVICE memory owned by the caller.  The library never
+ *    allocates, frees or keeps a pointer, has no global state and is re-entrant.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *    only enqueue work and return; they never synchronise.
+ *  - Arguments are validated on the host before anything is launched.  On error a
+ *    status is returned, nothing is launched and outputs are untouched.
+ *  - Input and output buffers must not overlap.  Non-finite inputs give
+ *    unspecified values (never an out-of-bounds access).
+ *  - X is [tokens, K] row-major fp16 (row = token, K = input channels);
+ *    W is [K, N] row-major fp16 (N = output channels).
+ *  - H is the unnormalised +-1 Hadamard matrix of order K: Sylvester
+ *    (H[i][j] = (-1)^popcount(i&j)) for K = 2^p; H_28 (x) H_{2^p} for K = 28 * 2^p,
+ *    with H_28 the Paley type-I matrix over GF(27) = GF(3)[x]/(x^3+2x+1) and the
+ *    28-index the slow one.  The rotation is T(v)_j = sum_k v_k H[k][j].
+ *  - INT4 codes are two's-complement values in [-8, 7], packed two per byte along
+ *    K: byte b of a row holds code(2b) in bits 0-3 and code(2b+1) in bits 4-7.
+ *  - Supported shapes: K = 2^p or 28 * 2^p with 64 <= K <= 32768 (28 * 2^p: <= 28672);
+ *    N a multiple of 16; any M >= 1 (M = 0 or T = 0 is a no-op returning SR_OK).
+ *    Base pointers must be 16-byte aligned and leading dimensions multiples of 8.
+ */
+#ifndef SMOOTHROT_H
+#define SMOOTHROT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__GNUC__) || defined(__clang__)
+#define SR_API __attribute__((visibility("default")))
+#else
+#define SR_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SR_OK = 0,
+    SR_ERR_NULL = 1,          /* a required pointer is NULL                               */
+    SR_ERR_SHAPE = 2,         /* negative size, N % 16 != 0, leading dimension too small  */
+    SR_ERR_UNSUPPORTED_K = 3, /* K is not 2^p / 28*2^p in the supported range             */
+    SR_ERR_ALIGN = 4,         /* pointer not 16-byte aligned / ld not a multiple of 8     */
+    SR_ERR_ARG = 5,           /* alpha outside [0,1], clip outside (0,1], unknown dtype   */
+    SR_ERR_WORKSPACE = 6,     /* workspace NULL or smaller than sr_*_workspace_bytes      */
+    SR_ERR_DEVICE = 7         /* the HIP runtime refused a launch                          */
+} sr_status;
+
+/* Output type selector of sr_w4a4_gemm. */
+enum { SR_F16 = 0, SR_I32 = 1 };
+
+/* Static, NUL-terminated description of a status (never NULL). */
+SR_API const char *sr_status_str(int status);
+
+/* 1 if a Hadamard matrix of order K is implemented (see "Supported shapes"), else 0. */
+SR_API int sr_hadamard_supported(int64_t K);
+
+/* Bytes of device scratch sr_fold_smooth_rotate_quant needs for a [K, N] weight
+ * (0 if the shape is unsupported). */
+SR_API size_t sr_fold_workspace_bytes(int64_t K, int64_t N);
+
+/* Bytes of device scratch sr_w4a4_gemm needs (currently 0 for every shape: partial
+ * sums are reduced on chip; the argument is kept so callers need not change). */
+SR_API size_t sr_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/*
+ * Calibration: running per-channel activation maximum,
+ *     absmax_io[j] <- max(absmax_io[j], max_t |X[t][j]|)
+ * -- the max|X_j| of the smoothing-factor formula (paper, section "Methodology").
+ *
+ *   X_f16      fp16 [T, K], row stride ldx elements (ldx >= K)
+ *   absmax_io  fp32 [K], in/out; the caller zero-initialises it before the first
+ *              call and may call repeatedly over chunks of the calibration set
+ *              (values must be >= 0).  The result is exact.
+ */
+SR_API int sr_calib_absmax(const void *X_f16, int64_t T, int64_t K, int64_t ldx,
+                    float *absmax_io, void *stream);
+
+/*
+ * Weight fold (offline), paper section "Methodology" + "Quantization" settings:
+ *     w_j   = max_n |W[j][n]|                         (input channel j, W as given)
+ *     s_j   = max(a_j,1e-5)^alpha / max(w_j,1e-5)^(1-alpha)
+ *     W^    = H^T diag(s) W / K                        (T applied to the columns of diag(s) W)
+ *     dw_n  = w_clip * max_j |W^[j][n]| / 7            (per output channel; 1 if the column is 0)
+ *     code  = clamp(rint(W^[j][n] / dw_n), -8, 7)      (round-to-nearest, ties to even)
+ *
+ *   W_f16       fp16 [K, N], row stride ldw (ldw >= N)
+ *   act_absmax  fp32 [K] from sr_calib_absmax, or NULL for s = 1 (rotation only)
+ *   alpha       migration strength in [0, 1];  w_clip in (0, 1] (1 = plain RTN)
+ *   Wq          out, uint8 [N, K/2] packed codes, output channel major
+ *   w_scale     out, fp32 [N]  (dw_n)
+ *   inv_s       out, fp32 [K]  (1 / s_j), may be NULL
+ *   workspace   at least sr_fold_workspace_bytes(K, N) bytes, 256-byte aligned
+ */
+SR_API int sr_fold_smooth_rotate_quant(const void *W_f16, int64_t K, int64_t N, int64_t ldw,
+                                const float *act_absmax, float alpha, float w_clip,
+                                uint8_t *Wq, float *w_scale, float *inv_s,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Online rotation + per-token quantisation (paper: online Hadamard before the
+ * projection, then per-token symmetric INT4 with a constant clipping ratio; Eq. (1)):
+ *     y_m   = (x_m * inv_s) H                          (fp32, never written to memory)
+ *     dx_m  = clip * max_j |y_mj| / 7                  (1 if the row is 0)
+ *     code  = clamp(rint(y_mj / dx_m), -8, 7)
+ *
+ *   X_f16    fp16 [M, K], row stride ldx
+ *   inv_s    fp32 [K] or NULL (activations already smoothed upstream, as when the
+ *            factors are absorbed into the preceding projection)
+ *   clip     clipping ratio in (0, 1] (paper: 0.9)
+ *   Xq       out, uint8 [M, K/2] packed codes;  x_scale out, fp32 [M] (dx_m)
+ */
+SR_API int sr_fwht_quant_act(const void *X_f16, int64_t M, int64_t K, int64_t ldx,
+                      const float *inv_s, float clip,
+                      uint8_t *Xq, float *x_scale, void *stream);
+
+/*
+ * INT4 x INT4 GEMM with INT32 accumulation and dequantising epilogue
+ * (paper: quantised forward pass; dequantisation Q(X) = X_int * Delta of Eq. (1)):
+ *     acc[m][n] = sum_k codeX[m][k] * codeW[n][k]      (exact)
+ *     Y[m][n]   = fp16( float(acc) * x_scale[m] * w_scale[n] )      out_dtype = SR_F16
+ *     Y[m][n]   = acc[m][n] as int32 (scales ignored, may be NULL)  out_dtype = SR_I32
+ *
+ *   Xq [M, K/2], Wq [N, K/2] packed codes as produced by the two calls above
+ *   Y   out, [M, N] with row stride ldy elements (fp16 or int32), ldy >= N
+ *   workspace / workspace_bytes: see sr_gemm_workspace_bytes (may be NULL / 0 when that is 0)
+ *   K only needs to be a multiple of 64 here (no Hadamard involved), K < 131072.
+ */
+SR_API int sr_w4a4_gemm(const uint8_t *Xq, const float *x_scale,
+                 const uint8_t *Wq, const float *w_scale,
+                 int64_t M, int64_t N, int64_t K,
+                 void *Y, int64_t ldy, int out_dtype,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SMOOTHROT_H */

@@ -1,0 +1,152 @@
+"""ctypes binding of libsmoothrot.so -- argument marshalling only.
+
+Function names and argument order follow include/smoothrot.h.  torch supplies
+device memory and the current stream; every step of the computation runs in the
+library's HIP kernels.  There is no fallback: if the shared library is missing
+or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+SR_OK, SR_ERR_NULL, SR_ERR_SHAPE, SR_ERR_UNSUPPORTED_K = 0, 1, 2, 3
+SR_ERR_ALIGN, SR_ERR_ARG, SR_ERR_WORKSPACE, SR_ERR_DEVICE = 4, 5, 6, 7
+SR_F16, SR_I32 = 0, 1
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libsmoothrot.so")
+
+_c = ctypes
+_vp, _i64, _f32, _sz, _int = _c.c_void_p, _c.c_int64, _c.c_float, _c.c_size_t, _c.c_int
+
+_SIGNATURES = {
+    "sr_status_str": (_c.c_char_p, [_int]),
+    "sr_hadamard_supported": (_int, [_i64]),
+    "sr_fold_workspace_bytes": (_sz, [_i64, _i64]),
+    "sr_gemm_workspace_bytes": (_sz, [_i64, _i64, _i64]),
+    "sr_calib_absmax": (_int, [_vp, _i64, _i64, _i64, _vp, _vp]),
+    "sr_fold_smooth_rotate_quant": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "sr_fwht_quant_act": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _vp]),
+    "sr_w4a4_gemm": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _int, _vp, _sz, _vp]),
+}
+
+_lib = None
+
+
+class SmoothRotError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = raw().sr_status_str(status).decode()
+        super().__init__("%s: status %d (%s)" % (where, status, msg))
+
+
+def raw() -> ctypes.CDLL:
+    """The loaded C library with argtypes set (loads it on first use)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libsmoothrot.so is not built: run `python -m paper_2506_05413_amd.build` "
+                              "(there is no fallback path)")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(status: int, where: str):
+    if status != SR_OK:
+        raise SmoothRotError(status, where)
+
+
+def _dev(t: torch.Tensor, dtype, name: str):
+    if not t.is_cuda:
+        raise ValueError("%s must be a device tensor" % name)
+    if t.dtype != dtype:
+        raise ValueError("%s must have dtype %s" % (name, dtype))
+    if t.dim() == 2 and t.stride(1) != 1 or t.dim() == 1 and t.numel() > 1 and t.stride(0) != 1:
+        raise ValueError("%s must be contiguous along its last dimension" % name)
+
+
+def sr_status_str(status: int) -> str:
+    return raw().sr_status_str(status).decode()
+
+
+def sr_hadamard_supported(K: int) -> bool:
+    return bool(raw().sr_hadamard_supported(K))
+
+
+def sr_fold_workspace_bytes(K: int, N: int) -> int:
+    return int(raw().sr_fold_workspace_bytes(K, N))
+
+
+def sr_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(raw().sr_gemm_workspace_bytes(M, N, K))
+
+
+def sr_calib_absmax(X: torch.Tensor, absmax_io: torch.Tensor) -> torch.Tensor:
+    """absmax_io[j] <- max(absmax_io[j], max_t |X[t][j]|); X fp16 [T, K], absmax_io fp32 [K]."""
+    _dev(X, torch.float16, "X"); _dev(absmax_io, torch.float32, "absmax_io")
+    T, K = X.shape
+    ldx = X.stride(0) if T > 1 else K
+    _check(raw().sr_calib_absmax(_ptr(X), T, K, ldx, _ptr(absmax_io), _stream()), "sr_calib_absmax")
+    return absmax_io
+
+
+def sr_fold_smooth_rotate_quant(W, act_absmax, alpha: float, w_clip: float = 1.0,
+                                Wq=None, w_scale=None, inv_s=None, workspace=None):
+    """W fp16 [K, N] -> (Wq uint8 [N, K/2], w_scale fp32 [N], inv_s fp32 [K])."""
+    _dev(W, torch.float16, "W")
+    K, N = W.shape
+    dev = W.device
+    Wq = torch.empty((N, K // 2), dtype=torch.uint8, device=dev) if Wq is None else Wq
+    w_scale = torch.empty(N, dtype=torch.float32, device=dev) if w_scale is None else w_scale
+    inv_s = torch.empty(K, dtype=torch.float32, device=dev) if inv_s is None else inv_s
+    if workspace is None:
+        workspace = torch.empty(max(sr_fold_workspace_bytes(K, N), 256), dtype=torch.uint8, device=dev)
+    _check(raw().sr_fold_smooth_rotate_quant(_ptr(W), K, N, W.stride(0), _ptr(act_absmax), alpha, w_clip,
+                                             _ptr(Wq), _ptr(w_scale), _ptr(inv_s), _ptr(workspace),
+                                             workspace.numel(), _stream()),
+           "sr_fold_smooth_rotate_quant")
+    return Wq, w_scale, inv_s
+
+
+def sr_fwht_quant_act(X, inv_s, clip: float = 0.9, Xq=None, x_scale=None):
+    """X fp16 [M, K] -> (Xq uint8 [M, K/2], x_scale fp32 [M])."""
+    _dev(X, torch.float16, "X")
+    M, K = X.shape
+    Xq = torch.empty((M, K // 2), dtype=torch.uint8, device=X.device) if Xq is None else Xq
+    x_scale = torch.empty(M, dtype=torch.float32, device=X.device) if x_scale is None else x_scale
+    ldx = X.stride(0) if M > 1 else K
+    _check(raw().sr_fwht_quant_act(_ptr(X), M, K, ldx, _ptr(inv_s), clip, _ptr(Xq), _ptr(x_scale), _stream()),
+           "sr_fwht_quant_act")
+    return Xq, x_scale
+
+
+def sr_w4a4_gemm(Xq, x_scale, Wq, w_scale, out_dtype: int = SR_F16, Y=None, workspace=None):
+    """Xq uint8 [M, K/2], Wq uint8 [N, K/2] -> Y [M, N] fp16 (dequantised) or int32 (accumulators)."""
+    _dev(Xq, torch.uint8, "Xq"); _dev(Wq, torch.uint8, "Wq")
+    M, Kb = Xq.shape
+    N = Wq.shape[0]
+    if Wq.shape[1] != Kb:
+        raise ValueError("Xq and Wq disagree on K")
+    if Y is None:
+        Y = torch.empty((M, N), dtype=torch.float16 if out_dtype == SR_F16 else torch.int32, device=Xq.device)
+    ldy = Y.stride(0) if M > 1 else N
+    _check(raw().sr_w4a4_gemm(_ptr(Xq), _ptr(x_scale), _ptr(Wq), _ptr(w_scale), M, N, 2 * Kb, _ptr(Y), ldy,
+                              out_dtype, _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                              _stream()),
+           "sr_w4a4_gemm")
+    return Y

@@ -1,0 +1,284 @@
+// Online Hadamard rotation fused with per-row symmetric INT4 quantisation.
+//
+// One workgroup owns one row (a token of X, or an output channel of the transposed,
+// smoothed weight during the fold).  The row is converted to fp32, rotated by
+// T(v) = v H on chip and quantised; only the packed codes and one scale per row go
+// back to memory.  (Paper: online exact Hadamard before the projection, section
+// "Methodology"; quantiser Eq. (1) with per-token / per-channel symmetric scales.)
+//
+// Rotation schedule.  H = (x) of 2x2 Sylvester factors (and H_28 for K = 28 * 2^p);
+// Kronecker factors commute, so the butterflies are grouped into passes of up to four
+// index bits that a thread can do entirely in registers on 16 values:
+//   pass 1   bits 0-3, straight from the global load (16 contiguous fp16 per group)
+//   pass 2.. bits 4-7, 8-11, ... gathered from / scattered to an fp32 row in LDS
+//   H_28     28 values at stride 2^p per group, as  y_j = S - 2 * sum_{H[i][j]=-1} v_i
+// The LDS row is padded by 4 floats per 64 so that every access pattern above is
+// bank-conflict free for K = 4096.
+#include "sr_common.h"
+
+#include <hip/hip_fp16.h>
+#include <utility>
+
+namespace sr {
+namespace {
+
+// ---- Paley type-I Hadamard matrix of order 28, built at compile time -------------
+// GF(27) = GF(3)[x] / (x^3 + 2x + 1); element c0 + c1 x + c2 x^2 has index c0 + 3 c1 + 9 c2.
+constexpr int gf27_sub(int a, int b)
+{
+    int r = 0, w = 1;
+    for (int d = 0; d < 3; ++d) {
+        r += ((a % 3 - b % 3 + 3) % 3) * w;
+        a /= 3; b /= 3; w *= 3;
+    }
+    return r;
+}
+constexpr int gf27_mul(int a, int b)
+{
+    int ca[3] = {a % 3, a / 3 % 3, a / 9}, cb[3] = {b % 3, b / 3 % 3, b / 9};
+    int p[5] = {0, 0, 0, 0, 0};
+    for (int i = 0; i < 3; ++i)
+        for (int j = 0; j < 3; ++j) p[i + j] += ca[i] * cb[j];
+    // x^3 = x + 2 and x^4 = x^2 + 2x over GF(3)
+    p[1] += 2 * p[4]; p[2] += p[4];
+    p[0] += 2 * p[3]; p[1] += p[3];
+    return p[0] % 3 + 3 * (p[1] % 3) + 9 * (p[2] % 3);
+}
+constexpr bool gf27_is_square(int e)
+{
+    for (int r = 1; r < 27; ++r)
+        if (gf27_mul(r, r) == e) return true;
+    return false;
+}
+// sign of H28[i][j]: first row +1, rest of first column -1, else chi(e_i - e_j) + identity
+constexpr int h28_sign(int i, int j)
+{
+    if (i == 0) return 1;
+    if (j == 0) return -1;
+    if (i == j) return 1;
+    return gf27_is_square(gf27_sub(i - 1, j - 1)) ? 1 : -1;
+}
+// bit i set  <=>  H28[i][j] == -1
+constexpr uint32_t h28_neg_mask(int j)
+{
+    uint32_t m = 0;
+    for (int i = 0; i < 28; ++i)
+        if (h28_sign(i, j) < 0) m |= 1u << i;
+    return m;
+}
+constexpr int popc(uint32_t v) { int c = 0; for (; v; v &= v - 1) ++c; return c; }
+
+template <int J>
+__device__ __forceinline__ float h28_col(const float (&v)[28], float S)
+{
+    constexpr uint32_t neg = h28_neg_mask(J);
+    if constexpr (popc(neg) <= 14) {
+        float n = 0.f;
+#pragma unroll
+        for (int i = 0; i < 28; ++i)
+            if ((neg >> i) & 1u) n += v[i];
+        return fmaf(-2.f, n, S);
+    } else {
+        float p = 0.f;
+#pragma unroll
+        for (int i = 0; i < 28; ++i)
+            if (!((neg >> i) & 1u)) p += v[i];
+        return fmaf(2.f, p, -S);
+    }
+}
+template <int... J>
+__device__ __forceinline__ void h28_apply(const float (&v)[28], float (&o)[28], float S,
+                                          std::integer_sequence<int, J...>)
+{
+    ((o[J] = h28_col<J>(v, S)), ...);
+}
+
+// ---- radix-2 butterflies on 2^B register values -----------------------------------
+template <int B>
+__device__ __forceinline__ void butterflies(float (&v)[1 << B])
+{
+#pragma unroll
+    for (int h = 1; h < (1 << B); h <<= 1) {
+#pragma unroll
+        for (int i = 0; i < (1 << B); ++i) {
+            if (!(i & h)) {
+                float a = v[i], b = v[i | h];
+                v[i] = a + b;
+                v[i | h] = a - b;
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ int pad(int i) { return i + ((i >> 6) << 2); }
+constexpr int padded_len(int K) { return K + (K >> 6) * 4; }
+
+constexpr int ilog2(int64_t v) { int l = 0; while ((int64_t(1) << (l + 1)) <= v) ++l; return l; }
+
+// In-LDS pass over index bits [LO, LO+B).
+template <int K, int NT, int LO, int B, bool TRACK>
+__device__ __forceinline__ void lds_pass(float *row, int t, float &amax)
+{
+    constexpr int E = 1 << B;
+    for (int g = t; g < (K >> B); g += NT) {
+        const int g_low = g & ((1 << LO) - 1);
+        const int base = ((g >> LO) << (LO + B)) | g_low;
+        float v[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) v[e] = row[pad(base + (e << LO))];
+        butterflies<B>(v);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            row[pad(base + (e << LO))] = v[e];
+            if (TRACK) amax = fmaxf(amax, fabsf(v[e]));
+        }
+    }
+}
+
+// All remaining power-of-two passes from bit LO up to LOGP.
+template <int K, int NT, int LO, int LOGP, bool TRACK_LAST>
+__device__ __forceinline__ void lds_passes(float *row, int t, float &amax)
+{
+    if constexpr (LO < LOGP) {
+        constexpr int B = (LOGP - LO) >= 4 ? 4 : (LOGP - LO);
+        constexpr bool last = (LO + B == LOGP);
+        lds_pass<K, NT, LO, B, last && TRACK_LAST>(row, t, amax);
+        __syncthreads();
+        lds_passes<K, NT, LO + B, LOGP, TRACK_LAST>(row, t, amax);
+    }
+}
+
+template <int K, int NT>
+__global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict__ X, int64_t ldx,
+                                                        const float *__restrict__ pre, float clip,
+                                                        float post_scale, uint8_t *__restrict__ Q,
+                                                        float *__restrict__ scale_out)
+{
+    constexpr bool KRON = !is_pow2(K);
+    constexpr int P2 = KRON ? K / 28 : K;       // power-of-two factor
+    constexpr int LOGP = ilog2(P2);
+    static_assert(LOGP >= 4 && K % 16 == 0, "first pass needs 16 contiguous values");
+
+    extern __shared__ float row[];
+    __shared__ float red[NT / 64];
+
+    const int t = threadIdx.x;
+    const int64_t m = blockIdx.x;
+    const __half *x = X + m * ldx;
+
+    // ---- pass 1: bits 0..3 from global ------------------------------------------------
+    for (int g = t; g < K / 16; g += NT) {
+        union { uint4 u[2]; __half h[16]; } raw;
+        raw.u[0] = *reinterpret_cast<const uint4 *>(x + 16 * g);
+        raw.u[1] = *reinterpret_cast<const uint4 *>(x + 16 * g + 8);
+        float v[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] = __half2float(raw.h[e]);
+        if (pre) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 s = *reinterpret_cast<const float4 *>(pre + 16 * g + 4 * q);
+                v[4 * q + 0] *= s.x; v[4 * q + 1] *= s.y; v[4 * q + 2] *= s.z; v[4 * q + 3] *= s.w;
+            }
+        }
+        butterflies<4>(v);
+        float *dst = row + pad(16 * g);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<float4 *>(dst + 4 * q) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+    }
+    __syncthreads();
+
+    // ---- remaining power-of-two bits ---------------------------------------------------
+    float amax = 0.f;
+    if constexpr (LOGP == 4 && !KRON) {
+        // K = 16 cannot occur (K >= 64); kept for completeness of the template
+    }
+    lds_passes<K, NT, 4, LOGP, !KRON>(row, t, amax);
+
+    // ---- Paley factor: 28 values at stride P2 per group ---------------------------------
+    if constexpr (KRON) {
+        for (int g = t; g < P2; g += NT) {
+            float v[28], o[28];
+            float S = 0.f;
+#pragma unroll
+            for (int i = 0; i < 28; ++i) {
+                v[i] = row[pad(g + i * P2)];
+                S += v[i];
+            }
+            h28_apply(v, o, S, std::make_integer_sequence<int, 28>{});
+#pragma unroll
+            for (int j = 0; j < 28; ++j) {
+                row[pad(g + j * P2)] = o[j];
+                amax = fmaxf(amax, fabsf(o[j]));
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- row absmax ----------------------------------------------------------------------
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+    if ((t & 63) == 0) red[t >> 6] = amax;
+    __syncthreads();
+    amax = red[0];
+#pragma unroll
+    for (int w = 1; w < NT / 64; ++w) amax = fmaxf(amax, red[w]);
+
+    // Delta = clip * absmax / 7 (1 for an all-zero row), Eq. (1) with the signed range
+    const float delta = (amax == 0.f) ? 1.f : (clip * amax) / 7.f;
+    const float inv_delta = 1.f / delta;
+    if (t == 0) scale_out[m] = (amax == 0.f) ? 1.f : delta * post_scale;
+
+    // ---- quantise 8 contiguous values -> one packed dword ---------------------------------
+    uint32_t *q = reinterpret_cast<uint32_t *>(Q + m * (int64_t)(K / 2));
+    for (int c = t; c < K / 8; c += NT) {
+        const float *src = row + pad(8 * c);
+        const float4 a = *reinterpret_cast<const float4 *>(src);
+        const float4 b = *reinterpret_cast<const float4 *>(src + 4);
+        const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        uint32_t word = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float r = rintf(v[e] * inv_delta);                 // round half to even
+            r = fminf(fmaxf(r, -8.f), 7.f);
+            word |= (static_cast<uint32_t>(static_cast<int>(r)) & 0xFu) << (4 * e);
+        }
+        q[c] = word;
+    }
+}
+
+template <int K>
+hipError_t launch_one(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip,
+                      float post_scale, uint8_t *Q, float *scale_out, hipStream_t st)
+{
+    constexpr int groups = K / 16;
+    constexpr int NT = groups >= 256 ? 256 : (groups >= 128 ? 128 : 64);
+    constexpr size_t lds = sizeof(float) * padded_len(K);
+    auto kern = fwht_quant_kernel<K, NT>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)rows), dim3(NT), lds, st,
+                       static_cast<const __half *>(X), ldx, pre, clip, post_scale, Q, scale_out);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_fwht_quant(const void *X, int64_t rows, int64_t K, int64_t ldx, const float *pre,
+                             float clip, float post_scale, uint8_t *Q, float *scale_out, hipStream_t st)
+{
+#define SR_CASE(KK) case KK: return launch_one<KK>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
+    switch (K) {
+        SR_CASE(64) SR_CASE(128) SR_CASE(256) SR_CASE(512) SR_CASE(1024) SR_CASE(2048)
+        SR_CASE(4096) SR_CASE(8192) SR_CASE(16384) SR_CASE(32768)
+        SR_CASE(448) SR_CASE(896) SR_CASE(1792) SR_CASE(3584) SR_CASE(7168) SR_CASE(14336) SR_CASE(28672)
+        default: return hipErrorInvalidValue;
+    }
+#undef SR_CASE
+}
+
+}  // namespace sr

@@ -1,0 +1,136 @@
+// C ABI of libsmoothrot: host-side argument validation and dispatch.
+// Every check happens before the first launch, so an error leaves all outputs untouched.
+#include "../../include/smoothrot.h"
+#include "sr_common.h"
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// layout of the fold workspace: [Wt fp16 N*K][s fp32 K][w_rowmax fp32 K]
+struct FoldWs { size_t wt, s, wmax, total; };
+inline FoldWs fold_ws(int64_t K, int64_t N)
+{
+    FoldWs w;
+    w.wt = 0;
+    w.s = round_up((size_t)N * (size_t)K * 2, 256);
+    w.wmax = w.s + round_up((size_t)K * 4, 256);
+    w.total = w.wmax + round_up((size_t)K * 4, 256);
+    return w;
+}
+
+inline int dev(hipError_t e) { return e == hipSuccess ? SR_OK : SR_ERR_DEVICE; }
+
+}  // namespace
+
+extern "C" {
+
+const char *sr_status_str(int status)
+{
+    switch (status) {
+        case SR_OK: return "ok";
+        case SR_ERR_NULL: return "a required pointer is NULL";
+        case SR_ERR_SHAPE: return "bad shape (negative size, N not a multiple of 16, or leading dimension too small)";
+        case SR_ERR_UNSUPPORTED_K: return "unsupported K (need 2^p or 28*2^p, 64 <= K <= 32768)";
+        case SR_ERR_ALIGN: return "pointer not 16-byte aligned or leading dimension not a multiple of 8";
+        case SR_ERR_ARG: return "argument out of range (alpha in [0,1], clip in (0,1], dtype)";
+        case SR_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case SR_ERR_DEVICE: return "HIP runtime error at launch";
+        default: return "unknown status";
+    }
+}
+
+int sr_hadamard_supported(int64_t K) { return sr::hadamard_supported(K) ? 1 : 0; }
+
+size_t sr_fold_workspace_bytes(int64_t K, int64_t N)
+{
+    if (!sr::hadamard_supported(K) || N <= 0 || N % 16 != 0) return 0;
+    return fold_ws(K, N).total;
+}
+
+size_t sr_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    (void)M; (void)N; (void)K;
+    return 0;
+}
+
+int sr_calib_absmax(const void *X_f16, int64_t T, int64_t K, int64_t ldx, float *absmax_io, void *stream)
+{
+    if (T < 0 || K <= 0 || ldx < K) return SR_ERR_SHAPE;
+    if (K % 8 != 0 || ldx % 8 != 0) return SR_ERR_ALIGN;
+    if (!absmax_io) return SR_ERR_NULL;
+    if (T == 0) return SR_OK;
+    if (!X_f16) return SR_ERR_NULL;
+    if (!aligned16(X_f16) || !aligned16(absmax_io)) return SR_ERR_ALIGN;
+    return dev(sr::launch_calib_absmax(X_f16, T, K, ldx, absmax_io, static_cast<hipStream_t>(stream)));
+}
+
+int sr_fold_smooth_rotate_quant(const void *W_f16, int64_t K, int64_t N, int64_t ldw,
+                                const float *act_absmax, float alpha, float w_clip,
+                                uint8_t *Wq, float *w_scale, float *inv_s,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (K <= 0 || N <= 0 || N % 16 != 0 || ldw < N) return SR_ERR_SHAPE;
+    if (!sr::hadamard_supported(K)) return SR_ERR_UNSUPPORTED_K;
+    if (!(alpha >= 0.f && alpha <= 1.f) || !(w_clip > 0.f && w_clip <= 1.f)) return SR_ERR_ARG;
+    if (!W_f16 || !Wq || !w_scale) return SR_ERR_NULL;
+    if (ldw % 8 != 0 || !aligned16(W_f16) || !aligned16(Wq) || !aligned16(w_scale) ||
+        (act_absmax && !aligned16(act_absmax)) || (inv_s && !aligned16(inv_s)))
+        return SR_ERR_ALIGN;
+    const FoldWs ws = fold_ws(K, N);
+    if (!workspace || workspace_bytes < ws.total || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return SR_ERR_WORKSPACE;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *base = static_cast<char *>(workspace);
+    void *Wt = base + ws.wt;
+    float *s = reinterpret_cast<float *>(base + ws.s);
+    float *wmax = reinterpret_cast<float *>(base + ws.wmax);
+
+    hipError_t e = hipSuccess;
+    if (act_absmax) e = sr::launch_row_absmax(W_f16, K, N, ldw, wmax, st);
+    if (e == hipSuccess) e = sr::launch_smooth_factors(act_absmax, wmax, K, alpha, s, inv_s, st);
+    if (e == hipSuccess) e = sr::launch_transpose_f16(W_f16, K, N, ldw, Wt, st);
+    // rows of Wt are the columns of W: rotate (s * column) and quantise per output channel;
+    // the 1/K of H H^T = K I goes into the scale only (codes do not depend on it).
+    if (e == hipSuccess)
+        e = sr::launch_fwht_quant(Wt, N, K, K, s, w_clip, 1.0f / (float)K, Wq, w_scale, st);
+    return dev(e);
+}
+
+int sr_fwht_quant_act(const void *X_f16, int64_t M, int64_t K, int64_t ldx, const float *inv_s, float clip,
+                      uint8_t *Xq, float *x_scale, void *stream)
+{
+    if (M < 0 || K <= 0 || ldx < K) return SR_ERR_SHAPE;
+    if (!sr::hadamard_supported(K)) return SR_ERR_UNSUPPORTED_K;
+    if (!(clip > 0.f && clip <= 1.f)) return SR_ERR_ARG;
+    if (M == 0) return SR_OK;
+    if (!X_f16 || !Xq || !x_scale) return SR_ERR_NULL;
+    if (ldx % 8 != 0 || !aligned16(X_f16) || !aligned16(Xq) || (inv_s && !aligned16(inv_s))) return SR_ERR_ALIGN;
+    return dev(sr::launch_fwht_quant(X_f16, M, K, ldx, inv_s, clip, 1.0f, Xq, x_scale,
+                                     static_cast<hipStream_t>(stream)));
+}
+
+int sr_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, const float *w_scale,
+                 int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_dtype,
+                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    if (M < 0 || N <= 0 || K <= 0 || N % 16 != 0 || ldy < N || M > INT32_MAX / 2 || N > INT32_MAX / 2)
+        return SR_ERR_SHAPE;
+    if (K % 64 != 0 || K >= 131072) return SR_ERR_UNSUPPORTED_K;
+    if (out_dtype != SR_F16 && out_dtype != SR_I32) return SR_ERR_ARG;
+    if (M == 0) return SR_OK;
+    if (!Xq || !Wq || !Y) return SR_ERR_NULL;
+    if (out_dtype == SR_F16 && (!x_scale || !w_scale)) return SR_ERR_NULL;
+    if (ldy % 8 != 0 || !aligned16(Xq) || !aligned16(Wq) || !aligned16(Y) ||
+        (out_dtype == SR_F16 && !aligned16(w_scale)))
+        return SR_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int i32 = out_dtype == SR_I32;
+    if (M <= 16) return dev(sr::launch_gemm_decode(Xq, x_scale, Wq, w_scale, M, N, K, Y, ldy, i32, st));
+    return dev(sr::launch_gemm_prefill(Xq, x_scale, Wq, w_scale, M, N, K, Y, ldy, i32, st));
+}
+
+}  // extern "C"

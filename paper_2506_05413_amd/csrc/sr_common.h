@@ -1,0 +1,52 @@
+// Internal declarations shared by the HIP translation units of libsmoothrot.
+// (Public interface: include/smoothrot.h.)
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace sr {
+
+// ---- Hadamard order helpers (host) ------------------------------------------------
+constexpr bool is_pow2(int64_t v) { return v >= 1 && (v & (v - 1)) == 0; }
+constexpr int64_t kMinK = 64, kMaxPow2K = 32768, kMaxKronK = 28672;
+
+inline bool hadamard_supported(int64_t K)
+{
+    if (K < kMinK) return false;
+    if (is_pow2(K)) return K <= kMaxPow2K;
+    return K % 28 == 0 && is_pow2(K / 28) && K % 64 == 0 && K <= kMaxKronK;
+}
+
+// ---- launchers (each returns hipGetLastError() of its launches) ------------------
+
+// y = (x * pre) H per row, per-row symmetric INT4, scale_out = delta * post_scale.
+hipError_t launch_fwht_quant(const void *X_f16, int64_t rows, int64_t K, int64_t ldx,
+                             const float *pre, float clip, float post_scale,
+                             uint8_t *Q, float *scale_out, hipStream_t st);
+
+hipError_t launch_calib_absmax(const void *X_f16, int64_t T, int64_t K, int64_t ldx,
+                               float *absmax_io, hipStream_t st);
+
+// w_rowmax[j] = max_n |W[j][n]|
+hipError_t launch_row_absmax(const void *W_f16, int64_t K, int64_t N, int64_t ldw,
+                             float *w_rowmax, hipStream_t st);
+
+// s / inv_s from calibration and weight maxima (act_absmax may be NULL: s = 1)
+hipError_t launch_smooth_factors(const float *act_absmax, const float *w_rowmax, int64_t K,
+                                 float alpha, float *s, float *inv_s, hipStream_t st);
+
+// Wt[n][k] = W[k][n] (fp16 bits moved unchanged)
+hipError_t launch_transpose_f16(const void *W_f16, int64_t K, int64_t N, int64_t ldw,
+                                void *Wt_f16, hipStream_t st);
+
+hipError_t launch_gemm_prefill(const uint8_t *Xq, const float *xs, const uint8_t *Wq, const float *ws,
+                               int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_i32,
+                               hipStream_t st);
+
+hipError_t launch_gemm_decode(const uint8_t *Xq, const float *xs, const uint8_t *Wq, const float *ws,
+                              int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_i32,
+                              hipStream_t st);
+
+}  // namespace sr

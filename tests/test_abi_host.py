@@ -1,0 +1,137 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2506_05413_amd as sr
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "smoothrot.h")
+
+A = 0x1000          # a fake, 16-byte aligned, non-NULL "device pointer" (never dereferenced on the host)
+WS = 0x10000        # 256-byte aligned fake workspace
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return re.findall(r"SR_API\s+[\w\s\*]+?\b(sr_\w+)\s*\(", text)
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert len(names) == 8 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
+    lib = ctypes.CDLL(sr.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(sr.binding._SIGNATURES)
+
+
+def test_status_strings():
+    for code in range(0, 8):
+        assert sr.sr_status_str(code) and sr.sr_status_str(code) != "unknown status"
+    assert sr.sr_status_str(99) == "unknown status"
+
+
+def test_hadamard_supported_orders():
+    ok = [64, 128, 512, 4096, 8192, 32768, 448, 896, 14336, 28672]
+    bad = [0, -4, 1, 16, 32, 65536, 100, 28, 56, 224, 57344, 12288, 4095, 3 * 4096]
+    assert all(sr.sr_hadamard_supported(k) for k in ok)
+    assert not any(sr.sr_hadamard_supported(k) for k in bad)
+
+
+def test_workspace_sizes():
+    assert sr.sr_fold_workspace_bytes(4096, 4096) >= 4096 * 4096 * 2 + 2 * 4096 * 4
+    assert sr.sr_fold_workspace_bytes(4096, 4096) % 256 == 0
+    assert sr.sr_fold_workspace_bytes(100, 64) == 0 and sr.sr_fold_workspace_bytes(4096, 10) == 0
+    assert sr.sr_gemm_workspace_bytes(2048, 4096, 4096) == 0
+
+
+def test_calib_absmax_rejects_bad_arguments():
+    f = sr.raw().sr_calib_absmax
+    assert f(A, -1, 512, 512, A, None) == sr.SR_ERR_SHAPE
+    assert f(A, 4, 512, 256, A, None) == sr.SR_ERR_SHAPE          # ldx < K
+    assert f(A, 4, 0, 0, A, None) == sr.SR_ERR_SHAPE
+    assert f(A, 4, 516, 520, A, None) == sr.SR_ERR_ALIGN          # K % 8
+    assert f(A, 4, 512, 516, A, None) == sr.SR_ERR_ALIGN          # ldx % 8
+    assert f(None, 4, 512, 512, A, None) == sr.SR_ERR_NULL
+    assert f(A, 4, 512, 512, None, None) == sr.SR_ERR_NULL
+    assert f(A + 2, 4, 512, 512, A, None) == sr.SR_ERR_ALIGN
+    assert f(None, 0, 512, 512, A, None) == sr.SR_OK               # T = 0: no-op
+
+
+def test_fold_rejects_bad_arguments():
+    f = sr.raw().sr_fold_smooth_rotate_quant
+    need = sr.sr_fold_workspace_bytes(512, 64)
+
+    def call(W=A, K=512, N=64, ldw=64, a=A, alpha=0.5, clip=1.0, Wq=A, ws=A, inv=A, wsp=WS, nbytes=need):
+        return f(W, K, N, ldw, a, alpha, clip, Wq, ws, inv, wsp, nbytes, None)
+
+    assert call(N=60) == sr.SR_ERR_SHAPE
+    assert call(N=0) == sr.SR_ERR_SHAPE
+    assert call(ldw=48) == sr.SR_ERR_SHAPE
+    assert call(K=500) == sr.SR_ERR_UNSUPPORTED_K
+    assert call(K=32) == sr.SR_ERR_UNSUPPORTED_K
+    assert call(alpha=1.5) == sr.SR_ERR_ARG
+    assert call(alpha=-0.1) == sr.SR_ERR_ARG
+    assert call(alpha=float("nan")) == sr.SR_ERR_ARG
+    assert call(clip=0.0) == sr.SR_ERR_ARG
+    assert call(clip=1.01) == sr.SR_ERR_ARG
+    assert call(W=None) == sr.SR_ERR_NULL
+    assert call(Wq=None) == sr.SR_ERR_NULL
+    assert call(ws=None) == sr.SR_ERR_NULL
+    assert call(W=A + 8) == sr.SR_ERR_ALIGN
+    assert call(ldw=68) == sr.SR_ERR_ALIGN
+    assert call(wsp=None) == sr.SR_ERR_WORKSPACE
+    assert call(nbytes=need - 1) == sr.SR_ERR_WORKSPACE
+    assert call(wsp=WS + 16) == sr.SR_ERR_WORKSPACE
+
+
+def test_fwht_quant_rejects_bad_arguments():
+    f = sr.raw().sr_fwht_quant_act
+
+    def call(X=A, M=4, K=4096, ldx=4096, inv=None, clip=0.9, Xq=A, xs=A):
+        return f(X, M, K, ldx, inv, clip, Xq, xs, None)
+
+    assert call(M=-1) == sr.SR_ERR_SHAPE
+    assert call(ldx=2048) == sr.SR_ERR_SHAPE
+    assert call(K=4000, ldx=4000) == sr.SR_ERR_UNSUPPORTED_K
+    assert call(K=65536, ldx=65536) == sr.SR_ERR_UNSUPPORTED_K
+    assert call(clip=0.0) == sr.SR_ERR_ARG
+    assert call(clip=2.0) == sr.SR_ERR_ARG
+    assert call(M=0, X=None, Xq=None, xs=None) == sr.SR_OK
+    assert call(X=None) == sr.SR_ERR_NULL
+    assert call(Xq=None) == sr.SR_ERR_NULL
+    assert call(xs=None) == sr.SR_ERR_NULL
+    assert call(ldx=4100) == sr.SR_ERR_ALIGN
+    assert call(X=A + 4) == sr.SR_ERR_ALIGN
+    assert call(inv=A + 4) == sr.SR_ERR_ALIGN
+
+
+def test_gemm_rejects_bad_arguments():
+    f = sr.raw().sr_w4a4_gemm
+
+    def call(Xq=A, xs=A, Wq=A, ws=A, M=32, N=64, K=512, Y=A, ldy=64, dt=sr.SR_F16):
+        return f(Xq, xs, Wq, ws, M, N, K, Y, ldy, dt, None, 0, None)
+
+    assert call(M=-1) == sr.SR_ERR_SHAPE
+    assert call(N=40) == sr.SR_ERR_SHAPE
+    assert call(ldy=32) == sr.SR_ERR_SHAPE
+    assert call(K=96) == sr.SR_ERR_UNSUPPORTED_K
+    assert call(K=131072) == sr.SR_ERR_UNSUPPORTED_K
+    assert call(dt=7) == sr.SR_ERR_ARG
+    assert call(M=0) == sr.SR_OK
+    assert call(Xq=None) == sr.SR_ERR_NULL
+    assert call(Y=None) == sr.SR_ERR_NULL
+    assert call(xs=None) == sr.SR_ERR_NULL
+    assert call(ldy=68) == sr.SR_ERR_ALIGN
+    assert call(Wq=A + 1) == sr.SR_ERR_ALIGN
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(ValueError):
+        sr.sr_fwht_quant_act(torch.zeros(2, 64, dtype=torch.float16), None)

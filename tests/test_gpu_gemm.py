@@ -1,0 +1,112 @@
+"""GPU parity: sr_w4a4_gemm.  Given identical codes the INT32 accumulators must be bit-exact;
+fp16 outputs within 1e-2 * rms of the oracle's dequantised product."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import smoothrot_oracle as o
+import workloads as wl
+from parity import check_output
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_gemm(sr, cx, cw, xs=None, ws=None, dtype=None, ldy=None):
+    dtype = sr.SR_I32 if dtype is None else dtype
+    Xq = torch.from_numpy(o.pack_int4(cx)).cuda()
+    Wq = torch.from_numpy(o.pack_int4(cw)).cuda()
+    xs_d = None if xs is None else torch.from_numpy(xs.astype(np.float32)).cuda()
+    ws_d = None if ws is None else torch.from_numpy(ws.astype(np.float32)).cuda()
+    Y = None
+    M, N = cx.shape[0], cw.shape[0]
+    if ldy is not None:
+        full = torch.full((M, ldy), -7, dtype=torch.int32 if dtype == sr.SR_I32 else torch.float16, device="cuda")
+        Y = full[:, :N]
+    out = sr.sr_w4a4_gemm(Xq, xs_d, Wq, ws_d, dtype, Y=Y)
+    torch.cuda.synchronize()
+    if ldy is not None:
+        assert bool((full[:, N:] == -7).all())                      # nothing written past N
+    return out.cpu().numpy()
+
+
+SHAPES = [(1, 16, 64), (4, 48, 128), (16, 512, 512), (16, 4096, 4096), (3, 64, 14336), (16, 256, 448),
+          (17, 16, 64), (33, 48, 192), (100, 144, 448), (128, 128, 128), (129, 272, 576), (300, 1040, 512),
+          (257, 400, 4096), (64, 128, 14336)]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_int32_accumulators_bit_exact(gpu, M, N, K):
+    print("case", M, N, K, flush=True)
+    cx, cw = wl.random_codes(M + K, M, K), wl.random_codes(N + 3 * K, N, K)
+    want = o.gemm_i32_c(cx, cw)
+    got = gpu_gemm(gpu, cx, cw)
+    assert got.dtype == np.int32 and np.array_equal(got.astype(np.int64), want)
+
+
+@pytest.mark.parametrize("M", [1, 16, 40])
+def test_extreme_codes_do_not_overflow(gpu, M):
+    """All codes -8 at the largest K the call accepts: acc = 64 K, the worst case of the accumulator."""
+    for K in (14336, 131008):
+        cx = np.full((M, K), -8, np.int8)
+        cw = np.full((32, K), -8, np.int8)
+        cw[1::2] = 7
+        got = gpu_gemm(gpu, cx, cw)
+        assert np.all(got[:, 0::2] == 64 * K) and np.all(got[:, 1::2] == -56 * K)
+
+
+@pytest.mark.parametrize("M,N,K", [(16, 512, 512), (4, 4096, 14336), (200, 528, 1024), (2048, 1024, 4096)])
+def test_fp16_epilogue(gpu, M, N, K):
+    rng = np.random.default_rng(M * N)
+    cx, cw = wl.random_codes(1, M, K), wl.random_codes(2, N, K)
+    xs = np.exp(rng.standard_normal(M) * 0.5).astype(np.float32) * 0.05   # per-token spread of the prefill config
+    ws = np.exp(rng.standard_normal(N) * 0.3).astype(np.float32) * 1e-3
+    want = o.dequant_out(o.gemm_i32_c(cx, cw), xs, ws)
+    got = gpu_gemm(gpu, cx, cw, xs, ws, gpu.SR_F16)
+    rel = check_output(got, want, "Y %dx%dx%d" % (M, N, K))
+    # fp16 rounding is the only error source: elementwise half-ulp bound as well
+    assert np.all(np.abs(got.astype(np.float64) - want) <= np.abs(want) * 2.0 ** -10 + 1e-7), rel
+
+
+def test_ragged_leading_dimension(gpu):
+    cx, cw = wl.random_codes(5, 50, 256), wl.random_codes(6, 80, 256)
+    want = o.gemm_i32(cx, cw)
+    assert np.array_equal(gpu_gemm(gpu, cx, cw, ldy=96), want)
+    assert np.array_equal(gpu_gemm(gpu, cx[:9], cw, ldy=96), want[:9])
+
+
+@pytest.mark.parametrize("N", [4096, 14336])
+def test_cfg2_full_size_properties_and_samples(gpu, N):
+    """Full prefill shape in the configuration the benchmark times.  The oracle computes a sample of
+    token rows one by one; every other output is covered by two exact identities that hold at any size:
+    sum_n acc[m][n] = cx[m] . (sum_n cw[n])   and   sum_m acc[m][n] = (sum_m cx[m]) . cw[n]."""
+    M, K = 2048, 4096
+    cx, cw = wl.random_codes(11, M, K), wl.random_codes(12 + N, N, K)
+    got = gpu_gemm(gpu, cx, cw).astype(np.int64)
+    rows = np.r_[0:8, 120:136, 1017:1033, 2040:2048]
+    assert np.array_equal(got[rows], o.gemm_i32_c(cx[rows], cw))
+    assert np.array_equal(got.sum(axis=1), cx.astype(np.int64) @ cw.astype(np.int64).sum(axis=0))
+    assert np.array_equal(got.sum(axis=0), cw.astype(np.int64) @ cx.astype(np.int64).sum(axis=0))
+
+
+def test_cfg3_full_size_properties_and_samples(gpu):
+    M, K, N = 2048, 14336, 4096
+    cx, cw = wl.random_codes(21, M, K), wl.random_codes(22, N, K)
+    got = gpu_gemm(gpu, cx, cw).astype(np.int64)
+    rows = np.r_[0:4, 1000:1008, 2044:2048]
+    assert np.array_equal(got[rows], o.gemm_i32_c(cx[rows], cw))
+    assert np.array_equal(got.sum(axis=1), cx.astype(np.int64) @ cw.astype(np.int64).sum(axis=0))
+    assert np.array_equal(got.sum(axis=0), cw.astype(np.int64) @ cx.astype(np.int64).sum(axis=0))
+
+
+@pytest.mark.parametrize("M", [1, 4, 16])
+@pytest.mark.parametrize("K,N", [(4096, 14336), (14336, 4096)])
+def test_cfg4_decode_shapes(gpu, M, K, N):
+    cx, cw = wl.random_codes(31 + M, M, K), wl.random_codes(32 + K, N, K)
+    assert np.array_equal(gpu_gemm(gpu, cx, cw).astype(np.int64), o.gemm_i32_c(cx, cw))
+
+
+def test_repeatable_bitwise(gpu):
+    cx, cw = wl.random_codes(41, 300, 1024), wl.random_codes(42, 512, 1024)
+    a = gpu_gemm(gpu, cx, cw)
+    for _ in range(3):
+        assert np.array_equal(a, gpu_gemm(gpu, cx, cw))
