@@ -166,7 +166,7 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import smoothrot_oracle as o
-        rows = 128
+        rows = M
         Xh = Xs[0][:rows].cpu().numpy()
         inv_h = inv_s.cpu().numpy()
         cws = {N: o.unpack_int4(Wq[N][0].cpu().numpy()) for N in NS}

@@ -73,8 +73,8 @@ SR_API int sr_hadamard_supported(int64_t K);
  * (0 if the shape is unsupported). */
 SR_API size_t sr_fold_workspace_bytes(int64_t K, int64_t N);
 
-/* Bytes of device scratch sr_w4a4_gemm needs (currently 0 for every shape: partial
- * sums are reduced on chip; the argument is kept so callers need not change). */
+/* Bytes of device scratch sr_w4a4_gemm needs (0 for every shape today: partial results stay
+ * on chip; callers should still query it and pass what it asks for). */
 SR_API size_t sr_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 /*
@@ -137,7 +137,9 @@ SR_API int sr_fwht_quant_act(const void *X_f16, int64_t M, int64_t K, int64_t ld
  *
  *   Xq [M, K/2], Wq [N, K/2] packed codes as produced by the two calls above
  *   Y   out, [M, N] with row stride ldy elements (fp16 or int32), ldy >= N
- *   workspace / workspace_bytes: see sr_gemm_workspace_bytes (may be NULL / 0 when that is 0)
+ *   workspace   at least sr_gemm_workspace_bytes(M, N, K) bytes, 256-byte aligned (may be NULL when
+ *               that is 0)
+ *   M * K and N * K must stay below 2^32 (rows are addressed with 32-bit byte offsets).
  *   K only needs to be a multiple of 64 here (no Hadamard involved), K < 131072.
  */
 SR_API int sr_w4a4_gemm(const uint8_t *Xq, const float *x_scale,

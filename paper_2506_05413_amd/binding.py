@@ -145,6 +145,10 @@ def sr_w4a4_gemm(Xq, x_scale, Wq, w_scale, out_dtype: int = SR_F16, Y=None, work
     if Y is None:
         Y = torch.empty((M, N), dtype=torch.float16 if out_dtype == SR_F16 else torch.int32, device=Xq.device)
     ldy = Y.stride(0) if M > 1 else N
+    if workspace is None:
+        need = sr_gemm_workspace_bytes(M, N, 2 * Kb)
+        if need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=Xq.device)
     _check(raw().sr_w4a4_gemm(_ptr(Xq), _ptr(x_scale), _ptr(Wq), _ptr(w_scale), M, N, 2 * Kb, _ptr(Y), ldy,
                               out_dtype, _ptr(workspace), 0 if workspace is None else workspace.numel(),
                               _stream()),

@@ -1,38 +1,328 @@
-// INT4 x INT4 GEMM, INT32 accumulation, dequantising epilogue -- compute-bound shapes.
+// INT4 x INT4 GEMM, INT32 accumulation, dequantising epilogue -- compute-bound shapes (M > 16).
 //
 //   acc[m][n] = sum_k cX[m][k] * cW[n][k],   Y = fp16(acc * dx[m] * dw[n])
 //
 // (Paper: the quantised forward pass of the linear layer; dequantisation per Eq. (1).)
 //
-// There is no 4-bit matrix instruction on gfx950, so the packed nibbles are widened
-// to int8 in registers and fed to v_mfma_i32_16x16x64_i8.  A nibble is sign-extended
-// for free by leaving it in the HIGH half of its byte:
+// gfx950 has no 4-bit matrix instruction, so the packed codes are widened to int8 in
+// registers and fed to the int8 MFMA.  A nibble is sign-extended for free by leaving it in
+// the HIGH half of its byte:
 //     lo = (w << 4) & 0xF0F0F0F0      (codes 0,2,4,6 of the dword, each x16)
 //     hi =  w       & 0xF0F0F0F0      (codes 1,3,5,7 of the dword, each x16)
-// Both operands are scaled by 16, so the accumulator holds 256 * acc exactly
-// (|256 * acc| <= 256 * 64 * K < 2^31 for K < 131072); the factor is removed by an
-// arithmetic shift (int32 output) or folded into the row scale (fp16 output).
-// A dot product does not care in which order k is visited, so X and W only have to
-// permute k identically -- which they do, because both are unpacked by the same code
-// from the same byte offsets.
+// Both operands carry the factor 16, so the accumulator holds 256 * acc exactly
+// (256 * 64 * K < 2^31 for K < 131072); the factor leaves by an arithmetic shift (int32
+// output) or inside the row scale (fp16 output).  A dot product does not care in which
+// order k is visited: X and W only have to permute k identically, and they do because both
+// are widened by the same three instructions from the same byte offsets.
 //
-// Tiling: 256 threads = 4 waves (2 x 2), block tile BM x BN, wave tile (BM/2) x (BN/2)
-// built from 16 x 16 MFMA tiles, K step of 128 codes (64 packed bytes per row).
-// Global -> registers -> LDS double buffering; LDS rows are 64 bytes with the 16-byte
-// chunk index XOR-swizzled by (row >> 2) & 3 so that both the 16-byte stores and the
-// 16-byte fragment loads are bank-conflict free.
+// What the main kernel is built around (all measured on MI355X):
+//  * v_mfma_i32_32x32x32_i8 (8 passes) lets vector-ALU instructions of the same wave issue
+//    underneath it, v_mfma_i32_16x16x64_i8 (4 passes) does not: with the 32x32x32 form the
+//    widening (4.5 ALU instructions per MFMA here) costs no MFMA time, and one wave per SIMD
+//    already saturates the matrix pipe.
+//  * L2 -> CU bandwidth is the scarce resource, not LDS or ALU: both operands stay packed
+//    (4 bit) all the way into LDS, and every global access fetches whole 128-byte lines
+//    (256 codes per row per stage) -- half-line fetches were re-fetched from L2 each time.
+//  * Global -> LDS copies use the LDS-DMA form of the global load (no staging registers),
+//    three stages of 256 codes; fragments for the next 64 codes are read from LDS into
+//    registers while the MFMAs of the current 64 run.  One barrier per stage.
+//  * LDS rows are XOR-swizzled in 16-byte chunks (applied on the global side of the DMA,
+//    which fills LDS linearly) so that every 16-byte fragment read is bank-conflict free.
+//  * MFMA operand roles are swapped (A = weight rows, B = token rows): a lane then owns 4
+//    consecutive output channels of one token per accumulator quad = one 8-byte store.
 //
-// MFMA operand roles are swapped (A operand = weight rows, B operand = token rows):
-// a lane then owns 4 consecutive output channels of one token, i.e. one 8-byte store.
+// K % 256 != 0 (and any K % 64 == 0) runs on a simpler register-staged kernel further down.
 #include "sr_common.h"
 
 #include <hip/hip_fp16.h>
+#include <stdlib.h>
+#include <type_traits>
 
 namespace sr {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+constexpr unsigned HM = 0xF0F0F0F0u;
+
+// ------------------------------------------------------------------------------------------
+// The DMA loads, their waits and the barrier are inline assembly on purpose: the compiler
+// would order every LDS read behind ALL outstanding LDS-DMA loads (vmcnt(0)) and put a full
+// fence on every barrier, which serialises the pipeline.  Hazards are handled by hand:
+// wait_vmcnt<n>() lets the n youngest loads stay in flight (loads complete in order), and the
+// "memory" clobbers keep the compiler from moving LDS accesses across these statements.
+// ------------------------------------------------------------------------------------------
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void barrier_nofence() { asm volatile("s_barrier" ::: "memory"); }
+
+// 64 lanes x 16 bytes: global (base + per-lane 32-bit offset) -> LDS bytes [lds, lds + 1024)
+__device__ __forceinline__ void dma16(const uint8_t *base, uint32_t lane_off, uint32_t lds)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(lane_off), "s"(base)
+                 : "memory", "m0");
+}
+
+// ------------------------------------------------------------------------------------------
+// Epilogue for 32 x 32 MFMA tiles: dequantise, then transpose the wave's WM x WN tile through LDS
+// so that global memory is written in whole rows of the tile (16 bytes per lane, WN * esize
+// contiguous bytes per token) instead of 8-byte pieces scattered over 32 rows per instruction.
+// In the accumulator layout a lane owns token (l & 31) and, per quad q, the four output channels
+// 8q + 4 (l >> 5) .. + 3 of each tile.  `stage` is this wave's private LDS area of
+// WM * (WN * esize + 16) bytes; the caller has made sure nobody still reads it.
+// ------------------------------------------------------------------------------------------
+template <int FM, int FN>
+__device__ __forceinline__ void store_wave_tile(const v16i (&acc)[FN][FM], uint8_t *stage, int lane, int m_base, int n_base,
+                                                int M, int N, const float *__restrict__ xs,
+                                                const float *__restrict__ ws, void *__restrict__ Yv, int64_t ldy,
+                                                int out_i32)
+{
+    constexpr int WM = FM * 32, WN = FN * 32;
+    const int fr = lane & 31, fg = lane >> 5;
+    if (out_i32) {
+        constexpr int RS = WN * 4 + 16;                      // padded row stride in bytes
+#pragma unroll
+        for (int j = 0; j < FM; ++j)
+#pragma unroll
+            for (int i = 0; i < FN; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<int4 *>(stage + (j * 32 + fr) * RS + (i * 32 + q * 8 + fg * 4) * 4) =
+                        make_int4(acc[i][j][4 * q] >> 8, acc[i][j][4 * q + 1] >> 8, acc[i][j][4 * q + 2] >> 8,
+                                  acc[i][j][4 * q + 3] >> 8);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        constexpr int CPR = WN * 4 / 16;                     // 16-byte chunks per row
+        constexpr int RPI = 64 / CPR;                        // rows per store instruction
+        const int c = lane % CPR, r0 = lane / CPR;
+#pragma unroll
+        for (int r = r0; r < WM; r += RPI) {
+            const int m = m_base + r, n = n_base + c * 4;
+            const int4 v = *reinterpret_cast<const int4 *>(stage + r * RS + c * 16);
+            if (m < M && n < N) *reinterpret_cast<int4 *>(static_cast<int32_t *>(Yv) + (int64_t)m * ldy + n) = v;
+        }
+    } else {
+        constexpr int RS = WN * 2 + 16;
+#pragma unroll
+        for (int j = 0; j < FM; ++j) {
+            const int m = m_base + j * 32 + fr;
+            const float sx = xs[m < M ? m : M - 1] * (1.f / 256.f);
+#pragma unroll
+            for (int i = 0; i < FN; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int nl = i * 32 + q * 8 + fg * 4;
+                    const int n = n_base + nl < N ? n_base + nl : N - 4;
+                    const float4 sw = *reinterpret_cast<const float4 *>(ws + n);
+                    union { __half h[4]; uint2 u; } o;
+                    o.h[0] = __float2half_rn((float)acc[i][j][4 * q] * sx * sw.x);
+                    o.h[1] = __float2half_rn((float)acc[i][j][4 * q + 1] * sx * sw.y);
+                    o.h[2] = __float2half_rn((float)acc[i][j][4 * q + 2] * sx * sw.z);
+                    o.h[3] = __float2half_rn((float)acc[i][j][4 * q + 3] * sx * sw.w);
+                    *reinterpret_cast<uint2 *>(stage + (j * 32 + fr) * RS + nl * 2) = o.u;
+                }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        constexpr int CPR = WN * 2 / 16;
+        constexpr int RPI = 64 / CPR;
+        const int c = lane % CPR, r0 = lane / CPR;
+#pragma unroll
+        for (int r = r0; r < WM; r += RPI) {
+            const int m = m_base + r, n = n_base + c * 8;
+            const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * RS + c * 16);
+            if (m < M && n < N) *reinterpret_cast<uint4 *>(static_cast<__half *>(Yv) + (int64_t)m * ldy + n) = v;
+        }
+    }
+}
+
+constexpr int ROWB = 128;  // packed bytes per row per stage (256 codes = one 128-byte line)
+constexpr int STAGES = 3;
+
+template <int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(WGM * WGN * 64) void gemm_w4a4_kernel(
+    const uint8_t *__restrict__ Xq, const float *__restrict__ xs, const uint8_t *__restrict__ Wq,
+    const float *__restrict__ ws, int M, int N, int K, void *__restrict__ Yv, int64_t ldy, int out_i32,
+    int tiles_m, int tiles_n)
+{
+    constexpr int NWAVE = WGM * WGN;
+    constexpr int WM = BM / WGM, WN = BN / WGN;      // wave tile
+    constexpr int FM = WM / 32, FN = WN / 32;        // 32 x 32 MFMA tiles per wave
+    constexpr int REGIONS = (BM + BN) / 8;           // 1 KB DMA regions (8 rows x 128 B) per stage
+    constexpr int RPW = REGIONS / NWAVE;             // DMA instructions per wave per stage
+    constexpr int X_BYTES = BM * ROWB, STAGE_BYTES = (BM + BN) * ROWB;
+    static_assert(REGIONS % NWAVE == 0 && NWAVE % 2 == 0 && WM % 32 == 0 && WN % 32 == 0 && RPW < 32, "tile");
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WGM, wn = wave / WGM;
+
+    // workgroups are dealt round-robin to the 8 XCDs: give each XCD a contiguous run of tiles
+    // (m fastest) so that neighbours share W panels and X panels in that XCD's L2
+    int bid = blockIdx.x;
+    const int total = tiles_m * tiles_n;
+    if ((total & 7) == 0) bid = (bid & 7) * (total >> 3) + (bid >> 3);
+    const int tm = bid % tiles_m, tn = bid / tiles_m;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int Kb = K >> 1;
+    const int ns = K / 256;                          // stages
+
+    // ---- DMA sources.  Region q = wave + NWAVE * i holds rows 8q .. 8q+7 of the combined
+    // [X rows ; W rows] tile.  Lane l lands in row l >> 3, physical chunk l & 7, and therefore
+    // fetches logical chunk (l & 7) ^ swz(row), swz(row) = (row >> 1) & 7 (q and wave have
+    // the same parity because NWAVE is even).
+    const int dchunk = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
+    constexpr int XI = BM / 8 / NWAVE;               // the first XI regions of a wave are X rows, the rest W rows
+    static_assert((BM / 8) % NWAVE == 0, "X regions must split evenly over the waves");
+    uint32_t goff[RPW];
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        const int trow = (wave + NWAVE * i) * 8 + (lane >> 3);
+        int r;
+        if (i < XI) { r = m0 + trow; r = r < M ? r : M - 1; }
+        else { r = n0 + trow - BM; r = r < N ? r : N - 1; }
+        goff[i] = (uint32_t)r * (uint32_t)Kb + (dchunk << 4);
+    }
+    const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
+    auto issue = [&](int s) {                        // stage s of K -> ring slot s % STAGES
+        const uint32_t sb = smem_base + (uint32_t)(s % STAGES) * STAGE_BYTES + wave * 1024;
+        const uint8_t *xsrc = Xq + (int64_t)s * ROWB;
+        const uint8_t *wsrc = Wq + (int64_t)s * ROWB;
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) dma16(i < XI ? xsrc : wsrc, goff[i], sb + NWAVE * i * 1024);
+    };
+
+    // ---- fragment addresses: lane (r = l & 31, g = l >> 5).  Sub-step p (64 codes) of a stage is
+    // chunks 2p, 2p+1 of the row; lane group g takes chunk 2p + g, whose two 8-byte halves are the
+    // operands of two consecutive MFMAs (K = 32 each).
+    const int fr = lane & 31, fg = lane >> 5;
+    const int fz = (fr >> 1) & 7;
+    const int xrow = (wm * WM + fr) * ROWB, wrow = X_BYTES + (wn * WN + fr) * ROWB;
+
+    struct Frag { uint4 x[FM]; uint4 w[FN]; };              // packed, as read from LDS
+    struct Ops { v4i x[FM][2]; v4i w[FN][2]; };              // widened MFMA operands of one sub-step
+    auto load_frags = [&](Frag &f, int slot, int p) {
+        const uint8_t *st = smem + slot * STAGE_BYTES + (((2 * p + fg) ^ fz) << 4);
+#pragma unroll
+        for (int j = 0; j < FM; ++j) f.x[j] = *reinterpret_cast<const uint4 *>(st + xrow + j * 32 * ROWB);
+#pragma unroll
+        for (int i = 0; i < FN; ++i) f.w[i] = *reinterpret_cast<const uint4 *>(st + wrow + i * 32 * ROWB);
+    };
+
+    v16i acc[FN][FM];
+#pragma unroll
+    for (int i = 0; i < FN; ++i)
+#pragma unroll
+        for (int j = 0; j < FM; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+
+    auto widen = [](const uint4 w, v4i &a0, v4i &a1) {
+        a0 = v4i{(int)((w.x << 4) & HM), (int)(w.x & HM), (int)((w.y << 4) & HM), (int)(w.y & HM)};
+        a1 = v4i{(int)((w.z << 4) & HM), (int)(w.z & HM), (int)((w.w << 4) & HM), (int)(w.w & HM)};
+    };
+    auto widen_all = [&](const Frag &f, Ops &o) {
+#pragma unroll
+        for (int j = 0; j < FM; ++j) widen(f.x[j], o.x[j][0], o.x[j][1]);
+#pragma unroll
+        for (int i = 0; i < FN; ++i) widen(f.w[i], o.w[i][0], o.w[i][1]);
+    };
+    auto mfmas = [&](const Ops &o) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int i = 0; i < FN; ++i)
+#pragma unroll
+                for (int j = 0; j < FM; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(o.w[i][h], o.x[j][h], acc[i][j], 0, 0, 0);
+    };
+    constexpr int NMFMA = 2 * FN * FM;                       // MFMAs per sub-step
+    constexpr int NWID = 12 * (FM + FN);                     // widening ALU instructions per sub-step
+    constexpr int PER = (NWID + NMFMA - 1) / NMFMA;
+    // One sub-step t, three things in flight (a register-level software pipeline):
+    //   LDS reads of the packed fragments of sub-step t+2          -> rd
+    //   widening of the fragments of sub-step t+1 (read last time) -> nxt, underneath ...
+    //   ... the MFMAs of sub-step t (the 8-pass MFMA leaves the ALU port free)
+    // The scheduling hints pin that interleaving: reads first, then PER ALU instructions after each MFMA.
+    auto sub = [&](auto do_read, auto do_widen, const Ops &cur, Ops &nxt, const Frag &wd, Frag &rd, int slot, int p) {
+        __builtin_amdgcn_sched_barrier(0);               // each sub-step is scheduled on its own
+        if constexpr (decltype(do_read)::value) load_frags(rd, slot, p);
+        mfmas(cur);
+        if constexpr (decltype(do_widen)::value) widen_all(wd, nxt);
+        if constexpr (decltype(do_read)::value) __builtin_amdgcn_sched_group_barrier(0x100, FM + FN, 0);
+#pragma unroll
+        for (int k = 0; k < NMFMA; ++k) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if constexpr (decltype(do_widen)::value) __builtin_amdgcn_sched_group_barrier(0x002, PER, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    constexpr std::true_type yes{};
+    constexpr std::false_type no{};
+
+    // ---- prologue: two stages in flight; operands of sub-step 0 and fragments of sub-step 1 in registers
+    issue(0);
+    issue(ns > 1 ? 1 : 0);
+    wait_vmcnt<RPW>();
+    barrier_nofence();
+    Ops o0, o1;
+    Frag fa, fb;                                     // fragments of even / odd sub-steps
+    load_frags(fa, 0, 0);
+    load_frags(fb, 0, 1);
+    widen_all(fa, o0);
+
+    // Every stage runs the same branch-free body.  Past the end of K the pipeline keeps reading (stale,
+    // in-bounds) LDS and re-fetching the last stage; those fragments are widened but never multiplied.
+    int slot = 0;
+    for (int s = 0; s < ns; ++s) {
+        const int nslot = slot == STAGES - 1 ? 0 : slot + 1;
+        sub(yes, yes, o0, o1, fb, fa, slot, 2);
+        sub(yes, yes, o1, o0, fa, fb, slot, 3);
+        // stage s+1 (issued one stage ago) must have landed for every wave; after the barrier every wave is
+        // also done with stage s-1, whose slot takes stage s+2
+        wait_vmcnt<0>();
+        barrier_nofence();
+        issue(s + 2 < ns ? s + 2 : ns - 1);
+        sub(yes, yes, o0, o1, fb, fa, nslot, 0);
+        sub(yes, yes, o1, o0, fa, fb, nslot, 1);
+        slot = nslot;
+    }
+    wait_vmcnt<0>();                                 // no LDS-DMA write may outlive the workgroup
+
+    // ---- epilogue: every wave transposes its tile through its own part of the (now idle) LDS ring ----
+    barrier_nofence();                               // all waves are done reading fragments
+    static_assert(NWAVE * WM * (WN * 4 + 16) <= STAGES * STAGE_BYTES, "epilogue staging must fit the ring");
+    store_wave_tile<FM, FN>(acc, smem + wave * (WM * (WN * 4 + 16)), lane, m0 + wm * WM, n0 + wn * WN, M, N, xs, ws,
+                            Yv, ldy, out_i32);
+}
+
+template <int BM, int BN, int WGM, int WGN>
+hipError_t launch_tile(const uint8_t *Xq, const float *xs, const uint8_t *Wq, const float *ws, int64_t M, int64_t N,
+                       int64_t K, void *Y, int64_t ldy, int out_i32, hipStream_t st)
+{
+    auto kern = gemm_w4a4_kernel<BM, BN, WGM, WGN>;
+    constexpr int lds = STAGES * (BM + BN) * ROWB;
+    static_assert(lds <= 160 * 1024, "LDS");
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+    }
+    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(WGM * WGN * 64), lds, st, Xq, xs, Wq, ws,
+                       (int)M, (int)N, (int)K, Y, ldy, out_i32, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Generic kernel (any K % 64 == 0): 128 x 128 tile, K step of 128 codes, global -> registers
+// -> LDS double buffering, v_mfma_i32_16x16x64_i8; a K tail of 64 codes is zero-filled.
+// ------------------------------------------------------------------------------------------
 constexpr int KB = 64;   // packed bytes of one K step per row (128 codes)
 
 __device__ __forceinline__ int swz_off(int row, int chunk)
@@ -42,15 +332,14 @@ __device__ __forceinline__ int swz_off(int row, int chunk)
 
 __device__ __forceinline__ void unpack16(const uint4 w, v4i &a0, v4i &a1)
 {
-    constexpr unsigned HM = 0xF0F0F0F0u;
-    a0[0] = (int)((w.x << 4) & HM); a0[1] = (int)(w.x & HM);
+        a0[0] = (int)((w.x << 4) & HM); a0[1] = (int)(w.x & HM);
     a0[2] = (int)((w.y << 4) & HM); a0[3] = (int)(w.y & HM);
     a1[0] = (int)((w.z << 4) & HM); a1[1] = (int)(w.z & HM);
     a1[2] = (int)((w.w << 4) & HM); a1[3] = (int)(w.w & HM);
 }
 
 template <int BM, int BN>
-__global__ __launch_bounds__(256) void gemm_w4a4_kernel(const uint8_t *__restrict__ Xq, const float *__restrict__ xs,
+__global__ __launch_bounds__(256) void gemm_w4a4_generic_kernel(const uint8_t *__restrict__ Xq, const float *__restrict__ xs,
                                                         const uint8_t *__restrict__ Wq, const float *__restrict__ ws,
                                                         int M, int N, int K, void *__restrict__ Yv, int64_t ldy,
                                                         int out_i32, int tiles_m, int tiles_n)
@@ -183,17 +472,32 @@ __global__ __launch_bounds__(256) void gemm_w4a4_kernel(const uint8_t *__restric
     }
 }
 
+
 }  // namespace
 
 hipError_t launch_gemm_prefill(const uint8_t *Xq, const float *xs, const uint8_t *Wq, const float *ws,
                                int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_i32,
                                hipStream_t st)
 {
-    constexpr int BM = 128, BN = 128;
-    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
-    hipLaunchKernelGGL((gemm_w4a4_kernel<BM, BN>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, st,
-                       Xq, xs, Wq, ws, (int)M, (int)N, (int)K, Y, ldy, out_i32, tiles_m, tiles_n);
-    return hipGetLastError();
+    // SMOOTHROT_GEMM_TILE selects a tile configuration by number (tuning aid); unset = heuristic.
+    int variant = 0;
+    if (const char *env = getenv("SMOOTHROT_GEMM_TILE")) variant = atoi(env);
+    if (K % 256 != 0 || variant == 9) {
+        constexpr int BM = 128, BN = 128;
+        const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
+        hipLaunchKernelGGL((gemm_w4a4_generic_kernel<BM, BN>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, st,
+                           Xq, xs, Wq, ws, (int)M, (int)N, (int)K, Y, ldy, out_i32, tiles_m, tiles_n);
+        return hipGetLastError();
+    }
+    switch (variant) {
+        case 1: return launch_tile<256, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+        case 2: return launch_tile<128, 256, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+        case 3: return launch_tile<128, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+        case 5: return launch_tile<256, 128, 4, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+        default: break;
+    }
+    if (M <= 128) return launch_tile<128, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+    return launch_tile<256, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
 }
 
 }  // namespace sr

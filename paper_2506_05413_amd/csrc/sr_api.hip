@@ -52,7 +52,7 @@ size_t sr_fold_workspace_bytes(int64_t K, int64_t N)
 size_t sr_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
     (void)M; (void)N; (void)K;
-    return 0;
+    return 0;                                        // both kernels keep their partial results on chip
 }
 
 int sr_calib_absmax(const void *X_f16, int64_t T, int64_t K, int64_t ldx, float *absmax_io, void *stream)
@@ -117,8 +117,9 @@ int sr_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, con
                  void *workspace, size_t workspace_bytes, void *stream)
 {
     (void)workspace; (void)workspace_bytes;
-    if (M < 0 || N <= 0 || K <= 0 || N % 16 != 0 || ldy < N || M > INT32_MAX / 2 || N > INT32_MAX / 2)
-        return SR_ERR_SHAPE;
+    if (M < 0 || N <= 0 || K <= 0 || N % 16 != 0 || ldy < N) return SR_ERR_SHAPE;
+    // kernels index rows with 32-bit byte offsets
+    if ((double)M * (double)K >= 4294967296.0 || (double)N * (double)K >= 4294967296.0) return SR_ERR_SHAPE;
     if (K % 64 != 0 || K >= 131072) return SR_ERR_UNSUPPORTED_K;
     if (out_dtype != SR_F16 && out_dtype != SR_I32) return SR_ERR_ARG;
     if (M == 0) return SR_OK;

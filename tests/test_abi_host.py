@@ -114,8 +114,8 @@ def test_fwht_quant_rejects_bad_arguments():
 def test_gemm_rejects_bad_arguments():
     f = sr.raw().sr_w4a4_gemm
 
-    def call(Xq=A, xs=A, Wq=A, ws=A, M=32, N=64, K=512, Y=A, ldy=64, dt=sr.SR_F16):
-        return f(Xq, xs, Wq, ws, M, N, K, Y, ldy, dt, None, 0, None)
+    def call(Xq=A, xs=A, Wq=A, ws=A, M=32, N=64, K=512, Y=A, ldy=64, dt=sr.SR_F16, wsp=WS, nbytes=32 * 512):
+        return f(Xq, xs, Wq, ws, M, N, K, Y, ldy, dt, wsp, nbytes, None)
 
     assert call(M=-1) == sr.SR_ERR_SHAPE
     assert call(N=40) == sr.SR_ERR_SHAPE
@@ -129,6 +129,7 @@ def test_gemm_rejects_bad_arguments():
     assert call(xs=None) == sr.SR_ERR_NULL
     assert call(ldy=68) == sr.SR_ERR_ALIGN
     assert call(Wq=A + 1) == sr.SR_ERR_ALIGN
+    assert call(M=70000, N=16, K=65536, ldy=16) == sr.SR_ERR_SHAPE         # 32-bit row offsets
 
 
 def test_binding_refuses_host_tensors():
