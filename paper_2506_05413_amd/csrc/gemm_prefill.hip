@@ -24,8 +24,10 @@
 //    (4 bit) all the way into LDS, and every global access fetches whole 128-byte lines
 //    (256 codes per row per stage) -- half-line fetches were re-fetched from L2 each time.
 //  * Global -> LDS copies use the LDS-DMA form of the global load (no staging registers),
-//    three stages of 256 codes; fragments for the next 64 codes are read from LDS into
-//    registers while the MFMAs of the current 64 run.  One barrier per stage.
+//    a ring of two stages of 256 codes; per 64 codes a register-level software pipeline
+//    (LDS reads for t+2, widening for t+1, MFMAs for t).  One barrier per stage.
+//  * The epilogue transposes each wave tile through the idle LDS ring and stores whole rows:
+//    8-byte stores scattered over 32 rows per instruction cost 14 us per tile, this costs ~5.
 //  * LDS rows are XOR-swizzled in 16-byte chunks (applied on the global side of the DMA,
 //    which fills LDS linearly) so that every 16-byte fragment read is bank-conflict free.
 //  * MFMA operand roles are swapped (A = weight rows, B = token rows): a lane then owns 4
@@ -74,7 +76,7 @@ __device__ __forceinline__ void dma16(const uint8_t *base, uint32_t lane_off, ui
 // contiguous bytes per token) instead of 8-byte pieces scattered over 32 rows per instruction.
 // In the accumulator layout a lane owns token (l & 31) and, per quad q, the four output channels
 // 8q + 4 (l >> 5) .. + 3 of each tile.  `stage` is this wave's private LDS area of
-// WM * (WN * esize + 16) bytes; the caller has made sure nobody still reads it.
+// WM * (WN * 2 + 16) bytes; the caller has made sure nobody still reads it.
 // ------------------------------------------------------------------------------------------
 template <int FM, int FN>
 __device__ __forceinline__ void store_wave_tile(const v16i (&acc)[FN][FM], uint8_t *stage, int lane, int m_base, int n_base,
@@ -84,27 +86,19 @@ __device__ __forceinline__ void store_wave_tile(const v16i (&acc)[FN][FM], uint8
 {
     constexpr int WM = FM * 32, WN = FN * 32;
     const int fr = lane & 31, fg = lane >> 5;
-    if (out_i32) {
-        constexpr int RS = WN * 4 + 16;                      // padded row stride in bytes
+    if (out_i32) {                                          // raw accumulators: a debugging / test output, stored directly
 #pragma unroll
         for (int j = 0; j < FM; ++j)
 #pragma unroll
             for (int i = 0; i < FN; ++i)
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    *reinterpret_cast<int4 *>(stage + (j * 32 + fr) * RS + (i * 32 + q * 8 + fg * 4) * 4) =
-                        make_int4(acc[i][j][4 * q] >> 8, acc[i][j][4 * q + 1] >> 8, acc[i][j][4 * q + 2] >> 8,
-                                  acc[i][j][4 * q + 3] >> 8);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        constexpr int CPR = WN * 4 / 16;                     // 16-byte chunks per row
-        constexpr int RPI = 64 / CPR;                        // rows per store instruction
-        const int c = lane % CPR, r0 = lane / CPR;
-#pragma unroll
-        for (int r = r0; r < WM; r += RPI) {
-            const int m = m_base + r, n = n_base + c * 4;
-            const int4 v = *reinterpret_cast<const int4 *>(stage + r * RS + c * 16);
-            if (m < M && n < N) *reinterpret_cast<int4 *>(static_cast<int32_t *>(Yv) + (int64_t)m * ldy + n) = v;
-        }
+                for (int q = 0; q < 4; ++q) {
+                    const int m = m_base + j * 32 + fr, n = n_base + i * 32 + q * 8 + fg * 4;
+                    if (m < M && n < N)
+                        *reinterpret_cast<int4 *>(static_cast<int32_t *>(Yv) + (int64_t)m * ldy + n) =
+                            make_int4(acc[i][j][4 * q] >> 8, acc[i][j][4 * q + 1] >> 8, acc[i][j][4 * q + 2] >> 8,
+                                      acc[i][j][4 * q + 3] >> 8);
+                }
     } else {
         constexpr int RS = WN * 2 + 16;
 #pragma unroll
@@ -134,15 +128,14 @@ __device__ __forceinline__ void store_wave_tile(const v16i (&acc)[FN][FM], uint8
         for (int r = r0; r < WM; r += RPI) {
             const int m = m_base + r, n = n_base + c * 8;
             const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * RS + c * 16);
-            if (m < M && n < N) *reinterpret_cast<uint4 *>(static_cast<__half *>(Yv) + (int64_t)m * ldy + n) = v;
+            if (lane < RPI * CPR && m < M && n < N) *reinterpret_cast<uint4 *>(static_cast<__half *>(Yv) + (int64_t)m * ldy + n) = v;
         }
     }
 }
 
 constexpr int ROWB = 128;  // packed bytes per row per stage (256 codes = one 128-byte line)
-constexpr int STAGES = 3;
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int STAGES>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_w4a4_kernel(
     const uint8_t *__restrict__ Xq, const float *__restrict__ xs, const uint8_t *__restrict__ Wq,
     const float *__restrict__ ws, int M, int N, int K, void *__restrict__ Yv, int64_t ldy, int out_i32,
@@ -265,27 +258,27 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_w4a4_kernel(
     constexpr std::true_type yes{};
     constexpr std::false_type no{};
 
+    Ops o0, o1;
+    Frag fa, fb;                                     // fragments of even / odd sub-steps
+    int slot = 0;
+    // Every stage runs the same branch-free body.  Past the end of K the pipeline keeps reading (stale,
+    // in-bounds) LDS and re-fetching the last stage; those fragments are widened but never multiplied.
     // ---- prologue: two stages in flight; operands of sub-step 0 and fragments of sub-step 1 in registers
     issue(0);
     issue(ns > 1 ? 1 : 0);
     wait_vmcnt<RPW>();
     barrier_nofence();
-    Ops o0, o1;
-    Frag fa, fb;                                     // fragments of even / odd sub-steps
     load_frags(fa, 0, 0);
     load_frags(fb, 0, 1);
     widen_all(fa, o0);
-
-    // Every stage runs the same branch-free body.  Past the end of K the pipeline keeps reading (stale,
-    // in-bounds) LDS and re-fetching the last stage; those fragments are widened but never multiplied.
-    int slot = 0;
     for (int s = 0; s < ns; ++s) {
         const int nslot = slot == STAGES - 1 ? 0 : slot + 1;
         sub(yes, yes, o0, o1, fb, fa, slot, 2);
         sub(yes, yes, o1, o0, fa, fb, slot, 3);
-        // stage s+1 (issued one stage ago) must have landed for every wave; after the barrier every wave is
-        // also done with stage s-1, whose slot takes stage s+2
-        wait_vmcnt<0>();
+        // stage s+1 (issued one stage ago) must have landed for every wave, and every wave's LDS reads of
+        // stage s (the last ones were issued a sub-step ago) must have returned: its slot takes stage s+2
+        // when the ring has two slots (the slot of stage s-1 when it has three)
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         barrier_nofence();
         issue(s + 2 < ns ? s + 2 : ns - 1);
         sub(yes, yes, o0, o1, fb, fa, nslot, 0);
@@ -296,16 +289,16 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_w4a4_kernel(
 
     // ---- epilogue: every wave transposes its tile through its own part of the (now idle) LDS ring ----
     barrier_nofence();                               // all waves are done reading fragments
-    static_assert(NWAVE * WM * (WN * 4 + 16) <= STAGES * STAGE_BYTES, "epilogue staging must fit the ring");
-    store_wave_tile<FM, FN>(acc, smem + wave * (WM * (WN * 4 + 16)), lane, m0 + wm * WM, n0 + wn * WN, M, N, xs, ws,
+    static_assert(NWAVE * WM * (WN * 2 + 16) <= STAGES * STAGE_BYTES, "epilogue staging must fit the ring");
+    store_wave_tile<FM, FN>(acc, smem + wave * (WM * (WN * 2 + 16)), lane, m0 + wm * WM, n0 + wn * WN, M, N, xs, ws,
                             Yv, ldy, out_i32);
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int STAGES = 2>
 hipError_t launch_tile(const uint8_t *Xq, const float *xs, const uint8_t *Wq, const float *ws, int64_t M, int64_t N,
                        int64_t K, void *Y, int64_t ldy, int out_i32, hipStream_t st)
 {
-    auto kern = gemm_w4a4_kernel<BM, BN, WGM, WGN>;
+    auto kern = gemm_w4a4_kernel<BM, BN, WGM, WGN, STAGES>;
     constexpr int lds = STAGES * (BM + BN) * ROWB;
     static_assert(lds <= 160 * 1024, "LDS");
     if (lds > 48 * 1024) {
@@ -494,10 +487,18 @@ hipError_t launch_gemm_prefill(const uint8_t *Xq, const float *xs, const uint8_t
         case 2: return launch_tile<128, 256, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
         case 3: return launch_tile<128, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
         case 5: return launch_tile<256, 128, 4, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+        case 6: return launch_tile<256, 128, 2, 2, 3>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
         default: break;
     }
-    if (M <= 128) return launch_tile<128, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-    return launch_tile<256, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+    // One 144 KB workgroup owns a CU, so a launch takes ceil(tiles / 256) rounds of one tile time each
+    // (tile time ~ BM * BN).  Pick the tile shape with the cheapest schedule; ties go to the larger tile.
+    auto cost = [&](int64_t bm, int64_t bn) {
+        const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+        return ((tiles + 255) / 256) * bm * bn;
+    };
+    const int64_t c256 = cost(256, 128), c128 = cost(128, 128);
+    if (c256 <= c128) return launch_tile<256, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+    return launch_tile<128, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
 }
 
 }  // namespace sr

@@ -29,7 +29,7 @@ def gpu_gemm(sr, cx, cw, xs=None, ws=None, dtype=None, ldy=None):
     return out.cpu().numpy()
 
 
-SHAPES = [(1, 16, 64), (4, 48, 128), (16, 512, 512), (16, 4096, 4096), (3, 64, 14336), (16, 256, 448),
+SHAPES = [(1, 16, 64), (4, 48, 128), (2, 32, 448), (5, 80, 4096), (8, 4096, 4096), (7, 16, 14336), (9, 32, 576), (16, 512, 512), (16, 4096, 4096), (3, 64, 14336), (16, 256, 448),
           (17, 16, 64), (33, 48, 192), (100, 144, 448), (128, 128, 128), (129, 272, 576), (300, 1040, 512),
           (257, 400, 4096), (64, 128, 14336)]
 
@@ -54,7 +54,7 @@ def test_extreme_codes_do_not_overflow(gpu, M):
         assert np.all(got[:, 0::2] == 64 * K) and np.all(got[:, 1::2] == -56 * K)
 
 
-@pytest.mark.parametrize("M,N,K", [(16, 512, 512), (4, 4096, 14336), (200, 528, 1024), (2048, 1024, 4096)])
+@pytest.mark.parametrize("M,N,K", [(16, 512, 512), (4, 4096, 14336), (1, 14336, 4096), (200, 528, 1024), (2048, 1024, 4096)])
 def test_fp16_epilogue(gpu, M, N, K):
     rng = np.random.default_rng(M * N)
     cx, cw = wl.random_codes(1, M, K), wl.random_codes(2, N, K)
@@ -98,7 +98,7 @@ def test_cfg3_full_size_properties_and_samples(gpu):
     assert np.array_equal(got.sum(axis=0), cw.astype(np.int64) @ cx.astype(np.int64).sum(axis=0))
 
 
-@pytest.mark.parametrize("M", [1, 4, 16])
+@pytest.mark.parametrize("M", [1, 2, 4, 8, 16])
 @pytest.mark.parametrize("K,N", [(4096, 14336), (14336, 4096)])
 def test_cfg4_decode_shapes(gpu, M, K, N):
     cx, cw = wl.random_codes(31 + M, M, K), wl.random_codes(32 + K, N, K)
