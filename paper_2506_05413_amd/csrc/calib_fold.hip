@@ -26,43 +26,44 @@ __device__ __forceinline__ float half_bits_to_float(unsigned short b)
 
 // Column-wise max |x| over a slab of rows.  |fp16| bit patterns of finite values order
 // like unsigned integers, so the running maximum is kept as packed u16 and is exact.
-// Block = 64 column groups (8 columns each) x 4 row lanes.
+// Block = 8 column groups (8 columns each: one 128-byte line per row) x 32 row lanes.  Narrow,
+// tall blocks keep the number of atomics per channel small: the atomics on the K shared
+// addresses, not the reads, were what bounded a wide-block version.
 __global__ __launch_bounds__(256) void calib_absmax_kernel(const __half *__restrict__ X, int64_t T, int K,
                                                             int64_t ldx, float *__restrict__ absmax,
                                                             int64_t rows_per_block)
 {
-    __shared__ us8 part[4][64];
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    const int col = (blockIdx.x * 64 + tx) * 8;
+    __shared__ us8 part[32][8];
+    const int tx = threadIdx.x & 7, ty = threadIdx.x >> 3;
+    const int col = (blockIdx.x * 8 + tx) * 8;
     const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
     const int64_t r1 = (r0 + rows_per_block < T) ? r0 + rows_per_block : T;
     us8 acc = {0, 0, 0, 0, 0, 0, 0, 0};
     if (col < K) {
         const __half *p = X + col;
         int64_t r = r0 + ty;
-        for (; r + 12 < r1; r += 16) {
-            const uint4 a = *reinterpret_cast<const uint4 *>(p + r * ldx);
-            const uint4 b = *reinterpret_cast<const uint4 *>(p + (r + 4) * ldx);
-            const uint4 c = *reinterpret_cast<const uint4 *>(p + (r + 8) * ldx);
-            const uint4 d = *reinterpret_cast<const uint4 *>(p + (r + 12) * ldx);
-            acc = __builtin_elementwise_max(acc, abs_bits(a));
-            acc = __builtin_elementwise_max(acc, abs_bits(b));
-            acc = __builtin_elementwise_max(acc, abs_bits(c));
-            acc = __builtin_elementwise_max(acc, abs_bits(d));
+        for (; r + 224 < r1; r += 256) {                 // 8 loads in flight
+            uint4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const uint4 *>(p + (r + 32 * u) * ldx);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc = __builtin_elementwise_max(acc, abs_bits(v[u]));
         }
-        for (; r < r1; r += 4)
+        for (; r < r1; r += 32)
             acc = __builtin_elementwise_max(acc, abs_bits(*reinterpret_cast<const uint4 *>(p + r * ldx)));
     }
     part[ty][tx] = acc;
     __syncthreads();
-    if (ty == 0 && col < K) {
-        acc = __builtin_elementwise_max(__builtin_elementwise_max(part[0][tx], part[1][tx]),
-                                        __builtin_elementwise_max(part[2][tx], part[3][tx]));
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float f = half_bits_to_float(acc[e]);
+    for (int s = 16; s >= 1; s >>= 1) {
+        if (ty < s) part[ty][tx] = __builtin_elementwise_max(part[ty][tx], part[ty + s][tx]);
+        __syncthreads();
+    }
+    if (threadIdx.x < 64) {                              // one channel per thread
+        const int c = (blockIdx.x * 8) * 8 + threadIdx.x;
+        if (c < K) {
+            const float f = half_bits_to_float(part[0][threadIdx.x >> 3][threadIdx.x & 7]);
             // non-negative floats order like their bit patterns
-            atomicMax(reinterpret_cast<unsigned int *>(absmax + col + e), __float_as_uint(f));
+            atomicMax(reinterpret_cast<unsigned int *>(absmax + c), __float_as_uint(f));
         }
     }
 }
@@ -131,13 +132,12 @@ __global__ __launch_bounds__(256) void transpose_f16_kernel(const unsigned short
 hipError_t launch_calib_absmax(const void *X, int64_t T, int64_t K, int64_t ldx, float *absmax_io,
                                hipStream_t st)
 {
-    const unsigned gx = (unsigned)((K + 511) / 512);
-    int64_t gy = (T + 63) / 64;
-    const int64_t gy_cap = 4096 / gx > 0 ? 4096 / gx : 1;
-    if (gy > gy_cap) gy = gy_cap;
-    if (gy < 1) gy = 1;
+    const unsigned gx = (unsigned)((K + 63) / 64);
+    // about 1024 workgroups, at least 32 rows each
+    int64_t gy = 1024 / gx > 0 ? 1024 / gx : 1;
+    if (gy > (T + 31) / 32) gy = (T + 31) / 32;
     int64_t rpb = (T + gy - 1) / gy;
-    rpb = (rpb + 3) / 4 * 4;
+    rpb = (rpb + 31) / 32 * 32;
     gy = (T + rpb - 1) / rpb;
     hipLaunchKernelGGL(calib_absmax_kernel, dim3(gx, (unsigned)gy), dim3(256), 0, st,
                        static_cast<const __half *>(X), T, (int)K, ldx, absmax_io, rpb);
