@@ -183,6 +183,30 @@ def main():
             extra["decode_M%d_4096x14336" % Md] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
                                                     "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
         del copies
+        # down-projection shape (config 3): K = 14336 = 28 * 512 -> N = 4096; rotation-only fold (s = 1)
+        K3, N3 = 14336, 4096
+        X3 = [torch.from_numpy(wl.cfg3_X(seed=2 + 10 * s)).to(dev) for s in range(4)]
+        W3 = torch.from_numpy(wl.cfg3_W()).to(dev)
+        Wq3, ws3, _ = sr.sr_fold_smooth_rotate_quant(W3, None, ALPHA, 1.0)
+        del W3
+        Xq3 = torch.empty((M, K3 // 2), dtype=torch.uint8, device=dev)
+        xs3 = torch.empty(M, dtype=torch.float32, device=dev)
+        Y3 = torch.empty((M, N3), dtype=torch.float16, device=dev)
+        t = graph_time(lambda i: sr.sr_fwht_quant_act(X3[i % 4], None, CLIP, Xq3, xs3), 32)
+        b = M * K3 * 2.5 + M * 4
+        extra["fwht_quant_K14336"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
+                                      "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+        t = graph_time(lambda i: sr.sr_w4a4_gemm(Xq3, xs3, Wq3, ws3, sr.SR_F16, Y3), 32)
+        extra["gemm_K14336_N4096"] = {"us": round(t * 1e6, 2), "TOPS": round(2.0 * M * N3 * K3 / t / 1e12, 1),
+                                      "frac_mfma": round(2.0 * M * N3 * K3 / t / 1e12 / PEAK_INT8_TOPS, 4)}
+        copies = [Wq3.clone() for _ in range(20)]
+        xq_d, xs_d = sr.sr_fwht_quant_act(X3[0][:1].contiguous(), None, CLIP)
+        Yd = torch.empty((1, N3), dtype=torch.float16, device=dev)
+        t = graph_time(lambda i: sr.sr_w4a4_gemm(xq_d, xs_d, copies[i % 20], ws3, sr.SR_F16, Yd), 100)
+        b = N3 * K3 / 2 + K3 / 2 + 2 * N3
+        extra["decode_M1_14336x4096"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
+                                         "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+        del copies, X3
 
     # ---------------- CPU baseline: the oracle on a bounded sample ------------------------
     cpu = None

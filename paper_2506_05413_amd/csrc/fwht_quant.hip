@@ -248,6 +248,104 @@ __global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// K = 4096: one WAVE per row, no workgroup barriers.  A lane holds 64 fp32 values, so six index
+// bits are butterflied in registers at a time and only one transposition separates the two
+// halves of the transform:
+//   phase 1  lane l loads the 16-byte chunks l, l+64, ..: registers = index bits {0,1,2,9,10,11}
+//   LDS      wave-private transposition (row padded by 8 floats per 512: conflict-free both ways)
+//   phase 2  lane (e = l & 7, j = l >> 3) holds elements 512 j + 8 r + e: registers = bits 3..8
+//   row absmax by a wave reduction, Delta, then back through LDS to the natural order, where a
+//   lane quantises 8 consecutive values into one packed dword.
+// Quantisation: t = fma(y, 1/Delta, 1.5 * 2^23) rounds y/Delta to the nearest-even integer in
+// the low mantissa bits (one rounding); the clamp is an integer median on those bits; eight
+// clamped words are packed by shift-adds modulo 2^32, the constant part subtracted once, and
+// offset-binary nibbles become two's complement by XOR 0x88888888.
+// ------------------------------------------------------------------------------------------
+constexpr uint32_t kMagicBits = 0x4B400000u;             // bit pattern of 1.5 * 2^23
+constexpr uint32_t pack_bias()
+{
+    uint32_t c = 0;
+    for (int e = 0; e < 8; ++e) c += (kMagicBits - 8u) << (4 * e);
+    return c;
+}
+
+template <bool HAS_PRE>
+__global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__restrict__ X, int64_t ldx, int64_t rows,
+                                                            const float *__restrict__ pre, float clip, float post_scale,
+                                                            uint8_t *__restrict__ Q, float *__restrict__ scale_out)
+{
+    constexpr int K = 4096, ROWF = K + 64;               // floats per wave-private row incl. padding
+    extern __shared__ float smem_rows[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t m = (int64_t)blockIdx.x * 4 + wave;
+    if (m >= rows) return;                               // no barrier below: waves are independent
+    float *buf = smem_rows + wave * ROWF;
+    const __half *x = X + m * ldx;
+
+    // ---- phase 1 --------------------------------------------------------------------------
+    float v[64];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        union { uint4 u; __half h[8]; } raw;
+        raw.u = *reinterpret_cast<const uint4 *>(x + 512 * j + 8 * lane);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[8 * j + e] = __half2float(raw.h[e]);
+        if (HAS_PRE) {
+            const float4 s0 = *reinterpret_cast<const float4 *>(pre + 512 * j + 8 * lane);
+            const float4 s1 = *reinterpret_cast<const float4 *>(pre + 512 * j + 8 * lane + 4);
+            v[8 * j + 0] *= s0.x; v[8 * j + 1] *= s0.y; v[8 * j + 2] *= s0.z; v[8 * j + 3] *= s0.w;
+            v[8 * j + 4] *= s1.x; v[8 * j + 5] *= s1.y; v[8 * j + 6] *= s1.z; v[8 * j + 7] *= s1.w;
+        }
+    }
+    butterflies<6>(v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        float *d = buf + 520 * j + 8 * lane;             // element 512 j + 8 l + e lives at 520 j + 8 l + e
+        *reinterpret_cast<float4 *>(d) = make_float4(v[8 * j], v[8 * j + 1], v[8 * j + 2], v[8 * j + 3]);
+        *reinterpret_cast<float4 *>(d + 4) = make_float4(v[8 * j + 4], v[8 * j + 5], v[8 * j + 6], v[8 * j + 7]);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+
+    // ---- phase 2 --------------------------------------------------------------------------
+    const float *src = buf + 520 * (lane >> 3) + (lane & 7);
+#pragma unroll
+    for (int r = 0; r < 64; ++r) v[r] = src[8 * r];
+    butterflies<6>(v);
+    float amax = 0.f;
+#pragma unroll
+    for (int r = 0; r < 64; r += 2) amax = fmaxf(fmaxf(amax, fabsf(v[r])), fabsf(v[r + 1]));
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+    const float delta = (amax == 0.f) ? 1.f : (clip * amax) / 7.f;
+    const float inv_delta = 1.f / delta;
+    if (lane == 0) scale_out[m] = (amax == 0.f) ? 1.f : delta * post_scale;
+
+    float *dst = buf + 520 * (lane >> 3) + (lane & 7);
+#pragma unroll
+    for (int r = 0; r < 64; ++r) dst[8 * r] = v[r];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+
+    // ---- quantise: 8 consecutive values -> one dword -------------------------------------------
+    uint32_t *q = reinterpret_cast<uint32_t *>(Q + m * (int64_t)(K / 2));
+    const float magic = __uint_as_float(kMagicBits);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float *s8 = buf + 520 * j + 8 * lane;
+        const float4 a = *reinterpret_cast<const float4 *>(s8);
+        const float4 b = *reinterpret_cast<const float4 *>(s8 + 4);
+        const float y[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        uint32_t word = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            int bits = (int)__float_as_uint(fmaf(y[e], inv_delta, magic));
+            bits = min(max(bits, (int)kMagicBits - 8), (int)kMagicBits + 7);
+            word += (uint32_t)bits << (4 * e);
+        }
+        q[64 * j + lane] = (word - pack_bias()) ^ 0x88888888u;
+    }
+}
+
 template <int K>
 hipError_t launch_one(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip,
                       float post_scale, uint8_t *Q, float *scale_out, hipStream_t st)
@@ -272,6 +370,25 @@ hipError_t launch_fwht_quant(const void *X, int64_t rows, int64_t K, int64_t ldx
                              float clip, float post_scale, uint8_t *Q, float *scale_out, hipStream_t st)
 {
 #define SR_CASE(KK) case KK: return launch_one<KK>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
+    if (K == 4096) {
+        constexpr size_t lds = 4 * (4096 + 64) * sizeof(float);
+        const unsigned blocks = (unsigned)((rows + 3) / 4);
+        hipError_t e;
+        if (pre) {
+            auto kern = fwht4096_wave_kernel<true>;
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, static_cast<const __half *>(X), ldx, rows, pre, clip,
+                               post_scale, Q, scale_out);
+        } else {
+            auto kern = fwht4096_wave_kernel<false>;
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, static_cast<const __half *>(X), ldx, rows, pre, clip,
+                               post_scale, Q, scale_out);
+        }
+        return hipGetLastError();
+    }
     switch (K) {
         SR_CASE(64) SR_CASE(128) SR_CASE(256) SR_CASE(512) SR_CASE(1024) SR_CASE(2048)
         SR_CASE(4096) SR_CASE(8192) SR_CASE(16384) SR_CASE(32768)
