@@ -148,6 +148,31 @@ __device__ __forceinline__ void lds_passes(float *row, int t, float &amax)
     }
 }
 
+// ---- quantise + pack eight values (shared by all kernels) ---------------------------------
+// t = fma(y, 1/Delta, 1.5 * 2^23) rounds y/Delta to the nearest-even integer in the low mantissa
+// bits (one rounding); the clamp to [-8, 7] is an integer median on those bits; the eight clamped
+// words are packed by shift-adds modulo 2^32, the constant part subtracted once, and the
+// offset-binary nibbles become two's complement by XOR 0x88888888.
+constexpr uint32_t kMagicBits = 0x4B400000u;             // bit pattern of 1.5 * 2^23
+constexpr uint32_t pack_bias()
+{
+    uint32_t c = 0;
+    for (int e = 0; e < 8; ++e) c += (kMagicBits - 8u) << (4 * e);
+    return c;
+}
+__device__ __forceinline__ uint32_t quant_pack8(const float (&y)[8], float inv_delta)
+{
+    const float magic = __uint_as_float(kMagicBits);
+    uint32_t word = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        int bits = (int)__float_as_uint(fmaf(y[e], inv_delta, magic));
+        bits = min(max(bits, (int)kMagicBits - 8), (int)kMagicBits + 7);
+        word += (uint32_t)bits << (4 * e);
+    }
+    return (word - pack_bias()) ^ 0x88888888u;
+}
+
 template <int K, int NT>
 __global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict__ X, int64_t ldx,
                                                         const float *__restrict__ pre, float clip,
@@ -194,10 +219,39 @@ __global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict
     if constexpr (LOGP == 4 && !KRON) {
         // K = 16 cannot occur (K >= 64); kept for completeness of the template
     }
-    lds_passes<K, NT, 4, LOGP, !KRON>(row, t, amax);
+    // a single leftover bit of the power-of-two part is folded into the Paley pass (56 values per group)
+    constexpr bool MERGE = KRON && ((LOGP - 4) % 4 == 1);
+    lds_passes<K, NT, 4, MERGE ? LOGP - 1 : LOGP, !KRON>(row, t, amax);
 
     // ---- Paley factor: 28 values at stride P2 per group ---------------------------------
-    if constexpr (KRON) {
+    if constexpr (MERGE) {
+        constexpr int HALF = P2 / 2;
+        for (int g = t; g < HALF; g += NT) {
+            float a[28], b[28], o[28];
+            float Sa = 0.f, Sb = 0.f;
+#pragma unroll
+            for (int i = 0; i < 28; ++i) {
+                const float lo = row[pad(g + i * P2)], hi = row[pad(g + HALF + i * P2)];
+                a[i] = lo + hi;
+                b[i] = lo - hi;
+                Sa += a[i];
+                Sb += b[i];
+            }
+            h28_apply(a, o, Sa, std::make_integer_sequence<int, 28>{});
+#pragma unroll
+            for (int j = 0; j < 28; ++j) {
+                row[pad(g + j * P2)] = o[j];
+                amax = fmaxf(amax, fabsf(o[j]));
+            }
+            h28_apply(b, o, Sb, std::make_integer_sequence<int, 28>{});
+#pragma unroll
+            for (int j = 0; j < 28; ++j) {
+                row[pad(g + HALF + j * P2)] = o[j];
+                amax = fmaxf(amax, fabsf(o[j]));
+            }
+        }
+        __syncthreads();
+    } else if constexpr (KRON) {
         for (int g = t; g < P2; g += NT) {
             float v[28], o[28];
             float S = 0.f;
@@ -237,14 +291,7 @@ __global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict
         const float4 a = *reinterpret_cast<const float4 *>(src);
         const float4 b = *reinterpret_cast<const float4 *>(src + 4);
         const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        uint32_t word = 0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float r = rintf(v[e] * inv_delta);                 // round half to even
-            r = fminf(fmaxf(r, -8.f), 7.f);
-            word |= (static_cast<uint32_t>(static_cast<int>(r)) & 0xFu) << (4 * e);
-        }
-        q[c] = word;
+        q[c] = quant_pack8(v, inv_delta);
     }
 }
 
@@ -257,18 +304,7 @@ __global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict
 //   phase 2  lane (e = l & 7, j = l >> 3) holds elements 512 j + 8 r + e: registers = bits 3..8
 //   row absmax by a wave reduction, Delta, then back through LDS to the natural order, where a
 //   lane quantises 8 consecutive values into one packed dword.
-// Quantisation: t = fma(y, 1/Delta, 1.5 * 2^23) rounds y/Delta to the nearest-even integer in
-// the low mantissa bits (one rounding); the clamp is an integer median on those bits; eight
-// clamped words are packed by shift-adds modulo 2^32, the constant part subtracted once, and
-// offset-binary nibbles become two's complement by XOR 0x88888888.
 // ------------------------------------------------------------------------------------------
-constexpr uint32_t kMagicBits = 0x4B400000u;             // bit pattern of 1.5 * 2^23
-constexpr uint32_t pack_bias()
-{
-    uint32_t c = 0;
-    for (int e = 0; e < 8; ++e) c += (kMagicBits - 8u) << (4 * e);
-    return c;
-}
 
 template <bool HAS_PRE>
 __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__restrict__ X, int64_t ldx, int64_t rows,
@@ -328,21 +364,13 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
 
     // ---- quantise: 8 consecutive values -> one dword -------------------------------------------
     uint32_t *q = reinterpret_cast<uint32_t *>(Q + m * (int64_t)(K / 2));
-    const float magic = __uint_as_float(kMagicBits);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const float *s8 = buf + 520 * j + 8 * lane;
         const float4 a = *reinterpret_cast<const float4 *>(s8);
         const float4 b = *reinterpret_cast<const float4 *>(s8 + 4);
         const float y[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        uint32_t word = 0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            int bits = (int)__float_as_uint(fmaf(y[e], inv_delta, magic));
-            bits = min(max(bits, (int)kMagicBits - 8), (int)kMagicBits + 7);
-            word += (uint32_t)bits << (4 * e);
-        }
-        q[64 * j + lane] = (word - pack_bias()) ^ 0x88888888u;
+        q[64 * j + lane] = quant_pack8(y, inv_delta);
     }
 }
 
