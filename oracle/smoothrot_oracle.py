@@ -272,6 +272,135 @@ def w4a4_linear(X, W, act_absmax, alpha=0.5, clip=0.9, w_clip=1.0, use_c=False):
 
 
 # ---------------------------------------------------------------------------
+# Rows around the core path: the gated FFN input, head-wise Hadamard transforms,
+# the weight clipping-ratio search and the KV-cache quantiser.
+# ---------------------------------------------------------------------------
+
+def swiglu(G: np.ndarray, U: np.ndarray) -> np.ndarray:
+    """Input of the down-projection (Fig. 2, FFN block): sigma(gate) * up with
+    sigma(g) = g / (1 + exp(-g)) (SiLU), elementwise, fp64."""
+    g = np.asarray(G, dtype=np.float64)
+    return g / (1.0 + np.exp(-g)) * np.asarray(U, dtype=np.float64)
+
+
+def fwht_quant_swiglu(G, U, inv_s, clip: float = 0.9):
+    """fwht_quant_act applied to x = sigma(gate) * up without rounding x to fp16 in
+    between (the smoothing, rotation and quantiser of Fig. 2's FFN branch)."""
+    return fwht_quant_act(swiglu(G, U), inv_s, clip)
+
+
+def rotate_heads(x: np.ndarray, n_heads: int, across: bool) -> np.ndarray:
+    """Head-wise Hadamard transforms on a [.., n_heads * d] axis seen as [n_heads, d]
+    (section "Methodology": the head-wise online Hadamard of the attention block).
+
+    across=True : H_{n_heads} (x) I_d -- mixes the heads, position inside the head kept;
+    across=False: I_{n_heads} (x) H_d -- one transform of order d inside every head.
+    Both orders are powers of two (Sylvester).  Their composition is the full
+    H_{n_heads * d}, which the pins check."""
+    n = x.shape[-1]
+    assert n % n_heads == 0
+    d = n // n_heads
+    v = np.asarray(x, dtype=np.float64).reshape(-1, n_heads, d)
+    if across:
+        y = np.einsum("ij,rid->rjd", sylvester(n_heads).astype(np.float64), v)
+    else:
+        y = fwht_pow2(v)
+    return y.reshape(x.shape)
+
+
+def fwht_quant_act_heads(X, n_heads: int, across: bool, inv_s, clip: float = 0.9):
+    """fwht_quant_act with the head-wise transform in place of the full one."""
+    Xd = np.asarray(X, dtype=np.float64)
+    if inv_s is not None:
+        Xd = Xd * np.asarray(inv_s, dtype=np.float64)[None, :]
+    y = rotate_heads(Xd, n_heads, across)
+    codes, x_scale, t = quant_sym_int4(y, clip)
+    return dict(codes=codes, packed=pack_int4(codes), x_scale=x_scale, y=y, t=t)
+
+
+def clip_grid(steps: int = 21, lo: float = 0.5) -> np.ndarray:
+    """Candidate clipping ratios of the weight search, 1.0 down to `lo` in equal steps
+    (the paper says 'linear search' and names no grid; 1.00, 0.975, .. 0.50 is this
+    build's reading)."""
+    return 1.0 - (1.0 - lo) * np.arange(steps) / float(steps - 1)
+
+
+def weight_clip_search(v: np.ndarray, grid: np.ndarray):
+    """Per-row clipping ratio by linear search over the squared error ("Quantization"
+    settings: weights RTN per channel, clipping ratios by a linear search over the squared
+    error).  For every ratio r of `grid` (descending): Delta = r * absmax / 7,
+    c = clamp(rint(v / Delta), -8, 7), err_r = sum_j (v_j - Delta * c_j)^2; the row takes
+    the ratio of smallest error, the first (largest) one on ties.
+    Returns (best ratio [rows], err [rows, len(grid)], codes, Delta, t) for the chosen ratio."""
+    v = np.asarray(v, dtype=np.float64)
+    errs = np.empty((v.shape[0], len(grid)))
+    for i, r in enumerate(grid):
+        c, d, _ = quant_sym_int4(v, float(r))
+        errs[:, i] = np.sum((v - dequant(c, d)) ** 2, axis=1)
+    best = np.argmin(errs, axis=1)            # first minimum = largest ratio
+    ratio = np.asarray(grid, dtype=np.float64)[best]
+    absmax = np.max(np.abs(v), axis=1)
+    delta = np.where(absmax == 0.0, 1.0, ratio * absmax / float(QMAX))
+    t = v / delta[:, None]
+    codes = np.clip(np.rint(t), QMIN, QMAX).astype(np.int8)
+    return ratio, errs, codes, delta, t
+
+
+def fold_clip_search(W, act_absmax, alpha: float, grid: np.ndarray):
+    """fold_smooth_rotate_quant with the per-output-channel clipping ratio searched."""
+    Wd = np.asarray(W, dtype=np.float64)
+    K, N = Wd.shape
+    s = np.ones(K) if act_absmax is None else smoothing_factors(act_absmax, Wd, alpha)
+    what_t = rotate(np.ascontiguousarray((s[:, None] * Wd).T)) / float(K)
+    ratio, errs, codes, w_scale, t = weight_clip_search(what_t, grid)
+    return dict(codes=codes, packed=pack_int4(codes), w_scale=w_scale, s=s, inv_s=1.0 / s,
+                ratio=ratio, errs=errs, t=t, W_hat_t=what_t)
+
+
+def quant_asym_int4_groups(v: np.ndarray, group: int = 128, clip: float = 0.95):
+    """Asymmetric 4-bit quantisation of consecutive groups of `group` values along the
+    last axis (Eq. (1), asymmetric case; "Quantization" settings: keys and values,
+    group size 128, constant clipping ratio 0.95):
+
+        hi = clip * max, lo = clip * min over the group
+        Delta = (hi - lo) / 15,  z = -rint(lo / Delta)
+        code  = clamp(rint(v / Delta) + z, 0, 15),   Q(v) = (code - z) * Delta
+
+    Readings: the clipping ratio shrinks both ends of the range; a group whose range is
+    zero takes Delta = 1; z is kept as an integer of any size (a group that does not
+    straddle zero has z outside 0..15).
+    Returns (codes uint8 [rows, n], Delta [rows, n/group], z [rows, n/group] int64,
+    u = v / Delta pre-round [rows, n], lo / Delta pre-round [rows, n/group])."""
+    v = np.asarray(v, dtype=np.float64)
+    rows, n = v.shape
+    assert n % group == 0
+    g = v.reshape(rows, n // group, group)
+    hi = clip * g.max(axis=2)
+    lo = clip * g.min(axis=2)
+    delta = (hi - lo) / 15.0
+    delta = np.where(hi == lo, 1.0, delta)
+    zt = lo / delta
+    z = -np.rint(zt).astype(np.int64)
+    u = g / delta[:, :, None]
+    codes = np.clip(np.rint(u) + z[:, :, None], 0, 15).astype(np.uint8)
+    return codes.reshape(rows, n), delta, z, u.reshape(rows, n), zt
+
+
+def dequant_asym(codes, delta, z, group: int = 128) -> np.ndarray:
+    """Q(v) = (code - z) * Delta per group (Eq. (1) ff.)."""
+    rows, n = codes.shape
+    c = codes.reshape(rows, n // group, group).astype(np.float64)
+    return ((c - np.asarray(z, np.float64)[:, :, None]) * np.asarray(delta, np.float64)[:, :, None]).reshape(rows, n)
+
+
+def pack_uint4(codes: np.ndarray) -> np.ndarray:
+    """[rows, n] codes in 0..15 -> [rows, n/2] bytes, even index in bits 0-3."""
+    c = np.asarray(codes).astype(np.uint8)
+    assert c.max(initial=0) <= 15
+    return (c[..., 0::2] | (c[..., 1::2] << 4)).astype(np.uint8)
+
+
+# ---------------------------------------------------------------------------
 # The same integer GEMM as a plain C triple loop (oracle/gemm_i4.c), for sizes
 # where numpy's int64 matmul is too slow.  Pinned to gemm_i32 in the tests.
 # ---------------------------------------------------------------------------

@@ -322,3 +322,203 @@ def test_qualitative_ordering_on_outlier_config():
     r_rot = np.abs(o.rotate(X)).max() / np.sqrt(512)
     r_sr = np.abs(o.fwht_quant_act(c["X"], 1 / o.smoothing_factors(a, W, 0.5), 0.9)["y"]).max() / np.sqrt(512)
     assert np.abs(X).max() > r_rot > r_sr
+
+
+# ----------------------------------------------------------------- rows around the core path
+
+def test_swiglu_closed_forms_and_library_sigmoid():
+    from scipy.special import expit          # an independent sigmoid
+    rng = np.random.default_rng(5)
+    g = rng.standard_normal(4000) * 4
+    u = rng.standard_normal(4000)
+    y = o.swiglu(g, u)
+    assert np.allclose(y, g * expit(g) * u, rtol=1e-14, atol=0)
+    # silu(g) - silu(-g) = g (sigma(g) + sigma(-g) = 1), silu(0) = 0, silu(g) -> g for large g
+    one = np.ones_like(g)
+    assert np.allclose(o.swiglu(g, one) - o.swiglu(-g, one), g, rtol=0, atol=1e-14)
+    assert o.swiglu(np.zeros(1), np.ones(1))[0] == 0.0
+    assert abs(o.swiglu(np.array([40.0]), np.array([1.0]))[0] - 40.0) < 1e-12
+    # the gate, not the up branch, goes through the non-linearity
+    assert o.swiglu(np.array([-30.0]), np.array([5.0]))[0] > -1e-10
+    assert o.swiglu(np.array([5.0]), np.array([-30.0]))[0] < -100
+
+
+@pytest.mark.parametrize("nh,d", [(4, 8), (8, 4), (32, 16), (1, 64), (64, 1)])
+def test_rotate_heads_is_the_kronecker_product(nh, d):
+    rng = np.random.default_rng(nh * 100 + d)
+    x = rng.integers(-9, 10, size=(5, nh * d)).astype(np.float64)
+    Hh, Hd = o.sylvester(nh), o.sylvester(d)
+    across = np.kron(Hh, np.eye(d, dtype=np.int64))
+    within = np.kron(np.eye(nh, dtype=np.int64), Hd)
+    assert np.array_equal(o.rotate_heads(x, nh, True), x @ across)
+    assert np.array_equal(o.rotate_heads(x, nh, False), x @ within)
+    # the two commute and compose to the full transform of order nh * d
+    full = x @ o.sylvester(nh * d)
+    assert np.array_equal(o.rotate_heads(o.rotate_heads(x, nh, True), nh, False), full)
+    assert np.array_equal(o.rotate_heads(o.rotate_heads(x, nh, False), nh, True), full)
+
+
+def test_rotate_heads_full_size_involution():
+    rng = np.random.default_rng(8)
+    x = rng.integers(-50, 50, size=(3, 4096)).astype(np.float64)
+    for across, order in ((True, 32), (False, 128)):
+        y = o.rotate_heads(o.rotate_heads(x, 32, across), 32, across)
+        assert np.array_equal(y, order * x)
+    # a single non-zero entry stays inside its head (within) / inside its lane of the head (across)
+    e = np.zeros((1, 4096)); e[0, 5 * 128 + 17] = 1.0
+    yw = o.rotate_heads(e, 32, False).reshape(32, 128)
+    assert np.all(yw[5] != 0) and np.count_nonzero(yw) == 128
+    ya = o.rotate_heads(e, 32, True).reshape(32, 128)
+    assert np.all(ya[:, 17] != 0) and np.count_nonzero(ya) == 32
+
+
+def test_fwht_quant_act_heads_uses_the_head_transform():
+    X = wl.cfg1()["X"][:4].astype(np.float64)
+    r = o.fwht_quant_act_heads(X, 8, True, None, 0.9)
+    y = X @ np.kron(o.sylvester(8), np.eye(64))
+    assert np.allclose(r["y"], y, rtol=0, atol=1e-9)
+    c, d, _ = o.quant_sym_int4(y, 0.9)
+    assert np.array_equal(r["codes"], c) and np.allclose(r["x_scale"], d, rtol=1e-15)
+
+
+def test_clip_grid():
+    g = o.clip_grid()
+    assert len(g) == 21 and g[0] == 1.0 and abs(g[-1] - 0.5) < 1e-15
+    assert np.allclose(np.diff(g), -0.025, atol=1e-15)
+
+
+def test_weight_clip_search_closed_form_row():
+    # v = [8, 1 x m]: for a ratio r in (7/12, 1] the ones get code 1 and the 8 is clamped to 7, so
+    # err(r) = m (1 - 8r/7)^2 + 64 (1 - r)^2; at r = 1 the 8 is exact: err = m / 49.
+    m = 99
+    v = np.array([[8.0] + [1.0] * m])
+    grid = o.clip_grid()
+    ratio, errs, codes, delta, _ = o.weight_clip_search(v, grid)
+    for i, r in enumerate(grid):
+        if r > 0.6:
+            want = m * (1 - 8 * r / 7) ** 2 + 64 * (1 - r) ** 2
+            assert abs(errs[0, i] - want) < 1e-9, (r, errs[0, i], want)
+    # minimiser of the closed form over the grid
+    cand = [(m * (1 - 8 * r / 7) ** 2 + 64 * (1 - r) ** 2, -r) for r in grid if r > 0.6]
+    best_r = -min(cand)[1]
+    assert abs(ratio[0] - best_r) < 1e-12 and best_r < 1.0
+    assert abs(delta[0] - best_r * 8 / 7) < 1e-12
+    assert codes[0, 0] == 7 and np.all(codes[0, 1:] == 1)
+
+
+def test_weight_clip_search_brute_force_and_ties():
+    rng = np.random.default_rng(21)
+    v = rng.standard_normal((6, 24)) * rng.choice([0.1, 1.0, 5.0], size=(6, 24))
+    grid = o.clip_grid()
+    ratio, errs, codes, delta, _ = o.weight_clip_search(v, grid)
+    for row in range(6):
+        best, best_err = None, None
+        amax = max(abs(float(x)) for x in v[row])
+        for r in grid:                                  # descending: '<' keeps the larger ratio on ties
+            d = float(r) * amax / 7.0
+            e = 0.0
+            for x in v[row]:
+                c = min(7, max(-8, round(float(x) / d)))      # Python's round = half to even
+                e += (float(x) - c * d) ** 2
+            if best_err is None or e < best_err:
+                best, best_err = float(r), e
+        assert abs(ratio[row] - best) < 1e-12
+        assert abs(errs[row].min() - best_err) <= 1e-12 * max(best_err, 1e-30)
+    # a row already on the 15-level grid has zero error at ratio 1: the tie rule keeps 1.0
+    exact = np.array([[7.0, -7.0, 3.0, 0.0, 1.0, -2.0, 5.0, -6.0]])
+    r2, e2, c2, d2, _ = o.weight_clip_search(exact, grid)
+    assert r2[0] == 1.0 and e2[0, 0] == 0.0 and d2[0] == 1.0
+    assert np.array_equal(c2[0], exact[0].astype(np.int8))
+    # never worse than plain RTN, zero row -> Delta 1
+    assert np.all(errs.min(axis=1) <= errs[:, 0])
+    assert o.weight_clip_search(np.zeros((1, 8)), grid)[3][0] == 1.0
+
+
+def test_fold_clip_search_consistent_with_plain_fold():
+    c1 = wl.cfg1()
+    X, W = c1["X"], c1["W"]
+    a = o.calib_absmax(X, np.zeros(512))
+    f1 = o.fold_smooth_rotate_quant(W[:, :32], a, 0.5, 1.0)
+    f = o.fold_clip_search(W[:, :32], a, 0.5, np.array([1.0]))      # one-point grid = plain RTN
+    assert np.array_equal(f["codes"], f1["codes"]) and np.allclose(f["w_scale"], f1["w_scale"], rtol=1e-15)
+    g = o.fold_clip_search(W[:, :32], a, 0.5, o.clip_grid())
+    what = f1["W_hat"].T
+    e_plain = np.sum((what - o.dequant(f1["codes"], f1["w_scale"])) ** 2, axis=1)
+    e_srch = np.sum((what - o.dequant(g["codes"], g["w_scale"])) ** 2, axis=1)
+    assert np.all(e_srch <= e_plain + 1e-18) and np.any(e_srch < e_plain)
+
+
+def test_asym_quantiser_hand_worked_group():
+    xs, want_c, want_q, clip = [], [], [], None
+    for line in open(os.path.join(GOLDEN, "hand_asym_group.txt")):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        p = line.split()
+        if p[0] == "clip":
+            clip = float(p[1])
+            continue
+        xs.append(float(p[0])); want_c.append(int(p[1])); want_q.append(float(p[2]))
+    v = np.array([xs])
+    codes, delta, z, _, _ = o.quant_asym_int4_groups(v, group=8, clip=clip)
+    assert delta[0, 0] == 0.25 and z[0, 0] == 5
+    assert codes[0].tolist() == want_c
+    assert o.dequant_asym(codes, delta, z, group=8)[0].tolist() == want_q
+
+
+def test_asym_quantiser_properties():
+    rng = np.random.default_rng(33)
+    v = rng.standard_normal((16, 512)) * 3 + rng.standard_normal((16, 1))
+    codes, delta, z, _, _ = o.quant_asym_int4_groups(v, 128, 1.0)
+    assert codes.min() == 0 and codes.max() == 15
+    g = v.reshape(16, 4, 128)
+    cg = codes.reshape(16, 4, 128)
+    # without clipping the minimum gets code 0, the maximum code 15, and no value moves by more than Delta / 2
+    assert np.all(np.take_along_axis(cg, g.argmin(axis=2)[..., None], 2) == 0)
+    assert np.all(np.take_along_axis(cg, g.argmax(axis=2)[..., None], 2) == 15)
+    err = np.abs(o.dequant_asym(codes, delta, z) - v).reshape(16, 4, 128)
+    assert np.all(err <= delta[:, :, None] / 2 * (1 + 1e-12))
+    assert np.allclose(delta, (g.max(axis=2) - g.min(axis=2)) / 15, rtol=1e-15)
+    # groups are independent: permuting groups permutes results
+    perm = v.reshape(16, 4, 128)[:, ::-1, :].reshape(16, 512)
+    c2, d2, z2, _, _ = o.quant_asym_int4_groups(perm, 128, 1.0)
+    assert np.array_equal(c2.reshape(16, 4, 128)[:, ::-1], cg) and np.array_equal(d2[:, ::-1], delta)
+    # power-of-two scaling leaves the codes alone; shifting by k * Delta moves only the zero-point
+    c3, d3, z3, _, _ = o.quant_asym_int4_groups(v * 8.0, 128, 1.0)
+    assert np.array_equal(c3, codes) and np.array_equal(z3, z) and np.allclose(d3, 8 * delta, rtol=1e-15)
+    one = np.array([[-1.0, 0.0, 0.45, 2.0]])                # Delta = 0.2, no ties
+    c4, d4, z4, _, _ = o.quant_asym_int4_groups(one, 4, 1.0)
+    c5, d5, z5, _, _ = o.quant_asym_int4_groups(one + 3 * d4[0, 0], 4, 1.0)
+    assert np.array_equal(c4, c5) and z5[0, 0] == z4[0, 0] - 3
+    # all-positive group: zero-point is negative; constant group: Delta = 1
+    c6, d6, z6, _, _ = o.quant_asym_int4_groups(np.array([[10.0, 25.0, 11.0, 12.0]]), 4, 1.0)
+    assert d6[0, 0] == 1.0 and z6[0, 0] == -10 and c6[0].tolist() == [0, 15, 1, 2]
+    c7, d7, z7, _, _ = o.quant_asym_int4_groups(np.full((1, 4), 3.0), 4, 0.95)
+    assert d7[0, 0] == 1.0
+    assert np.allclose(o.dequant_asym(c7, d7, z7, 4), 3.0)
+    # clipping: range shrinks at both ends, clipped values saturate at 0 / 15
+    c8, d8, z8, _, _ = o.quant_asym_int4_groups(v, 128, 0.95)
+    assert np.allclose(d8, 0.95 * delta, rtol=1e-15)
+    assert np.all(np.take_along_axis(c8.reshape(16, 4, 128), g.argmax(axis=2)[..., None], 2) == 15)
+    assert np.all(np.take_along_axis(c8.reshape(16, 4, 128), g.argmin(axis=2)[..., None], 2) == 0)
+
+
+def test_asym_quantiser_brute_force():
+    rng = np.random.default_rng(34)
+    v = rng.standard_normal((3, 16)) + 0.3
+    codes, delta, z, _, _ = o.quant_asym_int4_groups(v, 8, 0.95)
+    for r in range(3):
+        for gi in range(2):
+            xs = [float(x) for x in v[r, gi * 8:(gi + 1) * 8]]
+            hi, lo = 0.95 * max(xs), 0.95 * min(xs)
+            d = (hi - lo) / 15.0
+            zz = -round(lo / d)
+            assert abs(delta[r, gi] - d) < 1e-15 and z[r, gi] == zz
+            for j, x in enumerate(xs):
+                assert codes[r, gi * 8 + j] == min(15, max(0, round(x / d) + zz))
+
+
+def test_pack_uint4_all_bytes():
+    b = np.arange(256, dtype=np.uint8)
+    codes = np.stack([b & 0xF, b >> 4], axis=1).reshape(1, 512)
+    assert np.array_equal(o.pack_uint4(codes)[0], b)
