@@ -148,6 +148,71 @@ SR_API int sr_w4a4_gemm(const uint8_t *Xq, const float *x_scale,
                  void *Y, int64_t ldy, int out_dtype,
                  void *workspace, size_t workspace_bytes, void *stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Rows around the core path.  Same conventions as above.
+ * ------------------------------------------------------------------------------------------ */
+
+/*
+ * sr_fwht_quant_act with the gated-FFN product fused in front (paper, Fig. 2, FFN block: the
+ * down-projection input sigma(gate) (.) up is smoothed, rotated and quantised):
+ *     x_m = silu(G_m) * U_m     (fp32, silu(g) = g / (1 + exp(-g)); x is not rounded to fp16)
+ *     then exactly sr_fwht_quant_act on x.
+ *   G_f16, U_f16   fp16 [M, K], row strides ldg / ldu
+ */
+SR_API int sr_swiglu_fwht_quant_act(const void *G_f16, const void *U_f16, int64_t M, int64_t K,
+                             int64_t ldg, int64_t ldu, const float *inv_s, float clip,
+                             uint8_t *Xq, float *x_scale, void *stream);
+
+/*
+ * sr_fwht_quant_act with a head-wise Hadamard transform in place of the full one (paper,
+ * section "Methodology": head-wise online Hadamard in the attention block).  The K axis is
+ * seen as [n_heads, d], d = K / n_heads, both powers of two:
+ *     across != 0:  H_{n_heads} (x) I_d   (mixes the heads, position inside the head kept)
+ *     across == 0:  I_{n_heads} (x) H_d   (one transform of order d inside every head)
+ * The two commute and compose to the full H_K.  K must be a power of two here;
+ * 1 <= n_heads <= K (SR_ERR_ARG otherwise).
+ */
+SR_API int sr_fwht_quant_act_heads(const void *X_f16, int64_t M, int64_t K, int64_t ldx,
+                            int64_t n_heads, int across, const float *inv_s, float clip,
+                            uint8_t *Xq, float *x_scale, void *stream);
+
+/*
+ * sr_fold_smooth_rotate_quant with two options:
+ *   n_heads, across   the transform folded into the weights: n_heads = 0 is the full Hadamard
+ *                     (1/K folded into the scale); otherwise the head-wise transform of
+ *                     sr_fwht_quant_act_heads (its order n_heads or K / n_heads folded instead).
+ *   clip_steps, clip_lo   per-output-channel clipping ratio by linear search over the squared
+ *                     quantisation error (paper, "Quantization" settings): candidates
+ *                     r_i = 1 - (1 - clip_lo) * i / (clip_steps - 1), i = 0 .. clip_steps - 1;
+ *                     err_i = sum_j (W^[j][n] - d_i * code_i(W^[j][n]))^2 with d_i = r_i * absmax / 7;
+ *                     the smallest error wins, the larger ratio on ties.  clip_steps = 1 means
+ *                     the fixed ratio clip_lo (plain RTN for 1.0).  1 <= clip_steps <= 32,
+ *                     clip_lo in (0, 1].
+ *   w_ratio           out, fp32 [N]: the ratio chosen per output channel; may be NULL.
+ * Everything else as in sr_fold_smooth_rotate_quant (same workspace size).
+ */
+SR_API int sr_fold_smooth_rotate_quant_ex(const void *W_f16, int64_t K, int64_t N, int64_t ldw,
+                                   const float *act_absmax, float alpha,
+                                   int64_t n_heads, int across, int clip_steps, float clip_lo,
+                                   uint8_t *Wq, float *w_scale, float *inv_s, float *w_ratio,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Asymmetric 4-bit group quantiser for keys and values (paper: Eq. (1), asymmetric case;
+ * "Quantization" settings: group size 128, constant clipping ratio 0.95).  Per group of
+ * `group` consecutive values of a row:
+ *     hi = clip * max, lo = clip * min
+ *     d  = (hi - lo) / 15        (1 when hi == lo)
+ *     z  = -rint(lo / d)
+ *     code = clamp(rint(v / d) + z, 0, 15),     dequantised value = (code - z) * d
+ *
+ *   X_f16   fp16 [rows, D], row stride ldx;  D a multiple of group;  group in {32, 64, 128, 256, 512}
+ *   Q       out, uint8 [rows, D/2]: code(2b) in bits 0-3 of byte b, code(2b+1) in bits 4-7 (unsigned)
+ *   scale   out, fp32 [rows, D/group]  (d);   zero  out, fp32 [rows, D/group]  (z, integer valued)
+ */
+SR_API int sr_kv_quant_asym(const void *X_f16, int64_t rows, int64_t D, int64_t ldx, int64_t group, float clip,
+                     uint8_t *Q, float *scale, float *zero, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

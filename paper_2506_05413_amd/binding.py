@@ -31,6 +31,11 @@ _SIGNATURES = {
     "sr_fold_smooth_rotate_quant": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "sr_fwht_quant_act": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _vp]),
     "sr_w4a4_gemm": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _int, _vp, _sz, _vp]),
+    "sr_swiglu_fwht_quant_act": (_int, [_vp, _vp, _i64, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _vp]),
+    "sr_fwht_quant_act_heads": (_int, [_vp, _i64, _i64, _i64, _i64, _int, _vp, _f32, _vp, _vp, _vp]),
+    "sr_fold_smooth_rotate_quant_ex": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _i64, _int, _int, _f32,
+                                               _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "sr_kv_quant_asym": (_int, [_vp, _i64, _i64, _i64, _i64, _f32, _vp, _vp, _vp, _vp]),
 }
 
 _lib = None
@@ -154,3 +159,65 @@ def sr_w4a4_gemm(Xq, x_scale, Wq, w_scale, out_dtype: int = SR_F16, Y=None, work
                               _stream()),
            "sr_w4a4_gemm")
     return Y
+
+
+def sr_swiglu_fwht_quant_act(G, U, inv_s, clip: float = 0.9, Xq=None, x_scale=None):
+    """G, U fp16 [M, K] -> codes and scales of silu(G) * U (smoothed, rotated, quantised)."""
+    _dev(G, torch.float16, "G"); _dev(U, torch.float16, "U")
+    M, K = U.shape
+    if tuple(G.shape) != (M, K):
+        raise ValueError("G and U must have the same shape")
+    Xq = torch.empty((M, K // 2), dtype=torch.uint8, device=U.device) if Xq is None else Xq
+    x_scale = torch.empty(M, dtype=torch.float32, device=U.device) if x_scale is None else x_scale
+    ldg = G.stride(0) if M > 1 else K
+    ldu = U.stride(0) if M > 1 else K
+    _check(raw().sr_swiglu_fwht_quant_act(_ptr(G), _ptr(U), M, K, ldg, ldu, _ptr(inv_s), clip, _ptr(Xq),
+                                          _ptr(x_scale), _stream()), "sr_swiglu_fwht_quant_act")
+    return Xq, x_scale
+
+
+def sr_fwht_quant_act_heads(X, n_heads: int, across: bool, inv_s, clip: float = 0.9, Xq=None, x_scale=None):
+    """X fp16 [M, K] -> codes and scales after the head-wise Hadamard transform."""
+    _dev(X, torch.float16, "X")
+    M, K = X.shape
+    Xq = torch.empty((M, K // 2), dtype=torch.uint8, device=X.device) if Xq is None else Xq
+    x_scale = torch.empty(M, dtype=torch.float32, device=X.device) if x_scale is None else x_scale
+    ldx = X.stride(0) if M > 1 else K
+    _check(raw().sr_fwht_quant_act_heads(_ptr(X), M, K, ldx, n_heads, int(bool(across)), _ptr(inv_s), clip,
+                                         _ptr(Xq), _ptr(x_scale), _stream()), "sr_fwht_quant_act_heads")
+    return Xq, x_scale
+
+
+def sr_fold_smooth_rotate_quant_ex(W, act_absmax, alpha: float, n_heads: int = 0, across: bool = False,
+                                   clip_steps: int = 1, clip_lo: float = 1.0,
+                                   Wq=None, w_scale=None, inv_s=None, w_ratio=None, workspace=None):
+    """W fp16 [K, N] -> (Wq, w_scale, inv_s, w_ratio fp32 [N])."""
+    _dev(W, torch.float16, "W")
+    K, N = W.shape
+    dev = W.device
+    Wq = torch.empty((N, K // 2), dtype=torch.uint8, device=dev) if Wq is None else Wq
+    w_scale = torch.empty(N, dtype=torch.float32, device=dev) if w_scale is None else w_scale
+    inv_s = torch.empty(K, dtype=torch.float32, device=dev) if inv_s is None else inv_s
+    w_ratio = torch.empty(N, dtype=torch.float32, device=dev) if w_ratio is None else w_ratio
+    if workspace is None:
+        workspace = torch.empty(max(sr_fold_workspace_bytes(K, N), 256), dtype=torch.uint8, device=dev)
+    _check(raw().sr_fold_smooth_rotate_quant_ex(_ptr(W), K, N, W.stride(0), _ptr(act_absmax), alpha, n_heads,
+                                                int(bool(across)), clip_steps, clip_lo, _ptr(Wq), _ptr(w_scale),
+                                                _ptr(inv_s), _ptr(w_ratio), _ptr(workspace), workspace.numel(),
+                                                _stream()),
+           "sr_fold_smooth_rotate_quant_ex")
+    return Wq, w_scale, inv_s, w_ratio
+
+
+def sr_kv_quant_asym(X, group: int = 128, clip: float = 0.95, Q=None, scale=None, zero=None):
+    """X fp16 [rows, D] -> (Q uint8 [rows, D/2], scale fp32 [rows, D/group], zero fp32 [rows, D/group])."""
+    _dev(X, torch.float16, "X")
+    rows, D = X.shape
+    ng = max(D // group, 1)
+    Q = torch.empty((rows, D // 2), dtype=torch.uint8, device=X.device) if Q is None else Q
+    scale = torch.empty((rows, ng), dtype=torch.float32, device=X.device) if scale is None else scale
+    zero = torch.empty((rows, ng), dtype=torch.float32, device=X.device) if zero is None else zero
+    ldx = X.stride(0) if rows > 1 else D
+    _check(raw().sr_kv_quant_asym(_ptr(X), rows, D, ldx, group, clip, _ptr(Q), _ptr(scale), _ptr(zero), _stream()),
+           "sr_kv_quant_asym")
+    return Q, scale, zero

@@ -148,6 +148,51 @@ __device__ __forceinline__ void lds_passes(float *row, int t, float &amax)
     }
 }
 
+// ---- the same passes with a run-time choice of index bits (head-wise transforms) ---------------
+// Bit b of `mask` set <=> the 2 x 2 factor on index bit b is applied; a clear bit leaves the
+// identity there.  The branches are uniform over the workgroup.
+template <int B>
+__device__ __forceinline__ void butterflies_masked(float (&v)[1 << B], uint32_t mask)
+{
+#pragma unroll
+    for (int h = 1; h < (1 << B); h <<= 1) {
+        if (mask & (uint32_t)h) {
+#pragma unroll
+            for (int i = 0; i < (1 << B); ++i) {
+                if (!(i & h)) {
+                    float a = v[i], b = v[i | h];
+                    v[i] = a + b;
+                    v[i | h] = a - b;
+                }
+            }
+        }
+    }
+}
+
+template <int K, int NT, int LO, int LOGP>
+__device__ __forceinline__ void lds_passes_masked(float *row, int t, uint32_t mask)
+{
+    if constexpr (LO < LOGP) {
+        constexpr int B = (LOGP - LO) >= 4 ? 4 : (LOGP - LO);
+        constexpr int E = 1 << B;
+        const uint32_t mb = (mask >> LO) & (uint32_t)(E - 1);
+        if (mb) {                                           // a pass with no selected bit is skipped whole
+            for (int g = t; g < (K >> B); g += NT) {
+                const int g_low = g & ((1 << LO) - 1);
+                const int base = ((g >> LO) << (LO + B)) | g_low;
+                float v[E];
+#pragma unroll
+                for (int e = 0; e < E; ++e) v[e] = row[pad(base + (e << LO))];
+                butterflies_masked<B>(v, mb);
+#pragma unroll
+                for (int e = 0; e < E; ++e) row[pad(base + (e << LO))] = v[e];
+            }
+            __syncthreads();
+        }
+        lds_passes_masked<K, NT, LO + B, LOGP>(row, t, mask);
+    }
+}
+
 // ---- quantise + pack eight values (shared by all kernels) ---------------------------------
 // t = fma(y, 1/Delta, 1.5 * 2^23) rounds y/Delta to the nearest-even integer in the low mantissa
 // bits (one rounding); the clamp to [-8, 7] is an integer median on those bits; the eight clamped
@@ -296,6 +341,157 @@ __global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict
 }
 
 // ------------------------------------------------------------------------------------------
+// Extended row kernel: the same rotation + quantiser with three optional extras
+//   gate       x = silu(gate) * X in fp32 before smoothing (the down-projection input of the gated
+//              FFN, paper Fig. 2: sigma(gate) (.) up, then 1/s, Hadamard, quantiser)
+//   had_mask   head-wise Hadamard: only the selected index bits are transformed (power-of-two K)
+//   grid       per-row clipping ratio by linear search over the squared quantisation error
+//              (paper, "Quantization" settings for the weights), first minimum in grid order
+// Kept apart from the plain kernel so that the hot path carries none of these branches.
+// ------------------------------------------------------------------------------------------
+template <int K, int NT>
+__global__ __launch_bounds__(NT) void fwht_quant_ex_kernel(const __half *__restrict__ X, int64_t ldx,
+                                                           const float *__restrict__ pre, float clip,
+                                                           float post_scale, uint8_t *__restrict__ Q,
+                                                           float *__restrict__ scale_out, const RowExtras ex)
+{
+    constexpr bool KRON = !is_pow2(K);
+    constexpr int P2 = KRON ? K / 28 : K;
+    constexpr int LOGP = ilog2(P2);
+    constexpr int NW = NT / 64;
+
+    extern __shared__ float row[];
+    __shared__ float red[NW];
+    __shared__ double err_w[kMaxClipGrid][NW];
+
+    const int t = threadIdx.x;
+    const int64_t m = blockIdx.x;
+    const __half *x = X + m * ldx;
+    const __half *gt = ex.gate ? ex.gate + m * ex.ldg : nullptr;
+    const uint32_t mask = KRON ? 0xFFFFFFFFu : ex.had_mask;
+
+    // ---- pass 1: bits 0..3 from global ------------------------------------------------
+    for (int g = t; g < K / 16; g += NT) {
+        union { uint4 u[2]; __half h[16]; } raw, graw;
+        raw.u[0] = *reinterpret_cast<const uint4 *>(x + 16 * g);
+        raw.u[1] = *reinterpret_cast<const uint4 *>(x + 16 * g + 8);
+        float v[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] = __half2float(raw.h[e]);
+        if (gt) {
+            graw.u[0] = *reinterpret_cast<const uint4 *>(gt + 16 * g);
+            graw.u[1] = *reinterpret_cast<const uint4 *>(gt + 16 * g + 8);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float gv = __half2float(graw.h[e]);
+                // silu(g) = g / (1 + exp(-g)); exp(-g) = inf for very negative g gives g * 0 = -0
+                v[e] *= gv * __builtin_amdgcn_rcpf(1.f + __expf(-gv));
+            }
+        }
+        if (pre) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 s = *reinterpret_cast<const float4 *>(pre + 16 * g + 4 * q);
+                v[4 * q + 0] *= s.x; v[4 * q + 1] *= s.y; v[4 * q + 2] *= s.z; v[4 * q + 3] *= s.w;
+            }
+        }
+        butterflies_masked<4>(v, mask & 15u);
+        float *dst = row + pad(16 * g);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<float4 *>(dst + 4 * q) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+    }
+    __syncthreads();
+
+    lds_passes_masked<K, NT, 4, LOGP>(row, t, mask);
+
+    if constexpr (KRON) {
+        for (int g = t; g < P2; g += NT) {
+            float v[28], o[28];
+            float S = 0.f;
+#pragma unroll
+            for (int i = 0; i < 28; ++i) {
+                v[i] = row[pad(g + i * P2)];
+                S += v[i];
+            }
+            h28_apply(v, o, S, std::make_integer_sequence<int, 28>{});
+#pragma unroll
+            for (int j = 0; j < 28; ++j) row[pad(g + j * P2)] = o[j];
+        }
+        __syncthreads();
+    }
+
+    // ---- row absmax (own sweep: the last transforming pass depends on the mask) -----------------
+    float amax = 0.f;
+    for (int c = t; c < K / 8; c += NT) {
+        const float *src = row + pad(8 * c);
+        const float4 a = *reinterpret_cast<const float4 *>(src);
+        const float4 b = *reinterpret_cast<const float4 *>(src + 4);
+        amax = fmaxf(amax, fmaxf(fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))),
+                                 fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w)))));
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+    if ((t & 63) == 0) red[t >> 6] = amax;
+    __syncthreads();
+    amax = red[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) amax = fmaxf(amax, red[w]);
+
+    // ---- clipping-ratio search: err_r = sum_j (y_j - Delta_r * code_r(y_j))^2 for every ratio -------
+    if (ex.n_grid > 0 && amax != 0.f) {
+        for (int i = 0; i < ex.n_grid; ++i) {
+            const float d = (ex.grid[i] * amax) / 7.f;
+            const float inv = 1.f / d;
+            double acc = 0.0;
+            for (int c = t; c < K / 8; c += NT) {
+                const float *src = row + pad(8 * c);
+                const float4 a = *reinterpret_cast<const float4 *>(src);
+                const float4 b = *reinterpret_cast<const float4 *>(src + 4);
+                const float y[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+                float part = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float code = fminf(fmaxf(rintf(y[e] * inv), -8.f), 7.f);
+                    const float r = fmaf(-d, code, y[e]);
+                    part = fmaf(r, r, part);
+                }
+                acc += (double)part;
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+            if ((t & 63) == 0) err_w[i][t >> 6] = acc;
+        }
+        __syncthreads();
+        double best = 0.0;
+        int best_i = 0;
+        for (int i = 0; i < ex.n_grid; ++i) {               // every thread takes the same decision
+            double e = 0.0;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) e += err_w[i][w];
+            if (i == 0 || e < best) { best = e; best_i = i; }
+        }
+        clip = ex.grid[best_i];
+    } else if (ex.n_grid > 0) {
+        clip = ex.grid[0];
+    }
+    if (ex.ratio_out && t == 0) ex.ratio_out[m] = clip;
+
+    const float delta = (amax == 0.f) ? 1.f : (clip * amax) / 7.f;
+    const float inv_delta = 1.f / delta;
+    if (t == 0) scale_out[m] = (amax == 0.f) ? 1.f : delta * post_scale;
+
+    uint32_t *q = reinterpret_cast<uint32_t *>(Q + m * (int64_t)(K / 2));
+    for (int c = t; c < K / 8; c += NT) {
+        const float *src = row + pad(8 * c);
+        const float4 a = *reinterpret_cast<const float4 *>(src);
+        const float4 b = *reinterpret_cast<const float4 *>(src + 4);
+        const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        q[c] = quant_pack8(v, inv_delta);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // K = 4096: one WAVE per row, no workgroup barriers.  A lane holds 64 fp32 values, so six index
 // bits are butterflied in registers at a time and only one transposition separates the two
 // halves of the transform:
@@ -392,6 +588,24 @@ hipError_t launch_one(const void *X, int64_t rows, int64_t ldx, const float *pre
     return hipGetLastError();
 }
 
+template <int K>
+hipError_t launch_one_ex(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip,
+                         float post_scale, uint8_t *Q, float *scale_out, const RowExtras &ex, hipStream_t st)
+{
+    constexpr int groups = K / 16;
+    constexpr int NT = groups >= 256 ? 256 : (groups >= 128 ? 128 : 64);
+    constexpr size_t lds = sizeof(float) * padded_len(K);
+    auto kern = fwht_quant_ex_kernel<K, NT>;
+    if (lds > 40 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)rows), dim3(NT), lds, st,
+                       static_cast<const __half *>(X), ldx, pre, clip, post_scale, Q, scale_out, ex);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_fwht_quant(const void *X, int64_t rows, int64_t K, int64_t ldx, const float *pre,
@@ -417,6 +631,20 @@ hipError_t launch_fwht_quant(const void *X, int64_t rows, int64_t K, int64_t ldx
         }
         return hipGetLastError();
     }
+    switch (K) {
+        SR_CASE(64) SR_CASE(128) SR_CASE(256) SR_CASE(512) SR_CASE(1024) SR_CASE(2048)
+        SR_CASE(4096) SR_CASE(8192) SR_CASE(16384) SR_CASE(32768)
+        SR_CASE(448) SR_CASE(896) SR_CASE(1792) SR_CASE(3584) SR_CASE(7168) SR_CASE(14336) SR_CASE(28672)
+        default: return hipErrorInvalidValue;
+    }
+#undef SR_CASE
+}
+
+hipError_t launch_fwht_quant_ex(const void *X, int64_t rows, int64_t K, int64_t ldx, const float *pre,
+                                float clip, float post_scale, uint8_t *Q, float *scale_out,
+                                const RowExtras &ex, hipStream_t st)
+{
+#define SR_CASE(KK) case KK: return launch_one_ex<KK>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, ex, st);
     switch (K) {
         SR_CASE(64) SR_CASE(128) SR_CASE(256) SR_CASE(512) SR_CASE(1024) SR_CASE(2048)
         SR_CASE(4096) SR_CASE(8192) SR_CASE(16384) SR_CASE(32768)

@@ -66,14 +66,27 @@ int sr_calib_absmax(const void *X_f16, int64_t T, int64_t K, int64_t ldx, float 
     return dev(sr::launch_calib_absmax(X_f16, T, K, ldx, absmax_io, static_cast<hipStream_t>(stream)));
 }
 
-int sr_fold_smooth_rotate_quant(const void *W_f16, int64_t K, int64_t N, int64_t ldw,
-                                const float *act_absmax, float alpha, float w_clip,
-                                uint8_t *Wq, float *w_scale, float *inv_s,
-                                void *workspace, size_t workspace_bytes, void *stream)
+// Index bits transformed by a head-wise Hadamard: K = n_heads * d seen as [n_heads, d].
+static uint32_t head_mask(int64_t K, int64_t n_heads, int across)
+{
+    const uint32_t low = (uint32_t)(K / n_heads) - 1u;       // bits of the position inside a head
+    return across ? ((uint32_t)K - 1u) & ~low : low;
+}
+static bool heads_ok(int64_t K, int64_t n_heads)
+{
+    return sr::is_pow2(K) && n_heads >= 1 && n_heads <= K && sr::is_pow2(n_heads);
+}
+
+static int fold_impl(const void *W_f16, int64_t K, int64_t N, int64_t ldw, const float *act_absmax, float alpha,
+                     int64_t n_heads, int across, int clip_steps, float clip_lo, bool extended,
+                     uint8_t *Wq, float *w_scale, float *inv_s, float *w_ratio,
+                     void *workspace, size_t workspace_bytes, void *stream)
 {
     if (K <= 0 || N <= 0 || N % 16 != 0 || ldw < N) return SR_ERR_SHAPE;
     if (!sr::hadamard_supported(K)) return SR_ERR_UNSUPPORTED_K;
-    if (!(alpha >= 0.f && alpha <= 1.f) || !(w_clip > 0.f && w_clip <= 1.f)) return SR_ERR_ARG;
+    if (!(alpha >= 0.f && alpha <= 1.f) || !(clip_lo > 0.f && clip_lo <= 1.f)) return SR_ERR_ARG;
+    if (clip_steps < 1 || clip_steps > sr::kMaxClipGrid || n_heads < 0) return SR_ERR_ARG;
+    if (n_heads > 0 && !heads_ok(K, n_heads)) return SR_ERR_ARG;
     if (!W_f16 || !Wq || !w_scale) return SR_ERR_NULL;
     if (ldw % 8 != 0 || !aligned16(W_f16) || !aligned16(Wq) || !aligned16(w_scale) ||
         (act_absmax && !aligned16(act_absmax)) || (inv_s && !aligned16(inv_s)))
@@ -92,11 +105,43 @@ int sr_fold_smooth_rotate_quant(const void *W_f16, int64_t K, int64_t N, int64_t
     if (act_absmax) e = sr::launch_row_absmax(W_f16, K, N, ldw, wmax, st);
     if (e == hipSuccess) e = sr::launch_smooth_factors(act_absmax, wmax, K, alpha, s, inv_s, st);
     if (e == hipSuccess) e = sr::launch_transpose_f16(W_f16, K, N, ldw, Wt, st);
+    if (e != hipSuccess) return dev(e);
     // rows of Wt are the columns of W: rotate (s * column) and quantise per output channel;
-    // the 1/K of H H^T = K I goes into the scale only (codes do not depend on it).
-    if (e == hipSuccess)
-        e = sr::launch_fwht_quant(Wt, N, K, K, s, w_clip, 1.0f / (float)K, Wq, w_scale, st);
-    return dev(e);
+    // the 1/order of H H^T = order * I goes into the scale only (codes do not depend on it).
+    if (!extended)
+        return dev(sr::launch_fwht_quant(Wt, N, K, K, s, clip_lo, 1.0f / (float)K, Wq, w_scale, st));
+    sr::RowExtras ex;
+    float order = (float)K;
+    if (n_heads > 0) {
+        ex.had_mask = head_mask(K, n_heads, across);
+        order = across ? (float)n_heads : (float)(K / n_heads);
+    }
+    if (clip_steps > 1) {
+        ex.n_grid = clip_steps;
+        for (int i = 0; i < clip_steps; ++i)
+            ex.grid[i] = (float)(1.0 - (1.0 - (double)clip_lo) * (double)i / (double)(clip_steps - 1));
+    }
+    ex.ratio_out = w_ratio;
+    return dev(sr::launch_fwht_quant_ex(Wt, N, K, K, s, clip_lo, 1.0f / order, Wq, w_scale, ex, st));
+}
+
+int sr_fold_smooth_rotate_quant(const void *W_f16, int64_t K, int64_t N, int64_t ldw,
+                                const float *act_absmax, float alpha, float w_clip,
+                                uint8_t *Wq, float *w_scale, float *inv_s,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    return fold_impl(W_f16, K, N, ldw, act_absmax, alpha, 0, 0, 1, w_clip, false, Wq, w_scale, inv_s, nullptr,
+                     workspace, workspace_bytes, stream);
+}
+
+int sr_fold_smooth_rotate_quant_ex(const void *W_f16, int64_t K, int64_t N, int64_t ldw,
+                                   const float *act_absmax, float alpha,
+                                   int64_t n_heads, int across, int clip_steps, float clip_lo,
+                                   uint8_t *Wq, float *w_scale, float *inv_s, float *w_ratio,
+                                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    return fold_impl(W_f16, K, N, ldw, act_absmax, alpha, n_heads, across, clip_steps, clip_lo, true, Wq, w_scale,
+                     inv_s, w_ratio, workspace, workspace_bytes, stream);
 }
 
 int sr_fwht_quant_act(const void *X_f16, int64_t M, int64_t K, int64_t ldx, const float *inv_s, float clip,
@@ -110,6 +155,53 @@ int sr_fwht_quant_act(const void *X_f16, int64_t M, int64_t K, int64_t ldx, cons
     if (ldx % 8 != 0 || !aligned16(X_f16) || !aligned16(Xq) || (inv_s && !aligned16(inv_s))) return SR_ERR_ALIGN;
     return dev(sr::launch_fwht_quant(X_f16, M, K, ldx, inv_s, clip, 1.0f, Xq, x_scale,
                                      static_cast<hipStream_t>(stream)));
+}
+
+int sr_swiglu_fwht_quant_act(const void *G_f16, const void *U_f16, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
+                             const float *inv_s, float clip, uint8_t *Xq, float *x_scale, void *stream)
+{
+    if (M < 0 || K <= 0 || ldg < K || ldu < K) return SR_ERR_SHAPE;
+    if (!sr::hadamard_supported(K)) return SR_ERR_UNSUPPORTED_K;
+    if (!(clip > 0.f && clip <= 1.f)) return SR_ERR_ARG;
+    if (M == 0) return SR_OK;
+    if (!G_f16 || !U_f16 || !Xq || !x_scale) return SR_ERR_NULL;
+    if (ldg % 8 != 0 || ldu % 8 != 0 || !aligned16(G_f16) || !aligned16(U_f16) || !aligned16(Xq) ||
+        (inv_s && !aligned16(inv_s)))
+        return SR_ERR_ALIGN;
+    sr::RowExtras ex;
+    ex.gate = static_cast<const __half *>(G_f16);
+    ex.ldg = ldg;
+    return dev(sr::launch_fwht_quant_ex(U_f16, M, K, ldu, inv_s, clip, 1.0f, Xq, x_scale, ex,
+                                        static_cast<hipStream_t>(stream)));
+}
+
+int sr_fwht_quant_act_heads(const void *X_f16, int64_t M, int64_t K, int64_t ldx, int64_t n_heads, int across,
+                            const float *inv_s, float clip, uint8_t *Xq, float *x_scale, void *stream)
+{
+    if (M < 0 || K <= 0 || ldx < K) return SR_ERR_SHAPE;
+    if (!sr::hadamard_supported(K) || !sr::is_pow2(K)) return SR_ERR_UNSUPPORTED_K;
+    if (!(clip > 0.f && clip <= 1.f) || !heads_ok(K, n_heads)) return SR_ERR_ARG;
+    if (M == 0) return SR_OK;
+    if (!X_f16 || !Xq || !x_scale) return SR_ERR_NULL;
+    if (ldx % 8 != 0 || !aligned16(X_f16) || !aligned16(Xq) || (inv_s && !aligned16(inv_s))) return SR_ERR_ALIGN;
+    sr::RowExtras ex;
+    ex.had_mask = head_mask(K, n_heads, across);
+    return dev(sr::launch_fwht_quant_ex(X_f16, M, K, ldx, inv_s, clip, 1.0f, Xq, x_scale, ex,
+                                        static_cast<hipStream_t>(stream)));
+}
+
+int sr_kv_quant_asym(const void *X_f16, int64_t rows, int64_t D, int64_t ldx, int64_t group, float clip,
+                     uint8_t *Q, float *scale, float *zero, void *stream)
+{
+    if (rows < 0 || D <= 0 || ldx < D) return SR_ERR_SHAPE;
+    if (group != 32 && group != 64 && group != 128 && group != 256 && group != 512) return SR_ERR_ARG;
+    if (D % group != 0) return SR_ERR_SHAPE;
+    if (!(clip > 0.f && clip <= 1.f)) return SR_ERR_ARG;
+    if (rows == 0) return SR_OK;
+    if (!X_f16 || !Q || !scale || !zero) return SR_ERR_NULL;
+    if (ldx % 8 != 0 || !aligned16(X_f16) || !aligned16(Q)) return SR_ERR_ALIGN;
+    return dev(sr::launch_kv_quant(X_f16, rows, D, ldx, group, clip, Q, scale, zero,
+                                   static_cast<hipStream_t>(stream)));
 }
 
 int sr_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, const float *w_scale,

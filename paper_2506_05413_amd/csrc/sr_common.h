@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
 #include <stdint.h>
 #include <stddef.h>
 
@@ -26,6 +27,21 @@ hipError_t launch_fwht_quant(const void *X_f16, int64_t rows, int64_t K, int64_t
                              const float *pre, float clip, float post_scale,
                              uint8_t *Q, float *scale_out, hipStream_t st);
 
+// Optional extras of the row kernel (see fwht_quant.hip).
+constexpr int kMaxClipGrid = 32;
+struct RowExtras {
+    const __half *gate = nullptr;   // x = silu(gate) * X when set; row stride ldg elements
+    int64_t ldg = 0;
+    uint32_t had_mask = 0xFFFFFFFFu; // index bits that are transformed (power-of-two K only)
+    int n_grid = 0;                  // > 0: search the clipping ratio per row over grid[0 .. n_grid)
+    float grid[kMaxClipGrid] = {};
+    float *ratio_out = nullptr;      // chosen ratio per row
+};
+
+hipError_t launch_fwht_quant_ex(const void *X_f16, int64_t rows, int64_t K, int64_t ldx,
+                                const float *pre, float clip, float post_scale,
+                                uint8_t *Q, float *scale_out, const RowExtras &ex, hipStream_t st);
+
 hipError_t launch_calib_absmax(const void *X_f16, int64_t T, int64_t K, int64_t ldx,
                                float *absmax_io, hipStream_t st);
 
@@ -40,6 +56,10 @@ hipError_t launch_smooth_factors(const float *act_absmax, const float *w_rowmax,
 // Wt[n][k] = W[k][n] (fp16 bits moved unchanged)
 hipError_t launch_transpose_f16(const void *W_f16, int64_t K, int64_t N, int64_t ldw,
                                 void *Wt_f16, hipStream_t st);
+
+// asymmetric 4-bit group quantiser (keys / values)
+hipError_t launch_kv_quant(const void *X_f16, int64_t rows, int64_t D, int64_t ldx, int64_t group, float clip,
+                           uint8_t *Q, float *scale, float *zero, hipStream_t st);
 
 hipError_t launch_gemm_prefill(const uint8_t *Xq, const float *xs, const uint8_t *Wq, const float *ws,
                                int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_i32,

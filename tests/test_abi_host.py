@@ -23,7 +23,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = declared_symbols()
-    assert len(names) == 8 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
+    assert len(names) == 12 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
     lib = ctypes.CDLL(sr.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -136,3 +136,59 @@ def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(ValueError):
         sr.sr_fwht_quant_act(torch.zeros(2, 64, dtype=torch.float16), None)
+
+
+def test_swiglu_rejects_bad_arguments():
+    f = sr.raw().sr_swiglu_fwht_quant_act
+    assert f(A, A, -1, 512, 512, 512, None, 0.9, A, A, None) == sr.SR_ERR_SHAPE
+    assert f(A, A, 4, 512, 256, 512, None, 0.9, A, A, None) == sr.SR_ERR_SHAPE      # ldg < K
+    assert f(A, A, 4, 512, 512, 256, None, 0.9, A, A, None) == sr.SR_ERR_SHAPE      # ldu < K
+    assert f(A, A, 4, 100, 104, 104, None, 0.9, A, A, None) == sr.SR_ERR_UNSUPPORTED_K
+    assert f(A, A, 4, 512, 512, 512, None, 0.0, A, A, None) == sr.SR_ERR_ARG
+    assert f(None, A, 4, 512, 512, 512, None, 0.9, A, A, None) == sr.SR_ERR_NULL
+    assert f(A, None, 4, 512, 512, 512, None, 0.9, A, A, None) == sr.SR_ERR_NULL
+    assert f(A + 2, A, 4, 512, 512, 512, None, 0.9, A, A, None) == sr.SR_ERR_ALIGN
+    assert f(A, A, 4, 512, 516, 512, None, 0.9, A, A, None) == sr.SR_ERR_ALIGN
+    assert f(None, None, 0, 512, 512, 512, None, 0.9, None, None, None) == sr.SR_OK
+
+
+def test_heads_rejects_bad_arguments():
+    f = sr.raw().sr_fwht_quant_act_heads
+    assert f(A, 4, 14336, 14336, 32, 1, None, 0.9, A, A, None) == sr.SR_ERR_UNSUPPORTED_K   # not a power of two
+    assert f(A, 4, 4096, 4096, 0, 1, None, 0.9, A, A, None) == sr.SR_ERR_ARG
+    assert f(A, 4, 4096, 4096, 24, 1, None, 0.9, A, A, None) == sr.SR_ERR_ARG
+    assert f(A, 4, 4096, 4096, 8192, 0, None, 0.9, A, A, None) == sr.SR_ERR_ARG
+    assert f(A, 4, 4096, 4096, 32, 1, None, 1.5, A, A, None) == sr.SR_ERR_ARG
+    assert f(A, 4, 4096, 2048, 32, 1, None, 0.9, A, A, None) == sr.SR_ERR_SHAPE
+    assert f(None, 4, 4096, 4096, 32, 1, None, 0.9, A, A, None) == sr.SR_ERR_NULL
+    assert f(None, 0, 4096, 4096, 32, 1, None, 0.9, None, None, None) == sr.SR_OK
+
+
+def test_fold_ex_rejects_bad_arguments():
+    f = sr.raw().sr_fold_smooth_rotate_quant_ex
+    need = sr.sr_fold_workspace_bytes(512, 64)
+    ok = (A, 512, 64, 64, A, 0.5)
+    out = (A, A, A, A, WS, need, None)
+    assert f(*ok, 0, 0, 0, 1.0, *out) == sr.SR_ERR_ARG            # clip_steps < 1
+    assert f(*ok, 0, 0, 33, 0.5, *out) == sr.SR_ERR_ARG           # clip_steps > 32
+    assert f(*ok, 0, 0, 21, 0.0, *out) == sr.SR_ERR_ARG           # clip_lo out of range
+    assert f(*ok, 24, 1, 1, 1.0, *out) == sr.SR_ERR_ARG           # n_heads not a power of two
+    assert f(*ok, -1, 1, 1, 1.0, *out) == sr.SR_ERR_ARG
+    assert f(A, 896, 64, 64, A, 0.5, 8, 1, 1, 1.0, A, A, A, A, WS, 1 << 30, None) == sr.SR_ERR_ARG   # heads need 2^p
+    assert f(*ok, 0, 0, 21, 0.5, A, A, A, A, WS, need - 1, None) == sr.SR_ERR_WORKSPACE
+    assert f(A, 512, 60, 64, A, 0.5, 0, 0, 1, 1.0, *out) == sr.SR_ERR_SHAPE
+    assert f(None, 512, 64, 64, A, 0.5, 0, 0, 1, 1.0, *out) == sr.SR_ERR_NULL
+
+
+def test_kv_quant_rejects_bad_arguments():
+    f = sr.raw().sr_kv_quant_asym
+    assert f(A, -1, 1024, 1024, 128, 0.95, A, A, A, None) == sr.SR_ERR_SHAPE
+    assert f(A, 4, 1024, 512, 128, 0.95, A, A, A, None) == sr.SR_ERR_SHAPE
+    assert f(A, 4, 1000, 1000, 128, 0.95, A, A, A, None) == sr.SR_ERR_SHAPE          # D % group
+    assert f(A, 4, 1024, 1024, 100, 0.95, A, A, A, None) == sr.SR_ERR_ARG
+    assert f(A, 4, 1024, 1024, 128, 0.0, A, A, A, None) == sr.SR_ERR_ARG
+    assert f(None, 4, 1024, 1024, 128, 0.95, A, A, A, None) == sr.SR_ERR_NULL
+    assert f(A, 4, 1024, 1024, 128, 0.95, A, None, A, None) == sr.SR_ERR_NULL
+    assert f(A + 4, 4, 1024, 1024, 128, 0.95, A, A, A, None) == sr.SR_ERR_ALIGN
+    assert f(A, 4, 1024, 1028, 128, 0.95, A, A, A, None) == sr.SR_ERR_ALIGN
+    assert f(None, 0, 1024, 1024, 128, 0.95, None, None, None, None) == sr.SR_OK

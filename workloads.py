@@ -68,6 +68,24 @@ def glu_acts(seed: int, M: int, K: int, n_out: int, out_scale: float,
     return to_f16_sat(x)
 
 
+def gate_up(seed: int, M: int, K: int, n_out: int, out_scale: float, stream: int = _S_X):
+    """(G, U) fp16 [M, K], both ~ N(0,1): the two branches of a gated FFN before the
+    non-linearity; n_out whole channels of U multiplied by out_scale (same draws as glu_acts)."""
+    a = _rng(seed, stream).standard_normal((M, K), dtype=np.float32)
+    b = _rng(seed, _S_B + 7919 * stream).standard_normal((M, K), dtype=np.float32)
+    if n_out:
+        b[:, outlier_channels(seed, K, n_out)] *= np.float32(out_scale)
+    return to_f16_sat(a), to_f16_sat(b)
+
+
+def kv_acts(seed: int, rows: int, D: int, stream: int = _S_X) -> np.ndarray:
+    """Key / value rows fp16 [rows, D]: N(0,1) entries plus a fixed per-channel offset
+    ~ N(0, 0.5^2) (keys carry channel biases, so groups are not centred on zero)."""
+    x = _rng(seed, stream).standard_normal((rows, D), dtype=np.float32)
+    x += np.float32(0.5) * _rng(seed, _S_CHANNELS + 50).standard_normal(D).astype(np.float32)[None, :]
+    return to_f16_sat(x)
+
+
 # --------------------------------------------------------------------------
 # The configurations (numbered as in the benchmark description, 1-based).
 # --------------------------------------------------------------------------
