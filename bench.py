@@ -207,6 +207,39 @@ def main():
         extra["decode_M1_14336x4096"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
                                          "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
         del copies, X3
+        # ---- rows around the core path -----------------------------------------------------------
+        # gated-FFN prologue fused into the K = 14336 rotation + quantiser (two fp16 inputs per value)
+        GU = [tuple(torch.from_numpy(a).to(dev) for a in wl.gate_up(2 + 10 * s, M, K3, 3, 800.0)) for s in range(3)]
+        t = graph_time(lambda i: sr.sr_swiglu_fwht_quant_act(GU[i % 3][0], GU[i % 3][1], None, CLIP, Xq3, xs3), 24)
+        b = M * K3 * 4.5 + M * 4
+        extra["swiglu_fwht_quant_K14336"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
+                                             "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+        del GU
+        # head-wise Hadamard (32 heads of 128, across heads) + quantiser on the benchmark activations
+        t = graph_time(lambda i: sr.sr_fwht_quant_act_heads(Xs[i % SETS], 32, True, inv_s, CLIP, Xq, xs), 64)
+        b = M * K * 2.5 + M * 4
+        extra["fwht_quant_heads32_K4096"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
+                                             "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+        # weight fold with the 21-point clipping-ratio search (offline)
+        Wf = torch.from_numpy(wl.cfg2_W(4096)).to(dev)
+        work = torch.empty(sr.sr_fold_workspace_bytes(K, 4096), dtype=torch.uint8, device=dev)
+        outs = sr.sr_fold_smooth_rotate_quant_ex(Wf, absmax, ALPHA, 0, False, 21, 0.5, workspace=work)
+        torch.cuda.synchronize()
+        t = ev_time(lambda i: sr.sr_fold_smooth_rotate_quant_ex(Wf, absmax, ALPHA, 0, False, 21, 0.5, *outs,
+                                                                workspace=work), 5)
+        extra["fold_clip_search21_N4096"] = {"us": round(t * 1e6, 1)}
+        del Wf, work, outs
+        # KV-cache quantiser: 32768 tokens x (8 KV heads x 128), asymmetric INT4, groups of 128, clip 0.95
+        RKV, DKV = 32768, 1024
+        KV = [torch.from_numpy(wl.kv_acts(5 + s, RKV, DKV)).to(dev) for s in range(5)]       # 5 x 67 MB
+        kq = torch.empty((RKV, DKV // 2), dtype=torch.uint8, device=dev)
+        ksc = torch.empty((RKV, DKV // 128), dtype=torch.float32, device=dev)
+        kze = torch.empty((RKV, DKV // 128), dtype=torch.float32, device=dev)
+        t = graph_time(lambda i: sr.sr_kv_quant_asym(KV[i % 5], 128, 0.95, kq, ksc, kze), 40)
+        b = RKV * DKV * (2.0 + 0.5 + 8.0 / 128)
+        extra["kv_quant_asym_32768x1024"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
+                                             "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+        del KV
 
     # ---------------- CPU baseline: the oracle on a bounded sample ------------------------
     cpu = None

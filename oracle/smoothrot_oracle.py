@@ -280,7 +280,8 @@ def swiglu(G: np.ndarray, U: np.ndarray) -> np.ndarray:
     """Input of the down-projection (Fig. 2, FFN block): sigma(gate) * up with
     sigma(g) = g / (1 + exp(-g)) (SiLU), elementwise, fp64."""
     g = np.asarray(G, dtype=np.float64)
-    return g / (1.0 + np.exp(-g)) * np.asarray(U, dtype=np.float64)
+    with np.errstate(over="ignore"):                 # exp(-g) = inf for very negative g: g / inf = -0
+        return g / (1.0 + np.exp(-g)) * np.asarray(U, dtype=np.float64)
 
 
 def fwht_quant_swiglu(G, U, inv_s, clip: float = 0.9):
