@@ -135,7 +135,7 @@ __device__ __forceinline__ void store_wave_tile(const v16i (&acc)[FN][FM], uint8
 
 constexpr int ROWB = 128;  // packed bytes per row per stage (256 codes = one 128-byte line)
 
-template <int BM, int BN, int WGM, int WGN, int STAGES>
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool SMOOTH = false>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_w4a4_kernel(
     const uint8_t *__restrict__ Xq, const float *__restrict__ xs, const uint8_t *__restrict__ Wq,
     const float *__restrict__ ws, int M, int N, int K, void *__restrict__ Yv, int64_t ldy, int out_i32,
@@ -147,7 +147,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_w4a4_kernel(
     constexpr int REGIONS = (BM + BN) / 8;           // 1 KB DMA regions (8 rows x 128 B) per stage
     constexpr int RPW = REGIONS / NWAVE;             // DMA instructions per wave per stage
     constexpr int X_BYTES = BM * ROWB, STAGE_BYTES = (BM + BN) * ROWB;
-    static_assert(REGIONS % NWAVE == 0 && NWAVE % 2 == 0 && WM % 32 == 0 && WN % 32 == 0 && RPW < 32, "tile");
+    static_assert(REGIONS % NWAVE == 0 && NWAVE % 2 == 0 && WM % 32 == 0 && WN % 32 == 0 && STAGES >= 2 &&
+                      (STAGES - 1) * RPW < 64, "tile");
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
@@ -261,12 +262,109 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_w4a4_kernel(
     Ops o0, o1;
     Frag fa, fb;                                     // fragments of even / odd sub-steps
     int slot = 0;
+    if constexpr (SMOOTH) {
+        // ---- smooth issue: memory instructions block the issuing wave while their queue is full, and with
+        // one wave per SIMD a blocked wave idles the matrix pipe.  So nothing is issued in bursts: a sub-step
+        // is cut into NREG regions of [FPR fragment reads, ~NM/NREG MFMAs with the widening of FPR fragments
+        // underneath, ONE DMA instruction].  The RPW DMA instructions of a stage are thereby spread over the
+        // four sub-steps that follow the barrier which frees their slot (ring of three slots: stage s+3 is
+        // issued from the middle of iteration s to the middle of iteration s+1 and first read after barrier s+2).
+        // With a ring of two slots the slot is needed again one stage later, so the stage is issued over the two
+        // sub-steps after the barrier only (more than one DMA instruction per region).
+        static_assert((STAGES == 3 || STAGES == 2) && (FM + FN) % 2 == 0, "smooth schedule");
+        constexpr int FPR = 2;                       // fragments per region
+        constexpr int NREG = (FM + FN) / FPR;        // regions per sub-step
+        constexpr int NR = (STAGES == 3 ? 4 : 2) * NREG;        // regions a stage's DMA is spread over
+        constexpr int DPR = (RPW + NR - 1) / NR;     // DMA instructions per region
+        constexpr int HALF = 2 * NREG * DPR < RPW ? 2 * NREG * DPR : RPW;   // ... issued in a stage's first two sub-steps
+        constexpr int NM = 2 * FM * FN;              // MFMAs per sub-step
+        auto region = [&](auto RC, auto PARTC, const Ops &cur, Ops &nxt, const Frag &wd, Frag &rd, int rslot, int p,
+                          int dstage, int dslot) {
+            constexpr int r = decltype(RC)::value, part = decltype(PARTC)::value;
+            constexpr int mlo = r * NM / NREG, mhi = (r + 1) * NM / NREG;
+            constexpr int per = (12 * FPR + (mhi - mlo) - 1) / (mhi - mlo);
+            __builtin_amdgcn_sched_barrier(0);
+            const uint8_t *st = smem + rslot * STAGE_BYTES + (((2 * p + fg) ^ fz) << 4);
+#pragma unroll
+            for (int q = r * FPR; q < (r + 1) * FPR; ++q) {
+                if (q < FM) rd.x[q < FM ? q : 0] = *reinterpret_cast<const uint4 *>(st + xrow + q * 32 * ROWB);
+                else rd.w[q < FM ? 0 : q - FM] = *reinterpret_cast<const uint4 *>(st + wrow + (q - FM) * 32 * ROWB);
+            }
+#pragma unroll
+            for (int m = mlo; m < mhi; ++m) {
+                const int h = m / (FM * FN), i = (m % (FM * FN)) / FM, j = m % FM;
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.w[i][h], cur.x[j][h], acc[i][j], 0, 0, 0);
+            }
+#pragma unroll
+            for (int q = r * FPR; q < (r + 1) * FPR; ++q) {
+                if (q < FM) widen(wd.x[q < FM ? q : 0], nxt.x[q < FM ? q : 0][0], nxt.x[q < FM ? q : 0][1]);
+                else widen(wd.w[q < FM ? 0 : q - FM], nxt.w[q < FM ? 0 : q - FM][0], nxt.w[q < FM ? 0 : q - FM][1]);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x100, FPR, 0);
+#pragma unroll
+            for (int k = mlo; k < mhi; ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, per, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            constexpr int g = part * NREG + r;       // ordinal of this region among those that issue DMA
+            if constexpr (g < NR) {
+#pragma unroll
+                for (int idx = g * DPR; idx < (g + 1) * DPR && idx < RPW; ++idx)
+                    dma16((idx < XI ? Xq : Wq) + (int64_t)dstage * ROWB, goff[idx],
+                          smem_base + (uint32_t)dslot * STAGE_BYTES + wave * 1024 + NWAVE * idx * 1024);
+            }
+        };
+        auto ssub = [&](auto PARTC, const Ops &cur, Ops &nxt, const Frag &wd, Frag &rd, int rslot, int p, int dstage,
+                        int dslot) {
+            region(std::integral_constant<int, 0>{}, PARTC, cur, nxt, wd, rd, rslot, p, dstage, dslot);
+            if constexpr (NREG >= 2) region(std::integral_constant<int, 1>{}, PARTC, cur, nxt, wd, rd, rslot, p, dstage, dslot);
+            if constexpr (NREG >= 3) region(std::integral_constant<int, 2>{}, PARTC, cur, nxt, wd, rd, rslot, p, dstage, dslot);
+            if constexpr (NREG >= 4) region(std::integral_constant<int, 3>{}, PARTC, cur, nxt, wd, rd, rslot, p, dstage, dslot);
+            static_assert(NREG <= 4, "regions");
+        };
+        constexpr std::integral_constant<int, 0> P0{};
+        constexpr std::integral_constant<int, 1> P1{};
+        constexpr std::integral_constant<int, 2> P2{};
+        constexpr std::integral_constant<int, 3> P3{};
+        // prologue: stages 0 and 1 whole and, with three slots, the first half of stage 2
+        issue(0);
+        issue(ns > 1 ? 1 : 0);
+        if constexpr (STAGES == 3) {
+            const int st2 = ns > 2 ? 2 : ns - 1;
+#pragma unroll
+            for (int i = 0; i < HALF; ++i)
+                dma16((i < XI ? Xq : Wq) + (int64_t)st2 * ROWB, goff[i],
+                      smem_base + 2u * STAGE_BYTES + wave * 1024 + NWAVE * i * 1024);
+            wait_vmcnt<RPW + HALF>();                // stage 0 has landed
+        } else {
+            wait_vmcnt<RPW>();
+        }
+        barrier_nofence();
+        load_frags(fa, 0, 0);
+        load_frags(fb, 0, 1);
+        widen_all(fa, o0);
+        for (int s = 0; s < ns; ++s) {
+            const int nslot = slot == STAGES - 1 ? 0 : slot + 1, pslot = slot == 0 ? STAGES - 1 : slot - 1;
+            const int st2 = s + 2 < ns ? s + 2 : ns - 1, st3 = s + 3 < ns ? s + 3 : ns - 1;
+            // three slots: second half of stage s+2 -> slot of stage s-1; two slots: these sub-steps issue nothing
+            ssub(P2, o0, o1, fb, fa, slot, 2, st2, pslot);
+            ssub(P3, o1, o0, fa, fb, slot, 3, st2, pslot);
+            // stage s+1 must have landed (with three slots stage s+2, the youngest RPW instructions, may still fly),
+            // and every wave's reads of stage s must have returned: its slot takes stage s+STAGES from here on
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(STAGES == 3 ? RPW : 0) : "memory");
+            barrier_nofence();
+            ssub(P0, o0, o1, fb, fa, nslot, 0, STAGES == 3 ? st3 : st2, slot);
+            ssub(P1, o1, o0, fa, fb, nslot, 1, STAGES == 3 ? st3 : st2, slot);
+            slot = nslot;
+        }
+    } else {
     // Every stage runs the same branch-free body.  Past the end of K the pipeline keeps reading (stale,
     // in-bounds) LDS and re-fetching the last stage; those fragments are widened but never multiplied.
     // ---- prologue: two stages in flight; operands of sub-step 0 and fragments of sub-step 1 in registers
-    issue(0);
-    issue(ns > 1 ? 1 : 0);
-    wait_vmcnt<RPW>();
+#pragma unroll
+    for (int q = 0; q < STAGES; ++q) issue(q < ns ? q : ns - 1);
+    wait_vmcnt<(STAGES - 1) * RPW>();                // stage 0 has landed, the younger ones may still fly
     barrier_nofence();
     load_frags(fa, 0, 0);
     load_frags(fb, 0, 1);
@@ -275,15 +373,16 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_w4a4_kernel(
         const int nslot = slot == STAGES - 1 ? 0 : slot + 1;
         sub(yes, yes, o0, o1, fb, fa, slot, 2);
         sub(yes, yes, o1, o0, fa, fb, slot, 3);
-        // stage s+1 (issued one stage ago) must have landed for every wave, and every wave's LDS reads of
-        // stage s (the last ones were issued a sub-step ago) must have returned: its slot takes stage s+2
-        // when the ring has two slots (the slot of stage s-1 when it has three)
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        // stage s+1 (issued STAGES-1 stages ago) must have landed for every wave -- the STAGES-2 younger
+        // stages may stay in flight -- and every wave's LDS reads of stage s (the last ones were issued a
+        // sub-step ago) must have returned: its slot now takes stage s+STAGES
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((STAGES - 2) * RPW) : "memory");
         barrier_nofence();
-        issue(s + 2 < ns ? s + 2 : ns - 1);
+        issue(s + STAGES < ns ? s + STAGES : ns - 1);
         sub(yes, yes, o0, o1, fb, fa, nslot, 0);
         sub(yes, yes, o1, o0, fa, fb, nslot, 1);
         slot = nslot;
+    }
     }
     wait_vmcnt<0>();                                 // no LDS-DMA write may outlive the workgroup
 
@@ -294,11 +393,11 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_w4a4_kernel(
                             Yv, ldy, out_i32);
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES = 2>
+template <int BM, int BN, int WGM, int WGN, int STAGES = 2, bool SMOOTH = false>
 hipError_t launch_tile(const uint8_t *Xq, const float *xs, const uint8_t *Wq, const float *ws, int64_t M, int64_t N,
                        int64_t K, void *Y, int64_t ldy, int out_i32, hipStream_t st)
 {
-    auto kern = gemm_w4a4_kernel<BM, BN, WGM, WGN, STAGES>;
+    auto kern = gemm_w4a4_kernel<BM, BN, WGM, WGN, STAGES, SMOOTH>;
     constexpr int lds = STAGES * (BM + BN) * ROWB;
     static_assert(lds <= 160 * 1024, "LDS");
     if (lds > 48 * 1024) {
@@ -488,17 +587,29 @@ hipError_t launch_gemm_prefill(const uint8_t *Xq, const float *xs, const uint8_t
         case 3: return launch_tile<128, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
         case 5: return launch_tile<256, 128, 4, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
         case 6: return launch_tile<256, 128, 2, 2, 3>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+        case 7: return launch_tile<128, 128, 2, 2, 3>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+        case 10: return launch_tile<256, 128, 2, 2, 3, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+        case 11: return launch_tile<128, 128, 2, 2, 3, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+        case 12: return launch_tile<256, 128, 4, 2, 3, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+        case 13: return launch_tile<256, 128, 4, 2, 3>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+        case 14: return launch_tile<128, 128, 2, 2, 2, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+        case 15: return launch_tile<256, 128, 4, 2, 2, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+        case 8: return launch_tile<128, 128, 2, 2, 4>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
         default: break;
     }
-    // One 144 KB workgroup owns a CU, so a launch takes ceil(tiles / 256) rounds of one tile time each
-    // (tile time ~ BM * BN).  Pick the tile shape with the cheapest schedule; ties go to the larger tile.
+    // A launch takes about ceil(tiles / 256) rounds of one tile time each (tile time ~ BM * BN): pick the tile
+    // shape with the cheapest schedule; ties go to the larger tile (less L2 traffic, fewer fragment reads).
+    //   256 x 128: eight waves (two per SIMD, so that one can issue MFMAs while the other is held up issuing
+    //              LDS or DMA instructions), 96 KB of LDS, one workgroup per CU
+    //   128 x 128: four waves, 64 KB of LDS, two workgroups per CU
+    // both with the smooth (burst-free) instruction schedule and a ring of two stages.
     auto cost = [&](int64_t bm, int64_t bn) {
         const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
         return ((tiles + 255) / 256) * bm * bn;
     };
     const int64_t c256 = cost(256, 128), c128 = cost(128, 128);
-    if (c256 <= c128) return launch_tile<256, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-    return launch_tile<128, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+    if (c256 <= c128) return launch_tile<256, 128, 4, 2, 2, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+    return launch_tile<128, 128, 2, 2, 2, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
 }
 
 }  // namespace sr
