@@ -16,22 +16,32 @@
 // are widened by the same three instructions from the same byte offsets.
 //
 // What the main kernel is built around (all measured on MI355X):
-//  * v_mfma_i32_32x32x32_i8 (8 passes) lets vector-ALU instructions of the same wave issue
-//    underneath it, v_mfma_i32_16x16x64_i8 (4 passes) does not: with the 32x32x32 form the
-//    widening (4.5 ALU instructions per MFMA here) costs no MFMA time, and one wave per SIMD
-//    already saturates the matrix pipe.
-//  * L2 -> CU bandwidth is the scarce resource, not LDS or ALU: both operands stay packed
-//    (4 bit) all the way into LDS, and every global access fetches whole 128-byte lines
-//    (256 codes per row per stage) -- half-line fetches were re-fetched from L2 each time.
-//  * Global -> LDS copies use the LDS-DMA form of the global load (no staging registers),
-//    a ring of two stages of 256 codes; per 64 codes a register-level software pipeline
-//    (LDS reads for t+2, widening for t+1, MFMAs for t).  One barrier per stage.
+//  * v_mfma_i32_32x32x32_i8 (8 passes, 32 cycles of the matrix pipe) lets vector-ALU instructions
+//    of the same wave issue underneath it; v_mfma_i32_16x16x64_i8 (4 passes) does not.  The
+//    widening (4.5 - 6 ALU instructions per MFMA) therefore costs little MFMA time.
+//  * Memory instructions hold up the wave that issues them (an LDS-DMA load ~50 cycles, a
+//    ds_read_b128 ~25), and with one wave per SIMD a held-up wave idles the matrix pipe: timed
+//    per stage, DMA and fragment reads ADD to the MFMA time instead of hiding under it.  Hence
+//    (a) two waves per SIMD -- eight waves on a 256 x 128 tile, or two four-wave workgroups of
+//    128 x 128 per CU -- and (b) no bursts: a 64-code sub-step is cut into regions of
+//    [2 fragment reads, 4-5 MFMAs with the widening of 2 fragments underneath, 1-2 DMA
+//    instructions], the DMA of a stage being spread over the sub-steps after the barrier that
+//    frees its ring slot.
+//  * Both operands stay packed (4 bit) all the way into LDS, and every global access fetches
+//    whole 128-byte lines (256 codes per row per stage) -- half-line fetches were re-fetched
+//    from L2 each time, an int8 copy of X doubled its traffic and was slower.
+//  * Global -> LDS copies use the LDS-DMA form of the global load (no staging registers) into a
+//    ring of two stages of 256 codes; one barrier per stage; per 64 codes a register-level
+//    software pipeline (LDS reads for t+2, widening for t+1, MFMAs for t).
 //  * The epilogue transposes each wave tile through the idle LDS ring and stores whole rows:
 //    8-byte stores scattered over 32 rows per instruction cost 14 us per tile, this costs ~5.
 //  * LDS rows are XOR-swizzled in 16-byte chunks (applied on the global side of the DMA,
-//    which fills LDS linearly) so that every 16-byte fragment read is bank-conflict free.
+//    which fills LDS linearly): ds_read_b128 of a fragment runs at the full LDS rate
+//    (240 B/clk/CU measured with eight waves; one wave alone reaches 33 B/clk).
 //  * MFMA operand roles are swapped (A = weight rows, B = token rows): a lane then owns 4
 //    consecutive output channels of one token per accumulator quad = one 8-byte store.
+//  * Tried and dropped: deeper DMA prefetch (three ring slots: DMA latency is already hidden),
+//    dedicated DMA-issuing waves (1, 2 or 4 per workgroup: slower, a wave issues DMA too slowly).
 //
 // K % 256 != 0 (and any K % 64 == 0) runs on a simpler register-staged kernel further down.
 #include "sr_common.h"
@@ -582,19 +592,12 @@ hipError_t launch_gemm_prefill(const uint8_t *Xq, const float *xs, const uint8_t
         return hipGetLastError();
     }
     switch (variant) {
-        case 1: return launch_tile<256, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-        case 2: return launch_tile<128, 256, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-        case 3: return launch_tile<128, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-        case 5: return launch_tile<256, 128, 4, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-        case 6: return launch_tile<256, 128, 2, 2, 3>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-        case 7: return launch_tile<128, 128, 2, 2, 3>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-        case 10: return launch_tile<256, 128, 2, 2, 3, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-        case 11: return launch_tile<128, 128, 2, 2, 3, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-        case 12: return launch_tile<256, 128, 4, 2, 3, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-        case 13: return launch_tile<256, 128, 4, 2, 3>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+        case 1: return launch_tile<256, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);               // burst schedule
+        case 3: return launch_tile<128, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);               // burst schedule
+        case 10: return launch_tile<256, 128, 2, 2, 3, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);     // 4 waves, 3 slots
+        case 12: return launch_tile<256, 128, 4, 2, 3, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);     // 8 waves, 3 slots
         case 14: return launch_tile<128, 128, 2, 2, 2, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
         case 15: return launch_tile<256, 128, 4, 2, 2, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-        case 8: return launch_tile<128, 128, 2, 2, 4>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
         default: break;
     }
     // A launch takes about ceil(tiles / 256) rounds of one tile time each (tile time ~ BM * BN): pick the tile
