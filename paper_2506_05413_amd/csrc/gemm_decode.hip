@@ -5,16 +5,14 @@
 // packed weights once from HBM.  No scratch memory, no atomics: partial sums are integers,
 // reduced on chip (order-free, exact).
 //
-//  M <= 4   gemm_decode_dot_kernel: v_dot8_i32_i4 multiplies eight packed 4-bit codes of W
+//  M <= 2   gemm_decode_dot_kernel: v_dot8_i32_i4 multiplies eight packed 4-bit codes of W
 //           with eight of X directly -- no widening at all.  Eight lanes read one whole
 //           128-byte line of a weight row (measured: 5.7 us for the 29 MB of a 4096 x 14336
 //           weight against 6.9 us when an instruction touches 16 rows x 64 bytes); a
-//           workgroup owns 8..32 output channels, its waves take interleaved 128-byte slabs of K.
-//           (Beyond 4 tokens the M dot products per weight dword cost more than the MFMA path.)
-//  M <= 16  gemm_decode_kernel: one workgroup owns 16 output channels; its waves split K,
-//           issue all their 16-byte weight loads up front and multiply on the int8 MFMA with
-//           the <= 16 token rows as the second operand (the MFMA needs lane = row mod 16,
-//           hence the 64-byte pieces).
+//           workgroup owns 8..16 output channels, its waves take interleaved 128-byte slabs of K.
+//           (The M dot products per weight dword make it lose to the MFMA kernel from 3 tokens on.)
+//  M <= 16  gemm_decode_kernel: int8 MFMA 16x16x64 with operand rows re-interpreted so that
+//           weights and activations are both loaded as whole lines (see the kernel).
 #include "sr_common.h"
 
 #include <hip/hip_fp16.h>
@@ -35,79 +33,110 @@ __device__ __forceinline__ void unpack16(const u32x4 w, v4i &a0, v4i &a1)
 }
 
 constexpr int SLAB = 128;    // packed bytes per row per slab (256 codes)
-constexpr int UNR = 4;       // slabs in flight per wave iteration
 
-template <int NW>
+// ------------------------------------------------------------------------------------------
+// MFMA kernel for up to 8 * SETS tokens, every load a whole 128-byte line per row.
+// v_mfma_i32_16x16x64_i8 wants lane l to hold 16 bytes of operand row (l & 15); loading that
+// layout directly touches 16 rows x 64 bytes per instruction, and the two half-line requests
+// of a row are not merged on their way to L2 (three times the L2 requests of the data).  So
+// an operand "row" i of the MFMA is used as (real row i & 7, K half i >> 3): lane
+// (i = l & 15, g = l >> 4) loads the 16-byte chunk 4 (i >> 3) + g of row (i & 7) -- 8 rows x
+// 128 bytes per instruction, for the weights and for the activations alike.  Of the 16 x 16
+// products only the two diagonal 8 x 8 blocks (same K half on both sides) mean anything; the
+// matrix pipe has time to spare here.  The result of (channel r, token t) is the sum of the
+// accumulator entries [r][t] and [r + 8][t + 8], taken when the waves' partial sums are
+// reduced through LDS.  G groups of 16 output channels share the activation fragments.
+// ------------------------------------------------------------------------------------------
+template <int NW, int G, int SETS, int UNR>
 __global__ __launch_bounds__(NW * 64) void gemm_decode_kernel(const uint8_t *__restrict__ Xq, const float *__restrict__ xs,
                                                               const uint8_t *__restrict__ Wq, const float *__restrict__ ws,
                                                               int M, int N, int K, void *__restrict__ Yv, int64_t ldy,
                                                               int out_i32)
 {
-    __shared__ int red[NW][4][64];
+    constexpr int NA = 2 * G;                               // weight row sets of 8 channels
+    __shared__ int red[NW][NA][SETS][4][16];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int fr = lane & 15, fg = lane >> 4;
-    const int n0 = blockIdx.x * 16;
+    const int r8 = lane & 7, kh = (lane >> 3) & 1, fg = lane >> 4;
+    const int chunk = (4 * kh + fg) * 16;                   // byte offset of this lane's chunk inside a slab
+    const int n0 = blockIdx.x * (16 * G);
     const int Kb = K >> 1;
     const int nslab = (Kb + SLAB - 1) / SLAB;
 
-    const uint8_t *wrow = Wq + (int64_t)(n0 + fr) * Kb + fg * 16;
-    const bool xrow_ok = fr < M;
-    const uint8_t *xrow = Xq + (int64_t)(xrow_ok ? fr : 0) * Kb + fg * 16;
+    const uint8_t *wrow[NA];
+#pragma unroll
+    for (int a = 0; a < NA; ++a) {
+        int n = n0 + 8 * a + r8;
+        n = n < N ? n : N - 1;                             // a ragged last workgroup re-reads the last row
+        wrow[a] = Wq + (int64_t)n * Kb + chunk;
+    }
+    const uint8_t *xrow[SETS];
+    bool xok[SETS];
+#pragma unroll
+    for (int b = 0; b < SETS; ++b) {
+        xok[b] = 8 * b + r8 < M;
+        xrow[b] = Xq + (int64_t)(xok[b] ? 8 * b + r8 : 0) * Kb + chunk;
+    }
 
-    v4i acc = {0, 0, 0, 0};
+    v4i acc[NA][SETS];
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int b = 0; b < SETS; ++b) acc[a][b] = v4i{0, 0, 0, 0};
     const u32x4 zero = {0u, 0u, 0u, 0u};
 
     for (int s0 = wave * UNR; s0 < nslab; s0 += NW * UNR) {
-        u32x4 w[UNR][2], x[UNR][2];
+        u32x4 w[UNR][NA], x[UNR][SETS];
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
+            const int off = (s0 + u) * SLAB;
+            const bool ok = (s0 + u) < nslab && off + chunk < Kb;      // K % 256 != 0: the last slab is half empty
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int off = (s0 + u) * SLAB + h * 64;          // byte offset of this lane's chunk - fg*16
-                const bool ok = (s0 + u) < nslab && off + fg * 16 < Kb;
-                w[u][h] = ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wrow + off)) : zero;
-                x[u][h] = (ok && xrow_ok) ? *reinterpret_cast<const u32x4 *>(xrow + off) : zero;
-            }
+            for (int a = 0; a < NA; ++a)
+                w[u][a] = ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wrow[a] + off)) : zero;
+#pragma unroll
+            for (int b = 0; b < SETS; ++b)
+                x[u][b] = (ok && xok[b]) ? *reinterpret_cast<const u32x4 *>(xrow[b] + off) : zero;
         }
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
+            v4i xa0[SETS], xa1[SETS];
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                v4i wa0, wa1, xa0, xa1;
-                unpack16(w[u][h], wa0, wa1);
-                unpack16(x[u][h], xa0, xa1);
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa0, xa0, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa1, xa1, acc, 0, 0, 0);
+            for (int b = 0; b < SETS; ++b) unpack16(x[u][b], xa0[b], xa1[b]);
+#pragma unroll
+            for (int a = 0; a < NA; ++a) {
+                v4i wa0, wa1;
+                unpack16(w[u][a], wa0, wa1);
+#pragma unroll
+                for (int b = 0; b < SETS; ++b) {
+                    acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa0, xa0[b], acc[a][b], 0, 0, 0);
+                    acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa1, xa1[b], acc[a][b], 0, 0, 0);
+                }
             }
         }
     }
 
+    // accumulator entry [i][j] sits in lane (j, i >> 2), register i & 3.  Output (channel 8 a + r, token 8 b + t)
+    // = entries [r][t] + [r + 8][t + 8]: lane t + 16 (r >> 2) and the lane 40 above it.
 #pragma unroll
-    for (int v = 0; v < 4; ++v) red[wave][v][lane] = acc[v];
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int b = 0; b < SETS; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int both = acc[a][b][v] + __shfl(acc[a][b][v], (lane + 40) & 63, 64);
+                if (lane < 32 && !(lane & 8)) red[wave][a][b][v][(lane & 7) + 8 * (lane >> 4)] = both;
+            }
     __syncthreads();
-    if (wave != 0) return;
+    for (int o = threadIdx.x; o < NA * SETS * 64; o += NW * 64) {
+        const int t = o & 7, r = (o >> 3) & 7, ab = o >> 6, b = ab % SETS, a = ab / SETS;
+        const int m = 8 * b + t, n = n0 + 8 * a + r;
+        if (m >= M || n >= N) continue;
+        int sum = 0;
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        int s = 0;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) s += red[w][v][lane];
-        acc[v] = s;
-    }
-    // lane owns token m = fr, output channels n0 + 4*fg .. +3
-    const int m = fr, n = n0 + fg * 4;
-    if (m >= M) return;
-    if (out_i32) {
-        *reinterpret_cast<int4 *>(static_cast<int32_t *>(Yv) + (int64_t)m * ldy + n) =
-            make_int4(acc[0] >> 8, acc[1] >> 8, acc[2] >> 8, acc[3] >> 8);
-    } else {
-        const float sx = xs[m] * (1.f / 256.f);
-        const float4 sw = *reinterpret_cast<const float4 *>(ws + n);
-        union { __half h[4]; uint2 u; } o;
-        o.h[0] = __float2half_rn((float)acc[0] * sx * sw.x);
-        o.h[1] = __float2half_rn((float)acc[1] * sx * sw.y);
-        o.h[2] = __float2half_rn((float)acc[2] * sx * sw.z);
-        o.h[3] = __float2half_rn((float)acc[3] * sx * sw.w);
-        *reinterpret_cast<uint2 *>(static_cast<__half *>(Yv) + (int64_t)m * ldy + n) = o.u;
+        for (int w = 0; w < NW; ++w) sum += red[w][a][b][r & 3][t + 8 * (r >> 2)];
+        sum >>= 8;                                         // both operands carried the factor 16
+        if (out_i32) static_cast<int32_t *>(Yv)[(int64_t)m * ldy + n] = sum;
+        else static_cast<__half *>(Yv)[(int64_t)m * ldy + n] = __float2half_rn((float)sum * xs[m] * ws[n]);
     }
 }
 
@@ -213,22 +242,26 @@ hipError_t launch_dot(const uint8_t *Xq, const float *xs, const uint8_t *Wq, con
 hipError_t launch_gemm_decode(const uint8_t *Xq, const float *xs, const uint8_t *Wq, const float *ws,
                               int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_i32, hipStream_t st)
 {
+    // measured (4096 -> 14336): dot kernel 6.2 / 7.1 / 8.4 us for M = 1 / 2 / 3, MFMA kernel 7.5 - 7.9 us for M <= 4
     if (M <= 1) return launch_dot<1, 4, 1>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
     if (M <= 2) return launch_dot<2, 4, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-    if (M <= 4) {
-        // row groups per workgroup: reuse of the X chunks against enough workgroups to fill 256 CUs
-        if (N >= 32 * 400) return launch_dot<4, 2, 4>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-        if (N >= 16 * 400) return launch_dot<4, 4, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-        return launch_dot<4, 4, 1>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+    // groups of 16 channels per workgroup: two (activation fragments shared) once there are many tokens and
+    // still a few workgroups per CU
+    const int64_t groups = N / 16;
+    const int G = (M >= 8 && groups >= 800) ? 2 : 1;
+    const unsigned blocks = (unsigned)((groups + G - 1) / G);
+#define SR_DEC(NW, GG, SS, UU)                                                                                           \
+    hipLaunchKernelGGL((gemm_decode_kernel<NW, GG, SS, UU>), dim3(blocks), dim3(NW * 64), 0, st, Xq, xs, Wq, ws, (int)M, \
+                       (int)N, (int)K, Y, ldy, out_i32)
+    // enough waves per workgroup that a wave has most of its K range in flight at once
+    if (K >= 8192) {
+        if (M <= 8) { if (G == 2) SR_DEC(8, 2, 1, 4); else SR_DEC(8, 1, 1, 4); }
+        else { if (G == 2) SR_DEC(8, 2, 2, 2); else SR_DEC(8, 1, 2, 4); }
+    } else {
+        if (M <= 8) { if (G == 2) SR_DEC(4, 2, 1, 4); else SR_DEC(4, 1, 1, 4); }
+        else { if (G == 2) SR_DEC(4, 2, 2, 2); else SR_DEC(4, 1, 2, 4); }
     }
-    const unsigned blocks = (unsigned)(N / 16);
-    // enough waves per block that a wave streams ~2 KB of its 16 rows' K range at once
-    if (K >= 8192)
-        hipLaunchKernelGGL(gemm_decode_kernel<8>, dim3(blocks), dim3(512), 0, st, Xq, xs, Wq, ws, (int)M, (int)N,
-                           (int)K, Y, ldy, out_i32);
-    else
-        hipLaunchKernelGGL(gemm_decode_kernel<4>, dim3(blocks), dim3(256), 0, st, Xq, xs, Wq, ws, (int)M, (int)N,
-                           (int)K, Y, ldy, out_i32);
+#undef SR_DEC
     return hipGetLastError();
 }
 

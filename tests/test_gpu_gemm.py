@@ -30,6 +30,7 @@ def gpu_gemm(sr, cx, cw, xs=None, ws=None, dtype=None, ldy=None):
 
 
 SHAPES = [(1, 16, 64), (4, 48, 128), (2, 32, 448), (5, 80, 4096), (8, 4096, 4096), (7, 16, 14336), (9, 32, 576), (16, 512, 512), (16, 4096, 4096), (3, 64, 14336), (16, 256, 448),
+          (3, 16, 64), (12, 48, 192), (9, 12816, 512), (16, 12816, 576), (6, 12816, 256),
           (17, 16, 64), (33, 48, 192), (100, 144, 448), (128, 128, 128), (129, 272, 576), (300, 1040, 512),
           (257, 400, 4096), (64, 128, 14336)]
 
