@@ -182,6 +182,21 @@ def main():
             b = 14336 * K / 2 + Md * K / 2 + 2 * Md * 14336
             extra["decode_M%d_4096x14336" % Md] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
                                                     "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+        # one token, whole online path: rotation + quantiser + GEMM as two calls and as the single fused launch
+        Xd = Xs[0][:1].contiguous()
+        xq_d = torch.empty((1, K // 2), dtype=torch.uint8, device=dev)
+        xs_d = torch.empty(1, dtype=torch.float32, device=dev)
+        Yd = torch.empty((1, 14336), dtype=torch.float16, device=dev)
+
+        def two_calls(i):
+            sr.sr_fwht_quant_act(Xd, inv_s, CLIP, xq_d, xs_d)
+            sr.sr_w4a4_gemm(xq_d, xs_d, copies[i % 20], wsc, sr.SR_F16, Yd)
+        t2 = graph_time(two_calls, 100)
+        t1 = graph_time(lambda i: sr.sr_w4a4_linear_decode(Xd, inv_s, copies[i % 20], wsc, CLIP, Yd), 100)
+        b = 14336 * K / 2 + K * 2 + 2 * 14336
+        extra["decode_M1_4096x14336_whole_path"] = {"two_calls_us": round(t2 * 1e6, 2), "one_launch_us": round(t1 * 1e6, 2),
+                                                    "GB/s": round(b / t1 / 1e9, 1),
+                                                    "frac_hbm": round(b / t1 / 1e9 / PEAK_HBM_GBS, 4)}
         del copies
         # down-projection shape (config 3): K = 14336 = 28 * 512 -> N = 4096; rotation-only fold (s = 1)
         K3, N3 = 14336, 4096

@@ -213,6 +213,27 @@ SR_API int sr_fold_smooth_rotate_quant_ex(const void *W_f16, int64_t K, int64_t 
 SR_API int sr_kv_quant_asym(const void *X_f16, int64_t rows, int64_t D, int64_t ldx, int64_t group, float clip,
                      uint8_t *Q, float *scale, float *zero, void *stream);
 
+/*
+ * The whole online path for ONE token in a single launch (decode step):
+ *     exactly sr_fwht_quant_act(X, inv_s, clip) followed by sr_w4a4_gemm(..., SR_F16)
+ * (paper: online Hadamard and per-token INT4 in front of the quantised projection, section
+ * "Methodology", Eq. (1)).  Codes and scale are the ones the two calls would produce, up to the
+ * rounding-order freedom of the fp32 rotation (a code may sit on the other side of a rounding
+ * boundary).  Offered where it beats the two calls: one token, K a power of two up to 8192.
+ *
+ *   X_f16   fp16 [M, K], M = 1 (M = 0 is a no-op; M > 1 is SR_ERR_SHAPE: use the two calls)
+ *   K       2048, 4096 or 8192 (SR_ERR_UNSUPPORTED_K otherwise: use the two calls)
+ *   Wq, w_scale   packed weights [N, K/2] and scales [N] from the fold; N a multiple of 16
+ *   Y_f16   out, fp16 [M, N], row stride ldy
+ *   Xq_out  out, optional (may be NULL): uint8 [M, K/2], the activation codes that were used
+ *   x_scale_out  out, optional (may be NULL): fp32 [M]
+ */
+SR_API int sr_w4a4_linear_decode(const void *X_f16, int64_t M, int64_t K, int64_t ldx,
+                          const float *inv_s, float clip,
+                          const uint8_t *Wq, const float *w_scale, int64_t N,
+                          void *Y_f16, int64_t ldy,
+                          uint8_t *Xq_out, float *x_scale_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -36,6 +36,7 @@ _SIGNATURES = {
     "sr_fold_smooth_rotate_quant_ex": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _i64, _int, _int, _f32,
                                                _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "sr_kv_quant_asym": (_int, [_vp, _i64, _i64, _i64, _i64, _f32, _vp, _vp, _vp, _vp]),
+    "sr_w4a4_linear_decode": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _vp]),
 }
 
 _lib = None
@@ -221,3 +222,18 @@ def sr_kv_quant_asym(X, group: int = 128, clip: float = 0.95, Q=None, scale=None
     _check(raw().sr_kv_quant_asym(_ptr(X), rows, D, ldx, group, clip, _ptr(Q), _ptr(scale), _ptr(zero), _stream()),
            "sr_kv_quant_asym")
     return Q, scale, zero
+
+
+def sr_w4a4_linear_decode(X, inv_s, Wq, w_scale, clip: float = 0.9, Y=None, Xq_out=None, x_scale_out=None):
+    """X fp16 [1, K], Wq uint8 [N, K/2] -> Y fp16 [1, N] in one launch (rotate, quantise, multiply)."""
+    _dev(X, torch.float16, "X"); _dev(Wq, torch.uint8, "Wq")
+    M, K = X.shape
+    N = Wq.shape[0]
+    if Wq.shape[1] * 2 != K:
+        raise ValueError("X and Wq disagree on K")
+    Y = torch.empty((M, N), dtype=torch.float16, device=X.device) if Y is None else Y
+    ldx = X.stride(0) if M > 1 else K
+    ldy = Y.stride(0) if M > 1 else N
+    _check(raw().sr_w4a4_linear_decode(_ptr(X), M, K, ldx, _ptr(inv_s), clip, _ptr(Wq), _ptr(w_scale), N, _ptr(Y),
+                                       ldy, _ptr(Xq_out), _ptr(x_scale_out), _stream()), "sr_w4a4_linear_decode")
+    return Y

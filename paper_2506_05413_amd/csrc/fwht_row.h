@@ -1,0 +1,356 @@
+// Device code shared by the kernels that rotate a row on chip (T(v) = v H) and quantise it:
+// the compile-time Paley matrix of order 28, register butterflies, the padded LDS row layout,
+// the passes over it, and the INT4 quantise-and-pack step.
+// (Paper: online exact Hadamard, section "Methodology"; quantiser Eq. (1).)
+#pragma once
+
+#include "sr_common.h"
+
+#include <hip/hip_fp16.h>
+#include <utility>
+
+namespace sr {
+namespace {
+
+// ---- Paley type-I Hadamard matrix of order 28, built at compile time -------------
+// GF(27) = GF(3)[x] / (x^3 + 2x + 1); element c0 + c1 x + c2 x^2 has index c0 + 3 c1 + 9 c2.
+constexpr int gf27_sub(int a, int b)
+{
+    int r = 0, w = 1;
+    for (int d = 0; d < 3; ++d) {
+        r += ((a % 3 - b % 3 + 3) % 3) * w;
+        a /= 3; b /= 3; w *= 3;
+    }
+    return r;
+}
+constexpr int gf27_mul(int a, int b)
+{
+    int ca[3] = {a % 3, a / 3 % 3, a / 9}, cb[3] = {b % 3, b / 3 % 3, b / 9};
+    int p[5] = {0, 0, 0, 0, 0};
+    for (int i = 0; i < 3; ++i)
+        for (int j = 0; j < 3; ++j) p[i + j] += ca[i] * cb[j];
+    // x^3 = x + 2 and x^4 = x^2 + 2x over GF(3)
+    p[1] += 2 * p[4]; p[2] += p[4];
+    p[0] += 2 * p[3]; p[1] += p[3];
+    return p[0] % 3 + 3 * (p[1] % 3) + 9 * (p[2] % 3);
+}
+constexpr bool gf27_is_square(int e)
+{
+    for (int r = 1; r < 27; ++r)
+        if (gf27_mul(r, r) == e) return true;
+    return false;
+}
+// sign of H28[i][j]: first row +1, rest of first column -1, else chi(e_i - e_j) + identity
+constexpr int h28_sign(int i, int j)
+{
+    if (i == 0) return 1;
+    if (j == 0) return -1;
+    if (i == j) return 1;
+    return gf27_is_square(gf27_sub(i - 1, j - 1)) ? 1 : -1;
+}
+// bit i set  <=>  H28[i][j] == -1
+constexpr uint32_t h28_neg_mask(int j)
+{
+    uint32_t m = 0;
+    for (int i = 0; i < 28; ++i)
+        if (h28_sign(i, j) < 0) m |= 1u << i;
+    return m;
+}
+constexpr int popc(uint32_t v) { int c = 0; for (; v; v &= v - 1) ++c; return c; }
+
+template <int J>
+__device__ __forceinline__ float h28_col(const float (&v)[28], float S)
+{
+    constexpr uint32_t neg = h28_neg_mask(J);
+    if constexpr (popc(neg) <= 14) {
+        float n = 0.f;
+#pragma unroll
+        for (int i = 0; i < 28; ++i)
+            if ((neg >> i) & 1u) n += v[i];
+        return fmaf(-2.f, n, S);
+    } else {
+        float p = 0.f;
+#pragma unroll
+        for (int i = 0; i < 28; ++i)
+            if (!((neg >> i) & 1u)) p += v[i];
+        return fmaf(2.f, p, -S);
+    }
+}
+template <int... J>
+__device__ __forceinline__ void h28_apply(const float (&v)[28], float (&o)[28], float S,
+                                          std::integer_sequence<int, J...>)
+{
+    ((o[J] = h28_col<J>(v, S)), ...);
+}
+
+// ---- radix-2 butterflies on 2^B register values -----------------------------------
+template <int B>
+__device__ __forceinline__ void butterflies(float (&v)[1 << B])
+{
+#pragma unroll
+    for (int h = 1; h < (1 << B); h <<= 1) {
+#pragma unroll
+        for (int i = 0; i < (1 << B); ++i) {
+            if (!(i & h)) {
+                float a = v[i], b = v[i | h];
+                v[i] = a + b;
+                v[i | h] = a - b;
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ int pad(int i) { return i + ((i >> 6) << 2); }
+constexpr int padded_len(int K) { return K + (K >> 6) * 4; }
+
+constexpr int ilog2(int64_t v) { int l = 0; while ((int64_t(1) << (l + 1)) <= v) ++l; return l; }
+
+// In-LDS pass over index bits [LO, LO+B).
+template <int K, int NT, int LO, int B, bool TRACK>
+__device__ __forceinline__ void lds_pass(float *row, int t, float &amax)
+{
+    constexpr int E = 1 << B;
+    for (int g = t; g < (K >> B); g += NT) {
+        const int g_low = g & ((1 << LO) - 1);
+        const int base = ((g >> LO) << (LO + B)) | g_low;
+        float v[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) v[e] = row[pad(base + (e << LO))];
+        butterflies<B>(v);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            row[pad(base + (e << LO))] = v[e];
+            if (TRACK) amax = fmaxf(amax, fabsf(v[e]));
+        }
+    }
+}
+
+// All remaining power-of-two passes from bit LO up to LOGP.
+template <int K, int NT, int LO, int LOGP, bool TRACK_LAST>
+__device__ __forceinline__ void lds_passes(float *row, int t, float &amax)
+{
+    if constexpr (LO < LOGP) {
+        constexpr int B = (LOGP - LO) >= 4 ? 4 : (LOGP - LO);
+        constexpr bool last = (LO + B == LOGP);
+        lds_pass<K, NT, LO, B, last && TRACK_LAST>(row, t, amax);
+        __syncthreads();
+        lds_passes<K, NT, LO + B, LOGP, TRACK_LAST>(row, t, amax);
+    }
+}
+
+// ---- the same passes with a run-time choice of index bits (head-wise transforms) ---------------
+// Bit b of `mask` set <=> the 2 x 2 factor on index bit b is applied; a clear bit leaves the
+// identity there.  The branches are uniform over the workgroup.
+template <int B>
+__device__ __forceinline__ void butterflies_masked(float (&v)[1 << B], uint32_t mask)
+{
+#pragma unroll
+    for (int h = 1; h < (1 << B); h <<= 1) {
+        if (mask & (uint32_t)h) {
+#pragma unroll
+            for (int i = 0; i < (1 << B); ++i) {
+                if (!(i & h)) {
+                    float a = v[i], b = v[i | h];
+                    v[i] = a + b;
+                    v[i | h] = a - b;
+                }
+            }
+        }
+    }
+}
+
+template <int K, int NT, int LO, int LOGP>
+__device__ __forceinline__ void lds_passes_masked(float *row, int t, uint32_t mask)
+{
+    if constexpr (LO < LOGP) {
+        constexpr int B = (LOGP - LO) >= 4 ? 4 : (LOGP - LO);
+        constexpr int E = 1 << B;
+        const uint32_t mb = (mask >> LO) & (uint32_t)(E - 1);
+        if (mb) {                                           // a pass with no selected bit is skipped whole
+            for (int g = t; g < (K >> B); g += NT) {
+                const int g_low = g & ((1 << LO) - 1);
+                const int base = ((g >> LO) << (LO + B)) | g_low;
+                float v[E];
+#pragma unroll
+                for (int e = 0; e < E; ++e) v[e] = row[pad(base + (e << LO))];
+                butterflies_masked<B>(v, mb);
+#pragma unroll
+                for (int e = 0; e < E; ++e) row[pad(base + (e << LO))] = v[e];
+            }
+            __syncthreads();
+        }
+        lds_passes_masked<K, NT, LO + B, LOGP>(row, t, mask);
+    }
+}
+
+// ---- quantise + pack eight values (shared by all kernels) ---------------------------------
+// t = fma(y, 1/Delta, 1.5 * 2^23) rounds y/Delta to the nearest-even integer in the low mantissa
+// bits (one rounding); the clamp to [-8, 7] is an integer median on those bits; the eight clamped
+// words are packed by shift-adds modulo 2^32, the constant part subtracted once, and the
+// offset-binary nibbles become two's complement by XOR 0x88888888.
+constexpr uint32_t kMagicBits = 0x4B400000u;             // bit pattern of 1.5 * 2^23
+constexpr uint32_t pack_bias()
+{
+    uint32_t c = 0;
+    for (int e = 0; e < 8; ++e) c += (kMagicBits - 8u) << (4 * e);
+    return c;
+}
+__device__ __forceinline__ uint32_t quant_pack8(const float (&y)[8], float inv_delta)
+{
+    const float magic = __uint_as_float(kMagicBits);
+    uint32_t word = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        int bits = (int)__float_as_uint(fmaf(y[e], inv_delta, magic));
+        bits = min(max(bits, (int)kMagicBits - 8), (int)kMagicBits + 7);
+        word += (uint32_t)bits << (4 * e);
+    }
+    return (word - pack_bias()) ^ 0x88888888u;
+}
+
+// ---- rotation of one row by a whole workgroup -----------------------------------------------
+// x (fp16, optionally times pre) -> T(x) in `row` (fp32, padded layout, LDS) and the row's
+// absolute maximum, returned to every thread.  NT threads, t = thread index, red = NT / 64 floats
+// of LDS.  Ends with the row complete and visible to all threads.
+// The first pass (index bits 0..3, 16 contiguous values per group) is split into its global
+// loads and the rest, so that a caller can put other loads between the two.
+template <int K, int NT>
+struct RowLoad {
+    static constexpr int NG = (K / 16 + NT - 1) / NT;      // groups of 16 values per thread
+    uint4 u[NG][2];
+    float4 p[NG][4];                                       // the matching 16 values of `pre`, if any
+};
+
+template <int K, int NT>
+__device__ __forceinline__ void row_load(const __half *__restrict__ x, const float *__restrict__ pre, const int t,
+                                         RowLoad<K, NT> &ld)
+{
+#pragma unroll
+    for (int i = 0; i < RowLoad<K, NT>::NG; ++i) {
+        const int g = t + i * NT;
+        if (g < K / 16) {
+            ld.u[i][0] = *reinterpret_cast<const uint4 *>(x + 16 * g);
+            ld.u[i][1] = *reinterpret_cast<const uint4 *>(x + 16 * g + 8);
+            if (pre) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) ld.p[i][q] = *reinterpret_cast<const float4 *>(pre + 16 * g + 4 * q);
+            }
+        }
+    }
+}
+
+template <int K, int NT>
+__device__ __forceinline__ float rotate_loaded_row_absmax(const RowLoad<K, NT> &ld, const float *__restrict__ pre,
+                                                          float *row, float *red, const int t)
+{
+    constexpr bool KRON = !is_pow2(K);
+    constexpr int P2 = KRON ? K / 28 : K;       // power-of-two factor
+    constexpr int LOGP = ilog2(P2);
+    static_assert(LOGP >= 4 && K % 16 == 0, "first pass needs 16 contiguous values");
+
+    // ---- pass 1: bits 0..3 on the loaded values ------------------------------------------
+#pragma unroll
+    for (int i = 0; i < RowLoad<K, NT>::NG; ++i) {
+        const int g = t + i * NT;
+        if (g < K / 16) {
+            union { uint4 u[2]; __half h[16]; } raw;
+            raw.u[0] = ld.u[i][0];
+            raw.u[1] = ld.u[i][1];
+            float v[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) v[e] = __half2float(raw.h[e]);
+            if (pre) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 s = ld.p[i][q];
+                    v[4 * q + 0] *= s.x; v[4 * q + 1] *= s.y; v[4 * q + 2] *= s.z; v[4 * q + 3] *= s.w;
+                }
+            }
+            butterflies<4>(v);
+            float *dst = row + pad(16 * g);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<float4 *>(dst + 4 * q) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+        }
+    }
+    __syncthreads();
+
+    // ---- remaining power-of-two bits ---------------------------------------------------
+    float amax = 0.f;
+    if constexpr (LOGP == 4 && !KRON) {
+        // K = 16 cannot occur (K >= 64); kept for completeness of the template
+    }
+    // a single leftover bit of the power-of-two part is folded into the Paley pass (56 values per group)
+    constexpr bool MERGE = KRON && ((LOGP - 4) % 4 == 1);
+    lds_passes<K, NT, 4, MERGE ? LOGP - 1 : LOGP, !KRON>(row, t, amax);
+
+    // ---- Paley factor: 28 values at stride P2 per group ---------------------------------
+    if constexpr (MERGE) {
+        constexpr int HALF = P2 / 2;
+        for (int g = t; g < HALF; g += NT) {
+            float a[28], b[28], o[28];
+            float Sa = 0.f, Sb = 0.f;
+#pragma unroll
+            for (int i = 0; i < 28; ++i) {
+                const float lo = row[pad(g + i * P2)], hi = row[pad(g + HALF + i * P2)];
+                a[i] = lo + hi;
+                b[i] = lo - hi;
+                Sa += a[i];
+                Sb += b[i];
+            }
+            h28_apply(a, o, Sa, std::make_integer_sequence<int, 28>{});
+#pragma unroll
+            for (int j = 0; j < 28; ++j) {
+                row[pad(g + j * P2)] = o[j];
+                amax = fmaxf(amax, fabsf(o[j]));
+            }
+            h28_apply(b, o, Sb, std::make_integer_sequence<int, 28>{});
+#pragma unroll
+            for (int j = 0; j < 28; ++j) {
+                row[pad(g + HALF + j * P2)] = o[j];
+                amax = fmaxf(amax, fabsf(o[j]));
+            }
+        }
+        __syncthreads();
+    } else if constexpr (KRON) {
+        for (int g = t; g < P2; g += NT) {
+            float v[28], o[28];
+            float S = 0.f;
+#pragma unroll
+            for (int i = 0; i < 28; ++i) {
+                v[i] = row[pad(g + i * P2)];
+                S += v[i];
+            }
+            h28_apply(v, o, S, std::make_integer_sequence<int, 28>{});
+#pragma unroll
+            for (int j = 0; j < 28; ++j) {
+                row[pad(g + j * P2)] = o[j];
+                amax = fmaxf(amax, fabsf(o[j]));
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- row absmax ----------------------------------------------------------------------
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+    if ((t & 63) == 0) red[t >> 6] = amax;
+    __syncthreads();
+    amax = red[0];
+#pragma unroll
+    for (int w = 1; w < NT / 64; ++w) amax = fmaxf(amax, red[w]);
+
+    return amax;
+}
+
+template <int K, int NT>
+__device__ __forceinline__ float rotate_row_absmax(const __half *__restrict__ x, const float *__restrict__ pre,
+                                                   float *row, float *red, const int t)
+{
+    RowLoad<K, NT> ld;
+    row_load<K, NT>(x, pre, t, ld);
+    return rotate_loaded_row_absmax<K, NT>(ld, pre, row, red, t);
+}
+
+}  // namespace
+}  // namespace sr

@@ -1,0 +1,186 @@
+// Whole online path of the W4A4 linear layer for ONE token in ONE launch:
+//     x^ = quantise((x * inv_s) H),   Y = dequantise(x^ W^)
+// (Paper: online Hadamard + per-token INT4 of the activations in front of the quantised
+// projection, section "Methodology" and Eq. (1); this is the decode step, where a launch and a
+// round trip through memory cost as much as the arithmetic.)
+//
+// A workgroup owns 8 G output channels over all of K.  It first ISSUES the loads of all its
+// weights (they stay in flight in registers), then rotates and quantises the token row(s) in LDS
+// while those loads travel -- every workgroup repeats that small piece of work, which is why the
+// grid is kept near one workgroup per CU, and why only power-of-two K up to 8192 is offered: the
+// rotation of a longer or a 28 * 2^p row takes one workgroup longer than the weights take to arrive -- and finally multiplies packed codes with
+// v_dot8_i32_i4 straight from the registers against the codes in LDS.  Lane (r = l >> 3,
+// c = l & 7) holds the 16-byte chunk c of a 128-byte slab of row r of an 8-row group, so every
+// load instruction reads whole lines; wave w takes slabs w, w + 8, ...
+#include "fwht_row.h"
+
+namespace sr {
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int LD_NT = 512;                 // threads per workgroup
+constexpr int LD_NW = LD_NT / 64;
+constexpr int LD_MT = 1;                   // tokens per call (two rows lose to the two-call path: measured)
+
+template <int K, int G>
+__global__ __launch_bounds__(LD_NT) void linear_decode_kernel(const __half *__restrict__ X, int M, int64_t ldx,
+                                                              const float *__restrict__ pre, float clip,
+                                                              const uint8_t *__restrict__ Wq,
+                                                              const float *__restrict__ ws, int N,
+                                                              __half *__restrict__ Y, int64_t ldy,
+                                                              uint8_t *__restrict__ Xq_out, float *__restrict__ xs_out)
+{
+    constexpr int Kb = K / 2;
+    constexpr int NSLAB = (Kb + 127) / 128;
+    constexpr int U = (NSLAB + LD_NW - 1) / LD_NW;
+    static_assert(G * U <= 16, "weights in flight must fit the register file");
+
+    extern __shared__ float row[];                                     // padded_len(K) floats, then the codes
+    uint32_t *xq = reinterpret_cast<uint32_t *>(row + padded_len(K));   // [LD_MT][K / 8] packed codes
+    __shared__ float red[LD_NW];
+    __shared__ float sx[LD_MT];
+
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int r = lane >> 3, c = lane & 7;
+    const int n0 = blockIdx.x * (8 * G);
+
+    // ---- the first token row's loads go first (they are what the rotation waits for) ...
+    RowLoad<K, LD_NT> xld;
+    row_load<K, LD_NT>(X, pre, t, xld);
+
+    // ---- ... then all weight loads of this workgroup, up front -------------------------------
+    u32x4 w[G][U];
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        // register slot g holds row group (g + workgroup index) mod G: at any moment the workgroups of the
+        // chip then ask for different offsets inside their 8 G rows, not all for the same memory channels
+        int n = n0 + 8 * ((g + (int)blockIdx.x) % G) + r;
+        n = n < N ? n : N - 1;                                          // ragged last workgroup: re-read the last row
+        const uint8_t *wp = Wq + (int64_t)n * Kb + c * 16;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int off = (wave + LD_NW * u) * 128;
+            w[g][u] = (off + c * 16 < Kb) ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + off)) : zero;
+        }
+    }
+
+    // ---- rotate + quantise the token rows into LDS --------------------------------------------
+    for (int m = 0; m < M; ++m) {
+        if (m > 0) row_load<K, LD_NT>(X + m * ldx, pre, t, xld);
+        const float amax = rotate_loaded_row_absmax<K, LD_NT>(xld, pre, row, red, t);
+        const float delta = (amax == 0.f) ? 1.f : (clip * amax) / 7.f;
+        const float inv_delta = 1.f / delta;
+        if (t == 0) {
+            sx[m] = delta;
+            if (xs_out && blockIdx.x == 0) xs_out[m] = delta;
+        }
+        uint32_t *q = xq + m * (K / 8);
+        for (int i = t; i < K / 8; i += LD_NT) {
+            const float *src = row + pad(8 * i);
+            const float4 a = *reinterpret_cast<const float4 *>(src);
+            const float4 b = *reinterpret_cast<const float4 *>(src + 4);
+            const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+            const uint32_t code = quant_pack8(v, inv_delta);
+            q[i] = code;
+            if (Xq_out && blockIdx.x == 0) reinterpret_cast<uint32_t *>(Xq_out + (int64_t)m * Kb)[i] = code;
+        }
+        __syncthreads();                                               // row is free again, codes are visible
+    }
+
+    // ---- dot products: registers (weights) x LDS (activation codes) ---------------------------
+    int acc[G][LD_MT];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int m = 0; m < LD_MT; ++m) acc[g][m] = 0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int off = (wave + LD_NW * u) * 128 + c * 16;             // byte offset inside a row of codes
+        if (off < Kb) {
+#pragma unroll
+            for (int m = 0; m < LD_MT; ++m) {
+                if (m < M) {
+                    const u32x4 x = *reinterpret_cast<const u32x4 *>(xq + m * (K / 8) + off / 4);
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        int a = acc[g][m];
+                        a = __builtin_amdgcn_sdot8((int)w[g][u].x, (int)x.x, a, false);
+                        a = __builtin_amdgcn_sdot8((int)w[g][u].y, (int)x.y, a, false);
+                        a = __builtin_amdgcn_sdot8((int)w[g][u].z, (int)x.z, a, false);
+                        a = __builtin_amdgcn_sdot8((int)w[g][u].w, (int)x.w, a, false);
+                        acc[g][m] = a;
+                    }
+                }
+            }
+        }
+    }
+    // the 8 lanes of a row, then the waves (through the now idle row buffer)
+    int *part = reinterpret_cast<int *>(row);                          // [LD_NW][LD_MT][8 G]
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int m = 0; m < LD_MT; ++m) {
+            int v = acc[g][m];
+            v += __shfl_xor(v, 1, 64);
+            v += __shfl_xor(v, 2, 64);
+            v += __shfl_xor(v, 4, 64);
+            if (c == 0) part[(wave * LD_MT + m) * (8 * G) + ((g + (int)blockIdx.x) % G) * 8 + r] = v;
+        }
+    __syncthreads();
+    for (int o = t; o < M * 8 * G; o += LD_NT) {
+        const int m = o / (8 * G), j = o % (8 * G), n = n0 + j;
+        if (n >= N) continue;
+        int sum = 0;
+#pragma unroll
+        for (int wv = 0; wv < LD_NW; ++wv) sum += part[(wv * LD_MT + m) * (8 * G) + j];
+        Y[(int64_t)m * ldy + n] = __float2half_rn((float)sum * sx[m] * ws[n]);
+    }
+}
+
+template <int K, int G>
+hipError_t launch_ld(const void *X, int64_t M, int64_t ldx, const float *pre, float clip, const uint8_t *Wq,
+                     const float *ws, int64_t N, void *Y, int64_t ldy, uint8_t *Xq_out, float *xs_out, hipStream_t st)
+{
+    auto kern = linear_decode_kernel<K, G>;
+    constexpr int lds = (int)(sizeof(float) * padded_len(K)) + LD_MT * (K / 2);
+    static_assert(lds + 64 <= 160 * 1024, "LDS");
+    if (lds > 40 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+    }
+    const unsigned blocks = (unsigned)((N + 8 * G - 1) / (8 * G));
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(LD_NT), lds, st, static_cast<const __half *>(X), (int)M, ldx, pre, clip,
+                       Wq, ws, (int)N, static_cast<__half *>(Y), ldy, Xq_out, xs_out);
+    return hipGetLastError();
+}
+
+// largest G in {1, 2, 4, 8} with G <= gmax that still leaves at least ~256 workgroups (or G = 1)
+inline int pick_g(int64_t N, int gmax)
+{
+    int G = 1;
+    while (2 * G <= gmax && N / (16 * G) >= 224) G *= 2;
+    return G;
+}
+
+}  // namespace
+
+bool linear_decode_supported(int64_t K) { return K == 2048 || K == 4096 || K == 8192; }
+
+hipError_t launch_linear_decode(const void *X, int64_t M, int64_t K, int64_t ldx, const float *pre, float clip,
+                                const uint8_t *Wq, const float *ws, int64_t N, void *Y, int64_t ldy,
+                                uint8_t *Xq_out, float *xs_out, hipStream_t st)
+{
+#define SR_LD(KK, GG) return launch_ld<KK, GG>(X, M, ldx, pre, clip, Wq, ws, N, Y, ldy, Xq_out, xs_out, st)
+    switch (K) {
+        case 2048: switch (pick_g(N, 8)) { case 8: SR_LD(2048, 8); case 4: SR_LD(2048, 4); case 2: SR_LD(2048, 2); default: SR_LD(2048, 1); }
+        case 4096: switch (pick_g(N, 8)) { case 8: SR_LD(4096, 8); case 4: SR_LD(4096, 4); case 2: SR_LD(4096, 2); default: SR_LD(4096, 1); }
+        case 8192: switch (pick_g(N, 4)) { case 4: SR_LD(8192, 4); case 2: SR_LD(8192, 2); default: SR_LD(8192, 1); }
+        default: return hipErrorInvalidValue;
+    }
+#undef SR_LD
+}
+
+}  // namespace sr

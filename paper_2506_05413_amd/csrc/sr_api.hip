@@ -204,6 +204,23 @@ int sr_kv_quant_asym(const void *X_f16, int64_t rows, int64_t D, int64_t ldx, in
                                    static_cast<hipStream_t>(stream)));
 }
 
+int sr_w4a4_linear_decode(const void *X_f16, int64_t M, int64_t K, int64_t ldx, const float *inv_s, float clip,
+                          const uint8_t *Wq, const float *w_scale, int64_t N, void *Y_f16, int64_t ldy,
+                          uint8_t *Xq_out, float *x_scale_out, void *stream)
+{
+    if (M < 0 || M > 1 || K <= 0 || N <= 0 || N % 16 != 0 || ldx < K || ldy < N) return SR_ERR_SHAPE;
+    if ((double)N * (double)K >= 4294967296.0) return SR_ERR_SHAPE;
+    if (!sr::linear_decode_supported(K)) return SR_ERR_UNSUPPORTED_K;
+    if (!(clip > 0.f && clip <= 1.f)) return SR_ERR_ARG;
+    if (M == 0) return SR_OK;
+    if (!X_f16 || !Wq || !w_scale || !Y_f16) return SR_ERR_NULL;
+    if (ldx % 8 != 0 || !aligned16(X_f16) || !aligned16(Wq) || (inv_s && !aligned16(inv_s)) ||
+        (Xq_out && !aligned16(Xq_out)))
+        return SR_ERR_ALIGN;
+    return dev(sr::launch_linear_decode(X_f16, M, K, ldx, inv_s, clip, Wq, w_scale, N, Y_f16, ldy, Xq_out,
+                                        x_scale_out, static_cast<hipStream_t>(stream)));
+}
+
 int sr_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, const float *w_scale,
                  int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_dtype,
                  void *workspace, size_t workspace_bytes, void *stream)

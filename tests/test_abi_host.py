@@ -23,7 +23,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = declared_symbols()
-    assert len(names) == 12 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
+    assert len(names) == 13 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
     lib = ctypes.CDLL(sr.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -192,3 +192,27 @@ def test_kv_quant_rejects_bad_arguments():
     assert f(A + 4, 4, 1024, 1024, 128, 0.95, A, A, A, None) == sr.SR_ERR_ALIGN
     assert f(A, 4, 1024, 1028, 128, 0.95, A, A, A, None) == sr.SR_ERR_ALIGN
     assert f(None, 0, 1024, 1024, 128, 0.95, None, None, None, None) == sr.SR_OK
+
+
+def test_linear_decode_rejects_bad_arguments():
+    f = sr.raw().sr_w4a4_linear_decode
+    ok = dict(X=A, M=1, K=4096, ldx=4096, inv=None, clip=0.9, Wq=A, ws=A, N=64, Y=A, ldy=64, xq=None, xs=None, st=None)
+    def call(**kw):
+        a = dict(ok); a.update(kw)
+        return f(a["X"], a["M"], a["K"], a["ldx"], a["inv"], a["clip"], a["Wq"], a["ws"], a["N"], a["Y"], a["ldy"],
+                 a["xq"], a["xs"], a["st"])
+    assert call(M=2) == sr.SR_ERR_SHAPE                         # more than one token: use the two calls
+    assert call(M=-1) == sr.SR_ERR_SHAPE
+    assert call(N=40) == sr.SR_ERR_SHAPE
+    assert call(ldx=2048) == sr.SR_ERR_SHAPE
+    assert call(ldy=32) == sr.SR_ERR_SHAPE
+    assert call(K=512, ldx=512) == sr.SR_ERR_UNSUPPORTED_K      # a valid Hadamard order, but not built for this call
+    assert call(K=14336, ldx=14336) == sr.SR_ERR_UNSUPPORTED_K
+    assert call(K=4000, ldx=4000) == sr.SR_ERR_UNSUPPORTED_K
+    assert call(clip=0.0) == sr.SR_ERR_ARG
+    assert call(X=None) == sr.SR_ERR_NULL
+    assert call(Y=None) == sr.SR_ERR_NULL
+    assert call(ws=None) == sr.SR_ERR_NULL
+    assert call(X=A + 2) == sr.SR_ERR_ALIGN
+    assert call(ldx=4100) == sr.SR_ERR_ALIGN
+    assert call(M=0, X=None, Y=None) == sr.SR_OK
