@@ -16,6 +16,8 @@
 // bank-conflict free for K = 4096.
 #include "fwht_row.h"
 
+#include <stdlib.h>
+
 namespace sr {
 namespace {
 
@@ -316,11 +318,17 @@ hipError_t launch_one_ex(const void *X, int64_t rows, int64_t ldx, const float *
 
 }  // namespace
 
+// K = 4096: below this many rows the wave-per-row kernel leaves most of the chip idle (4 rows per workgroup)
+// and the workgroup-per-row kernel has the shorter critical path.
+constexpr int64_t kWaveKernelMinRows = 1024;   // measured: 3.3 - 4.8 us against 4.2 - 5.9 us up to 512 rows, equal at 1024
+
 hipError_t launch_fwht_quant(const void *X, int64_t rows, int64_t K, int64_t ldx, const float *pre,
                              float clip, float post_scale, uint8_t *Q, float *scale_out, hipStream_t st)
 {
 #define SR_CASE(KK) case KK: return launch_one<KK>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
-    if (K == 4096) {
+    int pick = 0;
+    if (const char *env = getenv("SMOOTHROT_FWHT4096")) pick = atoi(env);
+    if (K == 4096 && (pick == 1 || (pick == 0 && rows > kWaveKernelMinRows))) {
         constexpr size_t lds = 4 * (4096 + 64) * sizeof(float);
         const unsigned blocks = (unsigned)((rows + 3) / 4);
         hipError_t e;

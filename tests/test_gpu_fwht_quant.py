@@ -95,6 +95,21 @@ def test_edge_rows_and_strides(gpu):
     compare(gpu, X[:1], None, 1.0, what="M=1")
 
 
+def test_wave_per_row_kernel_edges(gpu):
+    """K = 4096 above 1024 rows runs on the wave-per-row kernel: ragged row count (1027 = 4 * 256 + 3),
+    degenerate rows, padded leading dimension, with and without smoothing factors."""
+    K, M = 4096, 1027
+    X = wl.cfg2_X(M=M).copy()
+    X[2] = 0
+    X[4] = 0; X[4, 17] = 65504.0
+    X[5] = 6e-8
+    X[M - 1] = 0; X[M - 1, K - 1] = -3.0
+    rng = np.random.default_rng(2)
+    inv_s = np.exp(rng.standard_normal(K) * 0.3).astype(np.float32)
+    compare(gpu, X, inv_s, 0.9, what="wave edges")
+    compare(gpu, X, None, 1.0, ldx=K + 8, what="wave edges ragged-ld")
+
+
 def test_cfg2_full_size(gpu):
     X = wl.cfg2_X()
     rng = np.random.default_rng(0)
