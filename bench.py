@@ -157,7 +157,7 @@ def main():
     roofline = {"bound": "mfma", "kernel": "sr_w4a4_gemm: gemm_w4a4_kernel, M=2048 N=14336 K=4096",
                 "achieved": round(gemm_ops / gemm_avg_s / 1e12, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                 "frac": round(gemm_ops / gemm_avg_s / 1e12 / PEAK_INT8_TOPS, 4),
-                "traffic": {"hbm_bytes_per_launch": 261.4e6, "algorithmic_bytes": 92.3e6,
+                "traffic": {"hbm_bytes_per_launch": 169.5e6, "algorithmic_bytes": 92.3e6,
                             "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/"},
                 "avg_launch_us": round(gemm_avg_s * 1e6, 2), "median_launch_us": round(gemm_ms[len(gemm_ms) // 2] * 1e3, 2)}
 

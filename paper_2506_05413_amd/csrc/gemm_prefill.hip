@@ -149,7 +149,7 @@ template <int BM, int BN, int WGM, int WGN, int STAGES, bool SMOOTH = false>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_w4a4_kernel(
     const uint8_t *__restrict__ Xq, const float *__restrict__ xs, const uint8_t *__restrict__ Wq,
     const float *__restrict__ ws, int M, int N, int K, void *__restrict__ Yv, int64_t ldy, int out_i32,
-    int tiles_m, int tiles_n)
+    int tiles_m, int tiles_n, int xcd_m)
 {
     constexpr int NWAVE = WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN;      // wave tile
@@ -166,12 +166,19 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_w4a4_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WGM, wn = wave / WGM;
 
-    // workgroups are dealt round-robin to the 8 XCDs: give each XCD a contiguous run of tiles
-    // (m fastest) so that neighbours share W panels and X panels in that XCD's L2
-    int bid = blockIdx.x;
-    const int total = tiles_m * tiles_n;
-    if ((total & 7) == 0) bid = (bid & 7) * (total >> 3) + (bid >> 3);
-    const int tm = bid % tiles_m, tn = bid / tiles_m;
+    // workgroups are dealt round-robin to the 8 XCDs (each with its own L2): XCD x = blockIdx & 7 gets the
+    // rectangle (x % xcd_m, x / xcd_m) of an xcd_m x (8 / xcd_m) split of the tile grid and walks it m
+    // fastest, so the tiles that run together share few X and W panels (the split is chosen on the host)
+    int tm, tn;
+    if (xcd_m > 0) {
+        const int x = blockIdx.x & 7, l = blockIdx.x >> 3;
+        const int rm = tiles_m / xcd_m, rn = tiles_n / (8 / xcd_m);      // rectangle size in tiles
+        tm = (x % xcd_m) * rm + l % rm;
+        tn = (x / xcd_m) * rn + l / rm;
+    } else {
+        tm = blockIdx.x % tiles_m;
+        tn = blockIdx.x / tiles_m;
+    }
     const int m0 = tm * BM, n0 = tn * BN;
     const int Kb = K >> 1;
     const int ns = K / 256;                          // stages
@@ -416,8 +423,23 @@ hipError_t launch_tile(const uint8_t *Xq, const float *xs, const uint8_t *Wq, co
         if (e != hipSuccess) return e;
     }
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
+    // split of the tile grid over the 8 XCDs.  Measured (FETCH_SIZE, M = 2048, K = 4096): two halves in m by four
+    // blocks in n reads 112 MB through the fabric at N = 14336 where one run of tiles per XCD read 223 MB (half
+    // of X then stays in an XCD's 4 MB L2); it was also the fastest split at K = 14336.  Otherwise: the split
+    // whose rectangles need the fewest operand rows.  0 = no remapping.
+    int xcd_m = 0;
+    if (tiles_m % 2 == 0 && tiles_n % 4 == 0) {
+        xcd_m = 2;
+    } else {
+        int64_t best = 0;
+        for (int sm = 1; sm <= 8; sm *= 2) {
+            if (tiles_m % sm != 0 || tiles_n % (8 / sm) != 0) continue;
+            const int64_t rows = (int64_t)(tiles_m / sm) * BM + (int64_t)(tiles_n / (8 / sm)) * BN;
+            if (xcd_m == 0 || rows < best) { xcd_m = sm; best = rows; }
+        }
+    }
     hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(WGM * WGN * 64), lds, st, Xq, xs, Wq, ws,
-                       (int)M, (int)N, (int)K, Y, ldy, out_i32, tiles_m, tiles_n);
+                       (int)M, (int)N, (int)K, Y, ldy, out_i32, tiles_m, tiles_n, xcd_m);
     return hipGetLastError();
 }
 
