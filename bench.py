@@ -255,6 +255,37 @@ def main():
         extra["kv_quant_asym_32768x1024"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
                                              "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
         del KV
+        # ---- config 5: the seven linears of a LLaMA-3.1-8B decoder layer at 8 x 2048 tokens (timing only:
+        # random packed weights; q/k/v share one quantised input, gate/up another) --------------------------
+        M5 = 16384
+        X5 = torch.randn((M5, K), dtype=torch.float16, device=dev)
+        X5d = torch.randn((M5, K3), dtype=torch.float16, device=dev)
+        Xq5 = torch.empty((M5, K // 2), dtype=torch.uint8, device=dev)
+        Xq5d = torch.empty((M5, K3 // 2), dtype=torch.uint8, device=dev)
+        xs5 = torch.empty(M5, dtype=torch.float32, device=dev)
+        W5 = {n: (torch.randint(0, 256, (nn, kk // 2), dtype=torch.uint8, device=dev), torch.rand(nn, device=dev) * 1e-3)
+              for n, kk, nn in wl.CFG5_LINEARS}
+        Y5 = torch.empty((M5, 14336), dtype=torch.float16, device=dev)
+
+        def layer(i):
+            sr.sr_fwht_quant_act(X5, inv_s, CLIP, Xq5, xs5)
+            for n in ("q", "k", "v"):
+                sr.sr_w4a4_gemm(Xq5, xs5, W5[n][0], W5[n][1], sr.SR_F16, Y5[:, :W5[n][0].shape[0]])
+            sr.sr_fwht_quant_act(X5, inv_s, CLIP, Xq5, xs5)
+            sr.sr_w4a4_gemm(Xq5, xs5, W5["o"][0], W5["o"][1], sr.SR_F16, Y5[:, :4096])
+            sr.sr_fwht_quant_act(X5, inv_s, CLIP, Xq5, xs5)
+            for n in ("gate", "up"):
+                sr.sr_w4a4_gemm(Xq5, xs5, W5[n][0], W5[n][1], sr.SR_F16, Y5)
+            sr.sr_fwht_quant_act(X5d, None, CLIP, Xq5d, xs5)
+            sr.sr_w4a4_gemm(Xq5d, xs5, W5["down"][0], W5["down"][1], sr.SR_F16, Y5[:, :4096])
+        layer(0)
+        torch.cuda.synchronize()
+        t = ev_time(layer, 5)
+        ops5 = sum(2.0 * M5 * kk * nn for _, kk, nn in wl.CFG5_LINEARS)
+        extra["cfg5_layer_M16384"] = {"ms": round(t * 1e3, 3), "TOPS": round(ops5 / t / 1e12, 1),
+                                      "frac_mfma": round(ops5 / t / 1e12 / PEAK_INT8_TOPS, 4),
+                                      "workload": "7 linears (q,k,v,o,gate,up,down) + 4 rotate/quantise passes, 16384 tokens"}
+        del X5, X5d, Xq5, Xq5d, W5, Y5
 
     # ---------------- CPU baseline: the oracle on a bounded sample ------------------------
     cpu = None
