@@ -137,8 +137,10 @@ __device__ __forceinline__ void store_wave_tile(const v16i (&acc)[FN][FM], uint8
 #pragma unroll
         for (int r = r0; r < WM; r += RPI) {
             const int m = m_base + r, n = n_base + c * 8;
-            const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * RS + c * 16);
-            if (lane < RPI * CPR && m < M && n < N) *reinterpret_cast<uint4 *>(static_cast<__half *>(Yv) + (int64_t)m * ldy + n) = v;
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(stage + r * RS + c * 16);
+            // streamed once, never read back by this kernel: keep it from displacing operand panels in L2
+            if (lane < RPI * CPR && m < M && n < N)
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(static_cast<__half *>(Yv) + (int64_t)m * ldy + n));
         }
     }
 }
