@@ -16,9 +16,10 @@
 namespace sr {
 namespace {
 
-constexpr int UNROLL = 4;        // 16-byte loads in flight per lane
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-template <int LPG>               // lanes per group = G / 8
+// LPG = lanes per group = G / 8; CONTIG: rows follow each other without padding; UNROLL 16-byte loads in flight per lane
+template <int LPG, bool CONTIG, int UNROLL>
 __global__ __launch_bounds__(256) void kv_quant_kernel(const __half *__restrict__ X, int64_t rows, int D, int64_t ldx,
                                                         float clip, uint32_t *__restrict__ Q, float *__restrict__ scale,
                                                         float *__restrict__ zero, int64_t chunks)
@@ -28,16 +29,20 @@ __global__ __launch_bounds__(256) void kv_quant_kernel(const __half *__restrict_
     const int64_t stride = (int64_t)gridDim.x * 256;
     int64_t c0 = (int64_t)blockIdx.x * 256 * UNROLL + threadIdx.x;
     for (; c0 - threadIdx.x < chunks; c0 += stride * UNROLL) {
-        union { uint4 u; __half h[8]; } raw[UNROLL];
+        union { u32x4 v; __half h[8]; } raw[UNROLL];
         bool ok[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int64_t c = c0 + 256 * u;
             ok[u] = c < chunks;
             const int64_t cc = ok[u] ? c : chunks - 1;     // in-bounds dummy for the tail lanes
-            const int64_t r = cc / cpr;
-            const int col = (int)(cc - r * cpr) << 3;
-            raw[u].u = *reinterpret_cast<const uint4 *>(X + r * ldx + col);
+            if (CONTIG) {
+                raw[u].v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(X + cc * 8));
+            } else {
+                const int64_t r = cc / cpr;                // (a 64-bit division per chunk: the padded layout is the slow path)
+                const int col = (int)(cc - r * cpr) << 3;
+                raw[u].v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(X + r * ldx + col));
+            }
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
@@ -55,7 +60,7 @@ __global__ __launch_bounds__(256) void kv_quant_kernel(const __half *__restrict_
             const float hi = clip * mx, lo = clip * mn;
             const float delta = (hi == lo) ? 1.f : (hi - lo) / 15.f;
             const float inv = 1.f / delta;
-            const float z = -rintf(lo / delta);
+            const float z = -rintf(lo * inv);
             uint32_t word = 0;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -64,7 +69,7 @@ __global__ __launch_bounds__(256) void kv_quant_kernel(const __half *__restrict_
             }
             const int64_t c = c0 + 256 * u;
             if (ok[u]) {
-                Q[c] = word;
+                __builtin_nontemporal_store(word, Q + c);
                 if ((threadIdx.x & (LPG - 1)) == 0) {
                     scale[c / LPG] = delta;
                     zero[c / LPG] = z;
@@ -74,27 +79,40 @@ __global__ __launch_bounds__(256) void kv_quant_kernel(const __half *__restrict_
     }
 }
 
+template <int LPG>
+hipError_t launch_lpg(const void *X, int64_t rows, int64_t D, int64_t ldx, float clip, uint8_t *Q, float *scale, float *zero,
+                      hipStream_t st)
+{
+    const int64_t chunks = rows * (D / 8);
+    const bool contig = ldx == D || rows == 1;
+    // eight loads in flight per lane once that still leaves every CU several workgroups, two otherwise
+    const bool big = chunks >= (int64_t)256 * 8 * 2048;
+    const int unroll = big ? 8 : 2;
+    int64_t blocks = (chunks + 256 * unroll - 1) / (256 * unroll);
+    if (blocks > 65536) blocks = 65536;
+#define SR_KV(CC, UU)                                                                                                  \
+    hipLaunchKernelGGL((kv_quant_kernel<LPG, CC, UU>), dim3((unsigned)blocks), dim3(256), 0, st,                        \
+                       static_cast<const __half *>(X), rows, (int)D, ldx, clip, reinterpret_cast<uint32_t *>(Q), scale, \
+                       zero, chunks)
+    if (contig) { if (big) SR_KV(true, 8); else SR_KV(true, 2); }
+    else { if (big) SR_KV(false, 8); else SR_KV(false, 2); }
+#undef SR_KV
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_kv_quant(const void *X, int64_t rows, int64_t D, int64_t ldx, int64_t group, float clip,
                            uint8_t *Q, float *scale, float *zero, hipStream_t st)
 {
-    const int64_t chunks = rows * (D / 8);
-    int64_t blocks = (chunks + 256 * UNROLL - 1) / (256 * UNROLL);
-    if (blocks > 8192) blocks = 8192;
-#define SR_KV(LPG)                                                                                                     \
-    hipLaunchKernelGGL(kv_quant_kernel<LPG>, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<const __half *>(X),  \
-                       rows, (int)D, ldx, clip, reinterpret_cast<uint32_t *>(Q), scale, zero, chunks)
     switch (group) {
-        case 32: SR_KV(4); break;
-        case 64: SR_KV(8); break;
-        case 128: SR_KV(16); break;
-        case 256: SR_KV(32); break;
-        case 512: SR_KV(64); break;
+        case 32: return launch_lpg<4>(X, rows, D, ldx, clip, Q, scale, zero, st);
+        case 64: return launch_lpg<8>(X, rows, D, ldx, clip, Q, scale, zero, st);
+        case 128: return launch_lpg<16>(X, rows, D, ldx, clip, Q, scale, zero, st);
+        case 256: return launch_lpg<32>(X, rows, D, ldx, clip, Q, scale, zero, st);
+        case 512: return launch_lpg<64>(X, rows, D, ldx, clip, Q, scale, zero, st);
         default: return hipErrorInvalidValue;
     }
-#undef SR_KV
-    return hipGetLastError();
 }
 
 }  // namespace sr
