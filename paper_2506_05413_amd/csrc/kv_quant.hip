@@ -4,6 +4,7 @@
 //   hi = clip * max, lo = clip * min over a group of G consecutive values
 //   Delta = (hi - lo) / 15 (1 when the range is empty),  z = -rint(lo / Delta)
 //   code  = clamp(rint(v / Delta) + z, 0, 15)
+// (divisions by Delta are multiplications by its fp32 reciprocal here)
 //
 // Pure streaming: 2 bytes read and 0.5 + 8 / G bytes written per value.  Eight lanes x 16 bytes
 // cover 64 values, so a group of G values is G / 8 neighbouring lanes: minimum and maximum are

@@ -4,14 +4,16 @@
 // projection, section "Methodology" and Eq. (1); this is the decode step, where a launch and a
 // round trip through memory cost as much as the arithmetic.)
 //
-// A workgroup owns 8 G output channels over all of K.  It first ISSUES the loads of all its
-// weights (they stay in flight in registers), then rotates and quantises the token row(s) in LDS
-// while those loads travel -- every workgroup repeats that small piece of work, which is why the
-// grid is kept near one workgroup per CU, and why only power-of-two K up to 8192 is offered: the
-// rotation of a longer or a 28 * 2^p row takes one workgroup longer than the weights take to arrive -- and finally multiplies packed codes with
-// v_dot8_i32_i4 straight from the registers against the codes in LDS.  Lane (r = l >> 3,
-// c = l & 7) holds the 16-byte chunk c of a 128-byte slab of row r of an 8-row group, so every
-// load instruction reads whole lines; wave w takes slabs w, w + 8, ...
+// A workgroup owns 8 G output channels over all of K.  It first ISSUES the loads of its token row
+// and smoothing factors, then of all its weights (they stay in flight in registers), then rotates
+// and quantises the row in LDS while the weights travel, and finally multiplies packed codes with
+// v_dot8_i32_i4 straight from the registers against the codes in LDS.  Every workgroup repeats
+// the rotation, so the grid is kept near one workgroup per CU; and only power-of-two K up to 8192
+// is offered, because the rotation of a longer or a 28 * 2^p row takes one workgroup longer than
+// the weights take to arrive.  Loads return in order per wave: whatever the rotation needs has to
+// be issued BEFORE the weights.  Lane (r = l >> 3, c = l & 7) holds the 16-byte chunk c of a
+// 128-byte slab of row r of an 8-row group, so every load instruction reads whole lines; wave w
+// takes slabs w, w + 8, ...
 #include "fwht_row.h"
 
 namespace sr {
