@@ -81,20 +81,21 @@ __device__ __forceinline__ void dma16(const uint8_t *base, uint32_t lane_off, ui
 }
 
 // ------------------------------------------------------------------------------------------
-// Epilogue for 32 x 32 MFMA tiles: dequantise, then transpose the wave's WM x WN tile through LDS
-// so that global memory is written in whole rows of the tile (16 bytes per lane, WN * esize
-// contiguous bytes per token) instead of 8-byte pieces scattered over 32 rows per instruction.
-// In the accumulator layout a lane owns token (l & 31) and, per quad q, the four output channels
-// 8q + 4 (l >> 5) .. + 3 of each tile.  `stage` is this wave's private LDS area of
-// WM * (WN * 2 + 16) bytes; the caller has made sure nobody still reads it.
+// Epilogue for 32 x 32 MFMA tiles: dequantise, then transpose the wave's WM x WN tile through LDS,
+// 32 tokens at a time, so that global memory is written in whole rows of the tile (16 bytes per
+// lane, WN * 2 contiguous bytes per token) instead of 8-byte pieces scattered over 32 rows per
+// instruction.  In the accumulator layout a lane owns token (l & 31) and, per quad q, the four
+// output channels 8q + 4 (l >> 5) .. + 3 of each tile.  `stage` is this wave's private LDS area of
+// 32 * (WN * 2 + 16) bytes; the caller has made sure nobody else touches it.  sx[j] is the token
+// scale / 256 of this lane's token in row block j, sw[i][q] the four channel scales of quad q of
+// column block i (fetched by the caller; unused for the raw int32 output).
 // ------------------------------------------------------------------------------------------
 template <int FM, int FN>
 __device__ __forceinline__ void store_wave_tile(const v16i (&acc)[FN][FM], uint8_t *stage, int lane, int m_base, int n_base,
-                                                int M, int N, const float *__restrict__ xs,
-                                                const float *__restrict__ ws, void *__restrict__ Yv, int64_t ldy,
-                                                int out_i32)
+                                                int M, int N, const float (&sx)[FM], const float4 (&sw)[FN][4],
+                                                void *__restrict__ Yv, int64_t ldy, int out_i32)
 {
-    constexpr int WM = FM * 32, WN = FN * 32;
+    constexpr int WN = FN * 32;
     const int fr = lane & 31, fg = lane >> 5;
     if (out_i32) {                                          // raw accumulators: a debugging / test output, stored directly
 #pragma unroll
@@ -111,77 +112,98 @@ __device__ __forceinline__ void store_wave_tile(const v16i (&acc)[FN][FM], uint8
                 }
     } else {
         constexpr int RS = WN * 2 + 16;
+        constexpr int CPR = WN * 2 / 16;
+        constexpr int RPI = 64 / CPR;
+        const int c = lane % CPR, r0 = lane / CPR;
 #pragma unroll
         for (int j = 0; j < FM; ++j) {
-            const int m = m_base + j * 32 + fr;
-            const float sx = xs[m < M ? m : M - 1] * (1.f / 256.f);
 #pragma unroll
             for (int i = 0; i < FN; ++i)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int nl = i * 32 + q * 8 + fg * 4;
-                    const int n = n_base + nl < N ? n_base + nl : N - 4;
-                    const float4 sw = *reinterpret_cast<const float4 *>(ws + n);
                     union { __half h[4]; uint2 u; } o;
-                    o.h[0] = __float2half_rn((float)acc[i][j][4 * q] * sx * sw.x);
-                    o.h[1] = __float2half_rn((float)acc[i][j][4 * q + 1] * sx * sw.y);
-                    o.h[2] = __float2half_rn((float)acc[i][j][4 * q + 2] * sx * sw.z);
-                    o.h[3] = __float2half_rn((float)acc[i][j][4 * q + 3] * sx * sw.w);
-                    *reinterpret_cast<uint2 *>(stage + (j * 32 + fr) * RS + nl * 2) = o.u;
+                    o.h[0] = __float2half_rn((float)acc[i][j][4 * q] * sx[j] * sw[i][q].x);
+                    o.h[1] = __float2half_rn((float)acc[i][j][4 * q + 1] * sx[j] * sw[i][q].y);
+                    o.h[2] = __float2half_rn((float)acc[i][j][4 * q + 2] * sx[j] * sw[i][q].z);
+                    o.h[3] = __float2half_rn((float)acc[i][j][4 * q + 3] * sx[j] * sw[i][q].w);
+                    *reinterpret_cast<uint2 *>(stage + fr * RS + nl * 2) = o.u;
                 }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        constexpr int CPR = WN * 2 / 16;
-        constexpr int RPI = 64 / CPR;
-        const int c = lane % CPR, r0 = lane / CPR;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
 #pragma unroll
-        for (int r = r0; r < WM; r += RPI) {
-            const int m = m_base + r, n = n_base + c * 8;
-            const u32x4 v = *reinterpret_cast<const u32x4 *>(stage + r * RS + c * 16);
-            // streamed once, never read back by this kernel: keep it from displacing operand panels in L2
-            if (lane < RPI * CPR && m < M && n < N)
-                __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(static_cast<__half *>(Yv) + (int64_t)m * ldy + n));
+            for (int r = r0; r < 32; r += RPI) {
+                const int m = m_base + j * 32 + r, n = n_base + c * 8;
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(stage + r * RS + c * 16);
+                // streamed once, never read back by this kernel: keep it from displacing operand panels in L2
+                if (lane < RPI * CPR && m < M && n < N)
+                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(static_cast<__half *>(Yv) + (int64_t)m * ldy + n));
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         }
     }
 }
 
+// compute units of the current device (asked once per process and device)
+int compute_units()
+{
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
 constexpr int ROWB = 128;  // packed bytes per row per stage (256 codes = one 128-byte line)
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool SMOOTH = false>
+// Persistent workgroups: a workgroup walks over tiles v = blockIdx.x, blockIdx.x + gridDim.x, ... and keeps the
+// memory pipeline going across the tile boundary -- the first stage of the next tile is in flight while the
+// finished tile is dequantised, transposed and stored, and the stores (fire and forget) drain under the next
+// tile's MFMAs.  One launch of <= (CUs x workgroups per CU) workgroups instead of one workgroup per tile.
+template <int BM, int BN, int WGM, int WGN>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_w4a4_kernel(
     const uint8_t *__restrict__ Xq, const float *__restrict__ xs, const uint8_t *__restrict__ Wq,
     const float *__restrict__ ws, int M, int N, int K, void *__restrict__ Yv, int64_t ldy, int out_i32,
     int tiles_m, int tiles_n, int xcd_m)
 {
+    constexpr int STAGES = 2;
     constexpr int NWAVE = WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN;      // wave tile
     constexpr int FM = WM / 32, FN = WN / 32;        // 32 x 32 MFMA tiles per wave
     constexpr int REGIONS = (BM + BN) / 8;           // 1 KB DMA regions (8 rows x 128 B) per stage
     constexpr int RPW = REGIONS / NWAVE;             // DMA instructions per wave per stage
     constexpr int X_BYTES = BM * ROWB, STAGE_BYTES = (BM + BN) * ROWB;
-    static_assert(REGIONS % NWAVE == 0 && NWAVE % 2 == 0 && WM % 32 == 0 && WN % 32 == 0 && STAGES >= 2 &&
-                      (STAGES - 1) * RPW < 64, "tile");
+    static_assert(REGIONS % NWAVE == 0 && NWAVE % 2 == 0 && WM % 32 == 0 && WN % 32 == 0 && 3 * RPW + 4 * FM < 64,
+                  "tile");
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WGM, wn = wave / WGM;
+    const int total = tiles_m * tiles_n;
 
-    // workgroups are dealt round-robin to the 8 XCDs (each with its own L2): XCD x = blockIdx & 7 gets the
-    // rectangle (x % xcd_m, x / xcd_m) of an xcd_m x (8 / xcd_m) split of the tile grid and walks it m
-    // fastest, so the tiles that run together share few X and W panels (the split is chosen on the host)
-    int tm, tn;
-    if (xcd_m > 0) {
-        const int x = blockIdx.x & 7, l = blockIdx.x >> 3;
-        const int rm = tiles_m / xcd_m, rn = tiles_n / (8 / xcd_m);      // rectangle size in tiles
-        tm = (x % xcd_m) * rm + l % rm;
-        tn = (x / xcd_m) * rn + l / rm;
-    } else {
-        tm = blockIdx.x % tiles_m;
-        tn = blockIdx.x / tiles_m;
-    }
-    const int m0 = tm * BM, n0 = tn * BN;
+    // workgroups are dealt round-robin to the 8 XCDs (each with its own L2): XCD x = v & 7 gets the rectangle
+    // (x % xcd_m, x / xcd_m) of an xcd_m x (8 / xcd_m) split of the tile grid and walks it m fastest, so the
+    // tiles that run together share few X and W panels (the split is chosen on the host; with it on, the grid
+    // size is a multiple of 8, so a workgroup's later tiles stay in its XCD's rectangle)
+    auto tile_origin = [&](int v, int &m0, int &n0) {
+        int tm, tn;
+        if (xcd_m > 0) {
+            const int x = v & 7, l = v >> 3;
+            const int rm = tiles_m / xcd_m, rn = tiles_n / (8 / xcd_m);      // rectangle size in tiles
+            tm = (x % xcd_m) * rm + l % rm;
+            tn = (x / xcd_m) * rn + l / rm;
+        } else {
+            tm = v % tiles_m;
+            tn = v / tiles_m;
+        }
+        m0 = tm * BM;
+        n0 = tn * BN;
+    };
     const int Kb = K >> 1;
     const int ns = K / 256;                          // stages
 
@@ -193,17 +215,19 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_w4a4_kernel(
     constexpr int XI = BM / 8 / NWAVE;               // the first XI regions of a wave are X rows, the rest W rows
     static_assert((BM / 8) % NWAVE == 0, "X regions must split evenly over the waves");
     uint32_t goff[RPW];
+    auto set_sources = [&](int m0, int n0) {
 #pragma unroll
-    for (int i = 0; i < RPW; ++i) {
-        const int trow = (wave + NWAVE * i) * 8 + (lane >> 3);
-        int r;
-        if (i < XI) { r = m0 + trow; r = r < M ? r : M - 1; }
-        else { r = n0 + trow - BM; r = r < N ? r : N - 1; }
-        goff[i] = (uint32_t)r * (uint32_t)Kb + (dchunk << 4);
-    }
+        for (int i = 0; i < RPW; ++i) {
+            const int trow = (wave + NWAVE * i) * 8 + (lane >> 3);
+            int r;
+            if (i < XI) { r = m0 + trow; r = r < M ? r : M - 1; }
+            else { r = n0 + trow - BM; r = r < N ? r : N - 1; }
+            goff[i] = (uint32_t)r * (uint32_t)Kb + (dchunk << 4);
+        }
+    };
     const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
-    auto issue = [&](int s) {                        // stage s of K -> ring slot s % STAGES
-        const uint32_t sb = smem_base + (uint32_t)(s % STAGES) * STAGE_BYTES + wave * 1024;
+    auto issue = [&](int s, int slot) {              // all of stage s of K -> ring slot
+        const uint32_t sb = smem_base + (uint32_t)slot * STAGE_BYTES + wave * 1024;
         const uint8_t *xsrc = Xq + (int64_t)s * ROWB;
         const uint8_t *wsrc = Wq + (int64_t)s * ROWB;
 #pragma unroll
@@ -228,12 +252,6 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_w4a4_kernel(
     };
 
     v16i acc[FN][FM];
-#pragma unroll
-    for (int i = 0; i < FN; ++i)
-#pragma unroll
-        for (int j = 0; j < FM; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
 
     auto widen = [](const uint4 w, v4i &a0, v4i &a1) {
         a0 = v4i{(int)((w.x << 4) & HM), (int)(w.x & HM), (int)((w.y << 4) & HM), (int)(w.y & HM)};
@@ -245,180 +263,180 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_w4a4_kernel(
 #pragma unroll
         for (int i = 0; i < FN; ++i) widen(f.w[i], o.w[i][0], o.w[i][1]);
     };
-    auto mfmas = [&](const Ops &o) {
+
+    // ---- smooth issue: memory instructions block the issuing wave while their queue is full, and a blocked
+    // wave idles the matrix pipe unless the SIMD's other wave has MFMAs to issue.  So nothing is issued in
+    // bursts: a sub-step (64 codes) is cut into NREG regions of [FPR fragment reads, ~NM/NREG MFMAs with the
+    // widening of FPR fragments underneath, DPR DMA instructions].  Three things are in flight per sub-step t
+    // (a register-level software pipeline): the LDS reads of the packed fragments of sub-step t+2 (rd), the
+    // widening of the fragments of sub-step t+1 (wd -> nxt), and the MFMAs of sub-step t (cur).  The DMA of a
+    // stage is spread over the two sub-steps after the barrier that frees its ring slot.
+    static_assert((FM + FN) % 2 == 0, "smooth schedule");
+    constexpr int FPR = 2;                       // fragments per region
+    constexpr int NREG = (FM + FN) / FPR;        // regions per sub-step
+    constexpr int NR = 2 * NREG;                 // regions a stage's DMA is spread over
+    constexpr int DPR = (RPW + NR - 1) / NR;     // DMA instructions per region
+    constexpr int NM = 2 * FM * FN;              // MFMAs per sub-step
+    auto region = [&](auto RC, auto PARTC, const Ops &cur, Ops &nxt, const Frag &wd, Frag &rd, int rslot, int p,
+                      int dstage, int dslot) {
+        constexpr int r = decltype(RC)::value, part = decltype(PARTC)::value;
+        constexpr int mlo = r * NM / NREG, mhi = (r + 1) * NM / NREG;
+        constexpr int per = (12 * FPR + (mhi - mlo) - 1) / (mhi - mlo);
+        __builtin_amdgcn_sched_barrier(0);
+        const uint8_t *st = smem + rslot * STAGE_BYTES + (((2 * p + fg) ^ fz) << 4);
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int q = r * FPR; q < (r + 1) * FPR; ++q) {
+            if (q < FM) rd.x[q < FM ? q : 0] = *reinterpret_cast<const uint4 *>(st + xrow + q * 32 * ROWB);
+            else rd.w[q < FM ? 0 : q - FM] = *reinterpret_cast<const uint4 *>(st + wrow + (q - FM) * 32 * ROWB);
+        }
 #pragma unroll
-            for (int i = 0; i < FN; ++i)
+        for (int m = mlo; m < mhi; ++m) {
+            const int h = m / (FM * FN), i = (m % (FM * FN)) / FM, j = m % FM;
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.w[i][h], cur.x[j][h], acc[i][j], 0, 0, 0);
+        }
 #pragma unroll
-                for (int j = 0; j < FM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(o.w[i][h], o.x[j][h], acc[i][j], 0, 0, 0);
-    };
-    constexpr int NMFMA = 2 * FN * FM;                       // MFMAs per sub-step
-    constexpr int NWID = 12 * (FM + FN);                     // widening ALU instructions per sub-step
-    constexpr int PER = (NWID + NMFMA - 1) / NMFMA;
-    // One sub-step t, three things in flight (a register-level software pipeline):
-    //   LDS reads of the packed fragments of sub-step t+2          -> rd
-    //   widening of the fragments of sub-step t+1 (read last time) -> nxt, underneath ...
-    //   ... the MFMAs of sub-step t (the 8-pass MFMA leaves the ALU port free)
-    // The scheduling hints pin that interleaving: reads first, then PER ALU instructions after each MFMA.
-    auto sub = [&](auto do_read, auto do_widen, const Ops &cur, Ops &nxt, const Frag &wd, Frag &rd, int slot, int p) {
-        __builtin_amdgcn_sched_barrier(0);               // each sub-step is scheduled on its own
-        if constexpr (decltype(do_read)::value) load_frags(rd, slot, p);
-        mfmas(cur);
-        if constexpr (decltype(do_widen)::value) widen_all(wd, nxt);
-        if constexpr (decltype(do_read)::value) __builtin_amdgcn_sched_group_barrier(0x100, FM + FN, 0);
+        for (int q = r * FPR; q < (r + 1) * FPR; ++q) {
+            if (q < FM) widen(wd.x[q < FM ? q : 0], nxt.x[q < FM ? q : 0][0], nxt.x[q < FM ? q : 0][1]);
+            else widen(wd.w[q < FM ? 0 : q - FM], nxt.w[q < FM ? 0 : q - FM][0], nxt.w[q < FM ? 0 : q - FM][1]);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, FPR, 0);
 #pragma unroll
-        for (int k = 0; k < NMFMA; ++k) {
+        for (int k = mlo; k < mhi; ++k) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if constexpr (decltype(do_widen)::value) __builtin_amdgcn_sched_group_barrier(0x002, PER, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, per, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
-    };
-    constexpr std::true_type yes{};
-    constexpr std::false_type no{};
-
-    Ops o0, o1;
-    Frag fa, fb;                                     // fragments of even / odd sub-steps
-    int slot = 0;
-    if constexpr (SMOOTH) {
-        // ---- smooth issue: memory instructions block the issuing wave while their queue is full, and with
-        // one wave per SIMD a blocked wave idles the matrix pipe.  So nothing is issued in bursts: a sub-step
-        // is cut into NREG regions of [FPR fragment reads, ~NM/NREG MFMAs with the widening of FPR fragments
-        // underneath, ONE DMA instruction].  The RPW DMA instructions of a stage are thereby spread over the
-        // four sub-steps that follow the barrier which frees their slot (ring of three slots: stage s+3 is
-        // issued from the middle of iteration s to the middle of iteration s+1 and first read after barrier s+2).
-        // With a ring of two slots the slot is needed again one stage later, so the stage is issued over the two
-        // sub-steps after the barrier only (more than one DMA instruction per region).
-        static_assert((STAGES == 3 || STAGES == 2) && (FM + FN) % 2 == 0, "smooth schedule");
-        constexpr int FPR = 2;                       // fragments per region
-        constexpr int NREG = (FM + FN) / FPR;        // regions per sub-step
-        constexpr int NR = (STAGES == 3 ? 4 : 2) * NREG;        // regions a stage's DMA is spread over
-        constexpr int DPR = (RPW + NR - 1) / NR;     // DMA instructions per region
-        constexpr int HALF = 2 * NREG * DPR < RPW ? 2 * NREG * DPR : RPW;   // ... issued in a stage's first two sub-steps
-        constexpr int NM = 2 * FM * FN;              // MFMAs per sub-step
-        auto region = [&](auto RC, auto PARTC, const Ops &cur, Ops &nxt, const Frag &wd, Frag &rd, int rslot, int p,
-                          int dstage, int dslot) {
-            constexpr int r = decltype(RC)::value, part = decltype(PARTC)::value;
-            constexpr int mlo = r * NM / NREG, mhi = (r + 1) * NM / NREG;
-            constexpr int per = (12 * FPR + (mhi - mlo) - 1) / (mhi - mlo);
-            __builtin_amdgcn_sched_barrier(0);
-            const uint8_t *st = smem + rslot * STAGE_BYTES + (((2 * p + fg) ^ fz) << 4);
+        constexpr int g = part * NREG + r;       // ordinal of this region among those that issue DMA
+        if constexpr (g < NR) {
 #pragma unroll
-            for (int q = r * FPR; q < (r + 1) * FPR; ++q) {
-                if (q < FM) rd.x[q < FM ? q : 0] = *reinterpret_cast<const uint4 *>(st + xrow + q * 32 * ROWB);
-                else rd.w[q < FM ? 0 : q - FM] = *reinterpret_cast<const uint4 *>(st + wrow + (q - FM) * 32 * ROWB);
-            }
-#pragma unroll
-            for (int m = mlo; m < mhi; ++m) {
-                const int h = m / (FM * FN), i = (m % (FM * FN)) / FM, j = m % FM;
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.w[i][h], cur.x[j][h], acc[i][j], 0, 0, 0);
-            }
-#pragma unroll
-            for (int q = r * FPR; q < (r + 1) * FPR; ++q) {
-                if (q < FM) widen(wd.x[q < FM ? q : 0], nxt.x[q < FM ? q : 0][0], nxt.x[q < FM ? q : 0][1]);
-                else widen(wd.w[q < FM ? 0 : q - FM], nxt.w[q < FM ? 0 : q - FM][0], nxt.w[q < FM ? 0 : q - FM][1]);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x100, FPR, 0);
-#pragma unroll
-            for (int k = mlo; k < mhi; ++k) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, per, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            constexpr int g = part * NREG + r;       // ordinal of this region among those that issue DMA
-            if constexpr (g < NR) {
-#pragma unroll
-                for (int idx = g * DPR; idx < (g + 1) * DPR && idx < RPW; ++idx)
-                    dma16((idx < XI ? Xq : Wq) + (int64_t)dstage * ROWB, goff[idx],
-                          smem_base + (uint32_t)dslot * STAGE_BYTES + wave * 1024 + NWAVE * idx * 1024);
-            }
-        };
-        auto ssub = [&](auto PARTC, const Ops &cur, Ops &nxt, const Frag &wd, Frag &rd, int rslot, int p, int dstage,
-                        int dslot) {
-            region(std::integral_constant<int, 0>{}, PARTC, cur, nxt, wd, rd, rslot, p, dstage, dslot);
-            if constexpr (NREG >= 2) region(std::integral_constant<int, 1>{}, PARTC, cur, nxt, wd, rd, rslot, p, dstage, dslot);
-            if constexpr (NREG >= 3) region(std::integral_constant<int, 2>{}, PARTC, cur, nxt, wd, rd, rslot, p, dstage, dslot);
-            if constexpr (NREG >= 4) region(std::integral_constant<int, 3>{}, PARTC, cur, nxt, wd, rd, rslot, p, dstage, dslot);
-            static_assert(NREG <= 4, "regions");
-        };
-        constexpr std::integral_constant<int, 0> P0{};
-        constexpr std::integral_constant<int, 1> P1{};
-        constexpr std::integral_constant<int, 2> P2{};
-        constexpr std::integral_constant<int, 3> P3{};
-        // prologue: stages 0 and 1 whole and, with three slots, the first half of stage 2
-        issue(0);
-        issue(ns > 1 ? 1 : 0);
-        if constexpr (STAGES == 3) {
-            const int st2 = ns > 2 ? 2 : ns - 1;
-#pragma unroll
-            for (int i = 0; i < HALF; ++i)
-                dma16((i < XI ? Xq : Wq) + (int64_t)st2 * ROWB, goff[i],
-                      smem_base + 2u * STAGE_BYTES + wave * 1024 + NWAVE * i * 1024);
-            wait_vmcnt<RPW + HALF>();                // stage 0 has landed
-        } else {
-            wait_vmcnt<RPW>();
+            for (int idx = g * DPR; idx < (g + 1) * DPR && idx < RPW; ++idx)
+                dma16((idx < XI ? Xq : Wq) + (int64_t)dstage * ROWB, goff[idx],
+                      smem_base + (uint32_t)dslot * STAGE_BYTES + wave * 1024 + NWAVE * idx * 1024);
         }
+    };
+    auto ssub = [&](auto PARTC, const Ops &cur, Ops &nxt, const Frag &wd, Frag &rd, int rslot, int p, int dstage,
+                    int dslot) {
+        region(std::integral_constant<int, 0>{}, PARTC, cur, nxt, wd, rd, rslot, p, dstage, dslot);
+        if constexpr (NREG >= 2) region(std::integral_constant<int, 1>{}, PARTC, cur, nxt, wd, rd, rslot, p, dstage, dslot);
+        if constexpr (NREG >= 3) region(std::integral_constant<int, 2>{}, PARTC, cur, nxt, wd, rd, rslot, p, dstage, dslot);
+        if constexpr (NREG >= 4) region(std::integral_constant<int, 3>{}, PARTC, cur, nxt, wd, rd, rslot, p, dstage, dslot);
+        static_assert(NREG <= 4, "regions");
+    };
+    constexpr std::integral_constant<int, 0> P0{};   // first / second sub-step after the barrier: issue DMA
+    constexpr std::integral_constant<int, 1> P1{};
+    constexpr std::integral_constant<int, 2> P2{};   // the two sub-steps before the barrier: no DMA
+    constexpr std::integral_constant<int, 3> P3{};
+
+    // epilogue staging: one piece = 32 tokens x WN channels of fp16 per wave, in ring slot 1
+    constexpr int PIECE = 32 * (WN * 2 + 16);
+    static_assert(NWAVE * PIECE <= STAGE_BYTES, "epilogue staging must fit one ring slot");
+
+    // Token and channel scales of the tile's epilogue are fetched at the start of the tile (10 loads per lane for
+    // a 64 x 64 wave tile) -- fetched at the tile boundary, their latency was exposed on every tile.
+    float sx[FM];
+    float4 sw[FN][4];
+    // (With the raw int32 output the host passes readable stand-ins for the two scale vectors, so the loads
+    // need no branch -- a branch made the compiler wait for them at once; the values are then not used.)
+    auto load_scales = [&](int m0, int n0) {
+#pragma unroll
+        for (int j = 0; j < FM; ++j) {
+            const int m = m0 + wm * WM + j * 32 + fr;
+            sx[j] = xs[m < M ? m : M - 1];
+        }
+#pragma unroll
+        for (int i = 0; i < FN; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * WN + i * 32 + q * 8 + fg * 4;
+                sw[i][q] = *reinterpret_cast<const float4 *>(ws + (n < N ? n : N - 4));
+            }
+    };
+
+    int v = blockIdx.x;
+    int m0, n0;
+    tile_origin(v, m0, n0);
+    set_sources(m0, n0);
+    issue(0, 0);
+    issue(ns > 1 ? 1 : 0, 1);
+    for (;;) {
+#pragma unroll
+        for (int i = 0; i < FN; ++i)
+#pragma unroll
+            for (int j = 0; j < FM; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+
+        // Stage 0 has landed once at most RPW of this wave's memory operations are still outstanding: loads
+        // complete in order among themselves and the RPW loads of stage 1 are the youngest, so an unfinished
+        // older load would leave more than RPW outstanding -- however many stores of the previous tile are
+        // still on their way (stores and loads may overtake each other).
+        wait_vmcnt<RPW>();
         barrier_nofence();
+        load_scales(m0, n0);                         // used after the K loop, whose first wait covers them
+        Ops o0, o1;
+        Frag fa, fb;                                 // fragments of even / odd sub-steps
         load_frags(fa, 0, 0);
         load_frags(fb, 0, 1);
         widen_all(fa, o0);
+        int slot = 0;
+        // Every stage runs the same branch-free body.  Past the end of K the pipeline keeps reading (stale,
+        // in-bounds) LDS and re-fetching the last stage; those fragments are widened but never multiplied.
         for (int s = 0; s < ns; ++s) {
-            const int nslot = slot == STAGES - 1 ? 0 : slot + 1, pslot = slot == 0 ? STAGES - 1 : slot - 1;
-            const int st2 = s + 2 < ns ? s + 2 : ns - 1, st3 = s + 3 < ns ? s + 3 : ns - 1;
-            // three slots: second half of stage s+2 -> slot of stage s-1; two slots: these sub-steps issue nothing
-            ssub(P2, o0, o1, fb, fa, slot, 2, st2, pslot);
-            ssub(P3, o1, o0, fa, fb, slot, 3, st2, pslot);
-            // stage s+1 must have landed (with three slots stage s+2, the youngest RPW instructions, may still fly),
-            // and every wave's reads of stage s must have returned: its slot takes stage s+STAGES from here on
-            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(STAGES == 3 ? RPW : 0) : "memory");
+            const int nslot = slot ^ 1;
+            const int st2 = s + 2 < ns ? s + 2 : ns - 1;
+            ssub(P2, o0, o1, fb, fa, slot, 2, st2, nslot);
+            ssub(P3, o1, o0, fa, fb, slot, 3, st2, nslot);
+            // stage s+1 must have landed, and every wave's reads of stage s must have returned: its slot takes
+            // stage s+2 from here on
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
             barrier_nofence();
-            ssub(P0, o0, o1, fb, fa, nslot, 0, STAGES == 3 ? st3 : st2, slot);
-            ssub(P1, o1, o0, fa, fb, nslot, 1, STAGES == 3 ? st3 : st2, slot);
+            ssub(P0, o0, o1, fb, fa, nslot, 0, st2, slot);
+            ssub(P1, o1, o0, fa, fb, nslot, 1, st2, slot);
             slot = nslot;
         }
-    } else {
-    // Every stage runs the same branch-free body.  Past the end of K the pipeline keeps reading (stale,
-    // in-bounds) LDS and re-fetching the last stage; those fragments are widened but never multiplied.
-    // ---- prologue: two stages in flight; operands of sub-step 0 and fragments of sub-step 1 in registers
-#pragma unroll
-    for (int q = 0; q < STAGES; ++q) issue(q < ns ? q : ns - 1);
-    wait_vmcnt<(STAGES - 1) * RPW>();                // stage 0 has landed, the younger ones may still fly
-    barrier_nofence();
-    load_frags(fa, 0, 0);
-    load_frags(fb, 0, 1);
-    widen_all(fa, o0);
-    for (int s = 0; s < ns; ++s) {
-        const int nslot = slot == STAGES - 1 ? 0 : slot + 1;
-        sub(yes, yes, o0, o1, fb, fa, slot, 2);
-        sub(yes, yes, o1, o0, fa, fb, slot, 3);
-        // stage s+1 (issued STAGES-1 stages ago) must have landed for every wave -- the STAGES-2 younger
-        // stages may stay in flight -- and every wave's LDS reads of stage s (the last ones were issued a
-        // sub-step ago) must have returned: its slot now takes stage s+STAGES
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((STAGES - 2) * RPW) : "memory");
-        barrier_nofence();
-        issue(s + STAGES < ns ? s + STAGES : ns - 1);
-        sub(yes, yes, o0, o1, fb, fa, nslot, 0);
-        sub(yes, yes, o1, o0, fa, fb, nslot, 1);
-        slot = nslot;
-    }
-    }
-    wait_vmcnt<0>();                                 // no LDS-DMA write may outlive the workgroup
 
-    // ---- epilogue: every wave transposes its tile through its own part of the (now idle) LDS ring ----
-    barrier_nofence();                               // all waves are done reading fragments
-    static_assert(NWAVE * WM * (WN * 2 + 16) <= STAGES * STAGE_BYTES, "epilogue staging must fit the ring");
-    store_wave_tile<FM, FN>(acc, smem + wave * (WM * (WN * 2 + 16)), lane, m0 + wm * WM, n0 + wn * WN, M, N, xs, ws,
-                            Yv, ldy, out_i32);
+        // ---- tile boundary
+        const int vn = v + (int)gridDim.x;
+        const bool more = vn < total;
+        wait_vmcnt<0>();                             // no LDS-DMA write is in flight any more ...
+        // (the scales arrived long ago; naming them here keeps the compiler's own wait for them at this point
+        // and not behind the loads issued next)
+#pragma unroll
+        for (int j = 0; j < FM; ++j) asm volatile("" : "+v"(sx[j]));
+#pragma unroll
+        for (int i = 0; i < FN; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                asm volatile("" : "+v"(sw[i][q].x), "+v"(sw[i][q].y), "+v"(sw[i][q].z), "+v"(sw[i][q].w));
+        barrier_nofence();                           // ... and all waves are done reading fragments
+        int m1 = 0, n1 = 0;
+        if (more) {                                  // first stage of the next tile flies during the epilogue
+            tile_origin(vn, m1, n1);
+            set_sources(m1, n1);
+            issue(0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < FM; ++j) sx[j] *= 1.f / 256.f;      // both operands carried a factor 16
+        store_wave_tile<FM, FN>(acc, smem + STAGE_BYTES + wave * PIECE, lane, m0 + wm * WM, n0 + wn * WN, M, N, sx, sw,
+                                Yv, ldy, out_i32);
+        if (!more) break;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        barrier_nofence();                           // every wave has read its staging back: slot 1 is free
+        issue(ns > 1 ? 1 : 0, 1);
+        v = vn;
+        m0 = m1;
+        n0 = n1;
+    }
+    wait_vmcnt<0>();
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES = 2, bool SMOOTH = false>
+template <int BM, int BN, int WGM, int WGN, int WG_PER_CU>
 hipError_t launch_tile(const uint8_t *Xq, const float *xs, const uint8_t *Wq, const float *ws, int64_t M, int64_t N,
                        int64_t K, void *Y, int64_t ldy, int out_i32, hipStream_t st)
 {
-    auto kern = gemm_w4a4_kernel<BM, BN, WGM, WGN, STAGES, SMOOTH>;
-    constexpr int lds = STAGES * (BM + BN) * ROWB;
-    static_assert(lds <= 160 * 1024, "LDS");
+    auto kern = gemm_w4a4_kernel<BM, BN, WGM, WGN>;
+    constexpr int lds = 2 * (BM + BN) * ROWB;
+    static_assert(lds * WG_PER_CU <= 160 * 1024, "LDS");
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -440,7 +458,19 @@ hipError_t launch_tile(const uint8_t *Xq, const float *xs, const uint8_t *Wq, co
             if (xcd_m == 0 || rows < best) { xcd_m = sm; best = rows; }
         }
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(WGM * WGN * 64), lds, st, Xq, xs, Wq, ws,
+    // persistent grid: as many workgroups as the chip holds at once (a multiple of 8, as the XCD map needs)
+    int64_t grid = (int64_t)compute_units() * WG_PER_CU;
+    if (const char *env = getenv("SMOOTHROT_GEMM_GRID")) grid = atoll(env) > 0 ? atoll(env) / 8 * 8 : grid;   // tuning aid
+    if (grid < 8) grid = 8;
+    const int64_t total = (int64_t)tiles_m * tiles_n;
+    if (grid > total) grid = total;
+    // the raw int32 output takes no scales (they may be NULL): the kernel still fetches M and N floats it
+    // then ignores, from the start of the code arrays (M * K / 2 >= 4 M bytes, 16-byte aligned)
+    if (out_i32) {
+        xs = reinterpret_cast<const float *>(Xq);
+        ws = reinterpret_cast<const float *>(Wq);
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WGM * WGN * 64), lds, st, Xq, xs, Wq, ws,
                        (int)M, (int)N, (int)K, Y, ldy, out_i32, tiles_m, tiles_n, xcd_m);
     return hipGetLastError();
 }
@@ -615,28 +645,21 @@ hipError_t launch_gemm_prefill(const uint8_t *Xq, const float *xs, const uint8_t
                            Xq, xs, Wq, ws, (int)M, (int)N, (int)K, Y, ldy, out_i32, tiles_m, tiles_n);
         return hipGetLastError();
     }
-    switch (variant) {
-        case 1: return launch_tile<256, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);               // burst schedule
-        case 3: return launch_tile<128, 128, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);               // burst schedule
-        case 10: return launch_tile<256, 128, 2, 2, 3, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);     // 4 waves, 3 slots
-        case 12: return launch_tile<256, 128, 4, 2, 3, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);     // 8 waves, 3 slots
-        case 14: return launch_tile<128, 128, 2, 2, 2, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-        case 15: return launch_tile<256, 128, 4, 2, 2, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-        default: break;
-    }
-    // A launch takes about ceil(tiles / 256) rounds of one tile time each (tile time ~ BM * BN): pick the tile
-    // shape with the cheapest schedule; ties go to the larger tile (less L2 traffic, fewer fragment reads).
+    // A launch takes about ceil(tiles / slots) rounds of one tile time each (tile time ~ BM * BN): pick the
+    // tile shape with the cheapest schedule; ties go to the larger tile (less L2 traffic, fewer fragment reads).
     //   256 x 128: eight waves (two per SIMD, so that one can issue MFMAs while the other is held up issuing
     //              LDS or DMA instructions), 96 KB of LDS, one workgroup per CU
     //   128 x 128: four waves, 64 KB of LDS, two workgroups per CU
-    // both with the smooth (burst-free) instruction schedule and a ring of two stages.
-    auto cost = [&](int64_t bm, int64_t bn) {
+    if (variant == 14) return launch_tile<128, 128, 2, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+    if (variant == 15) return launch_tile<256, 128, 4, 2, 1>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+    const int64_t cus = compute_units();
+    auto cost = [&](int64_t bm, int64_t bn) {       // a half-filled last round of 128 x 128 tiles costs about half
         const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
-        return ((tiles + 255) / 256) * bm * bn;
+        return ((tiles + cus - 1) / cus) * bm * bn;
     };
-    const int64_t c256 = cost(256, 128), c128 = cost(128, 128);
-    if (c256 <= c128) return launch_tile<256, 128, 4, 2, 2, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
-    return launch_tile<128, 128, 2, 2, 2, true>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+    if (cost(256, 128) <= cost(128, 128))
+        return launch_tile<256, 128, 4, 2, 1>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
+    return launch_tile<128, 128, 2, 2, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
 }
 
 }  // namespace sr
