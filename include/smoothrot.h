@@ -234,6 +234,58 @@ SR_API int sr_w4a4_linear_decode(const void *X_f16, int64_t M, int64_t K, int64_
                           void *Y_f16, int64_t ldy,
                           uint8_t *Xq_out, float *x_scale_out, void *stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Fast prefill path: the same INT4 x INT4 product on the FP6 matrix pipe.
+ *
+ * gfx950 multiplies 6-bit floats at twice its int8 rate, and the 6-bit format E2M3 holds every
+ * INT4 code exactly (value code / 8; pattern (code < 0 ? 32 : 0) | |code|), so the sums of the
+ * paper's quantised forward pass come out bit for bit as from integer arithmetic (fp32
+ * accumulation of integers / 64 below 2^24).  The operands are kept in "f6 tiles", a layout the
+ * matrix instruction reads without any unpacking:
+ *
+ *   a code matrix [rows, K] (K % 128 == 0; rows padded with zero codes to a multiple of 8) is
+ *   cut into blocks of 8 rows x 128 codes; block (R, C) is 768 bytes at ((C * rows/8) + R) * 768
+ *   (all row blocks of one 128-code chunk are contiguous);
+ *   inside it, piece (r, t, g) = codes k = 128 C + 64 t + 32 g + j, j = 0..31, of row 8 R + r,
+ *   code j in bits [6j, 6j+6) of a 24-byte little-endian string, whose first 16 bytes sit at
+ *   256 t + 128 (g ^ (R & 1)) + 16 r and whose last 8 bytes at 512 + 64 ((2t + g) ^ (R & 3)) + 8 r.
+ * ------------------------------------------------------------------------------------------ */
+
+/* Bytes of the f6-tile form of a [rows, K] code matrix (0 if K % 128 != 0 or a size is <= 0). */
+SR_API size_t sr_f6_tiles_bytes(int64_t rows, int64_t K);
+
+/*
+ * Repack canonical packed INT4 codes into f6 tiles (weights: once, offline; activations:
+ * sr_fwht_quant_act_f6 writes the tiles directly).
+ *   Q4   uint8 [rows, K/2] as written by the fold / the activation quantiser
+ *   T6   out, sr_f6_tiles_bytes(rows, K) bytes, 16-byte aligned
+ *   K a multiple of 128, rows * K < 2^32.
+ */
+SR_API int sr_pack_f6_tiles(const uint8_t *Q4, int64_t rows, int64_t K, uint8_t *T6, void *stream);
+
+/*
+ * sr_fwht_quant_act writing the activation codes as f6 tiles (same rotation, same quantiser, same
+ * scales; the codes are the ones sr_fwht_quant_act would pack as nibbles).
+ *   X6   out, sr_f6_tiles_bytes(M, K) bytes, 16-byte aligned; the rows that pad the last block of
+ *        8 are left unwritten (the GEMM never stores their outputs)
+ *   K    a supported Hadamard order that is a multiple of 128
+ */
+SR_API int sr_fwht_quant_act_f6(const void *X_f16, int64_t M, int64_t K, int64_t ldx,
+                         const float *inv_s, float clip,
+                         uint8_t *X6, float *x_scale, void *stream);
+
+/*
+ * sr_w4a4_gemm on f6-tile operands: same sums (exact), same epilogue, same outputs.
+ *   X6 = tiles of the activation codes [M, K], W6 = tiles of the weight codes [N, K].
+ *   K a multiple of 128, K < 131072; N a multiple of 16; M * K and N * K below 2^32.
+ *   workspace: none needed (pass NULL, 0).
+ */
+SR_API int sr_w4a4_gemm_f6(const uint8_t *X6, const float *x_scale,
+                    const uint8_t *W6, const float *w_scale,
+                    int64_t M, int64_t N, int64_t K,
+                    void *Y, int64_t ldy, int out_dtype,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -36,6 +36,10 @@ _SIGNATURES = {
     "sr_fold_smooth_rotate_quant_ex": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _i64, _int, _int, _f32,
                                                _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "sr_kv_quant_asym": (_int, [_vp, _i64, _i64, _i64, _i64, _f32, _vp, _vp, _vp, _vp]),
+    "sr_f6_tiles_bytes": (_sz, [_i64, _i64]),
+    "sr_pack_f6_tiles": (_int, [_vp, _i64, _i64, _vp, _vp]),
+    "sr_fwht_quant_act_f6": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _vp]),
+    "sr_w4a4_gemm_f6": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _int, _vp, _sz, _vp]),
     "sr_w4a4_linear_decode": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _vp]),
 }
 
@@ -237,3 +241,45 @@ def sr_w4a4_linear_decode(X, inv_s, Wq, w_scale, clip: float = 0.9, Y=None, Xq_o
     _check(raw().sr_w4a4_linear_decode(_ptr(X), M, K, ldx, _ptr(inv_s), clip, _ptr(Wq), _ptr(w_scale), N, _ptr(Y),
                                        ldy, _ptr(Xq_out), _ptr(x_scale_out), _stream()), "sr_w4a4_linear_decode")
     return Y
+
+
+def sr_f6_tiles_bytes(rows: int, K: int) -> int:
+    return int(raw().sr_f6_tiles_bytes(rows, K))
+
+
+def sr_pack_f6_tiles(Q4, T6=None):
+    """Q4 uint8 [rows, K/2] (canonical packed INT4 codes) -> T6 uint8 [sr_f6_tiles_bytes(rows, K)] (f6 tiles)."""
+    _dev(Q4, torch.uint8, "Q4")
+    if not Q4.is_contiguous():
+        raise ValueError("Q4 must be contiguous")
+    rows, Kb = Q4.shape
+    if T6 is None:
+        T6 = torch.empty(max(sr_f6_tiles_bytes(rows, 2 * Kb), 16), dtype=torch.uint8, device=Q4.device)
+    _check(raw().sr_pack_f6_tiles(_ptr(Q4), rows, 2 * Kb, _ptr(T6), _stream()), "sr_pack_f6_tiles")
+    return T6
+
+
+def sr_w4a4_gemm_f6(X6, x_scale, W6, w_scale, M: int, N: int, K: int, out_dtype: int = SR_F16, Y=None):
+    """X6, W6 = f6 tiles of the codes [M, K] and [N, K] -> Y [M, N] fp16 (dequantised) or int32 (accumulators)."""
+    _dev(X6, torch.uint8, "X6"); _dev(W6, torch.uint8, "W6")
+    if X6.numel() < sr_f6_tiles_bytes(M, K) or W6.numel() < sr_f6_tiles_bytes(N, K):
+        raise ValueError("tile buffers are smaller than sr_f6_tiles_bytes says")
+    if Y is None:
+        Y = torch.empty((M, N), dtype=torch.float16 if out_dtype == SR_F16 else torch.int32, device=X6.device)
+    ldy = Y.stride(0) if M > 1 else N
+    _check(raw().sr_w4a4_gemm_f6(_ptr(X6), _ptr(x_scale), _ptr(W6), _ptr(w_scale), M, N, K, _ptr(Y), ldy,
+                                 out_dtype, None, 0, _stream()), "sr_w4a4_gemm_f6")
+    return Y
+
+
+def sr_fwht_quant_act_f6(X, inv_s, clip: float = 0.9, X6=None, x_scale=None):
+    """X fp16 [M, K] -> (X6 uint8 [sr_f6_tiles_bytes(M, K)] f6 tiles of the codes, x_scale fp32 [M])."""
+    _dev(X, torch.float16, "X")
+    M, K = X.shape
+    if X6 is None:
+        X6 = torch.zeros(max(sr_f6_tiles_bytes(M, K), 16), dtype=torch.uint8, device=X.device)
+    x_scale = torch.empty(M, dtype=torch.float32, device=X.device) if x_scale is None else x_scale
+    ldx = X.stride(0) if M > 1 else K
+    _check(raw().sr_fwht_quant_act_f6(_ptr(X), M, K, ldx, _ptr(inv_s), clip, _ptr(X6), _ptr(x_scale), _stream()),
+           "sr_fwht_quant_act_f6")
+    return X6, x_scale

@@ -21,7 +21,8 @@
 namespace sr {
 namespace {
 
-template <int K, int NT>
+// F6: Q receives f6 tiles (operands of the FP6-MFMA GEMM) instead of packed nibbles; K % 128 == 0 then.
+template <int K, int NT, bool F6>
 __global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict__ X, int64_t ldx,
                                                         const float *__restrict__ pre, float clip,
                                                         float post_scale, uint8_t *__restrict__ Q,
@@ -39,14 +40,21 @@ __global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict
     const float inv_delta = 1.f / delta;
     if (t == 0) scale_out[m] = (amax == 0.f) ? 1.f : delta * post_scale;
 
-    // ---- quantise 8 contiguous values -> one packed dword ---------------------------------
+    // ---- quantise 8 contiguous values -> one packed dword (or 48 bits of a tile piece) ---------
     uint32_t *q = reinterpret_cast<uint32_t *>(Q + m * (int64_t)(K / 2));
+    const int64_t row_blocks = ((int64_t)gridDim.x + 7) >> 3;
     for (int c = t; c < K / 8; c += NT) {
         const float *src = row + pad(8 * c);
         const float4 a = *reinterpret_cast<const float4 *>(src);
         const float4 b = *reinterpret_cast<const float4 *>(src + 4);
         const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        q[c] = quant_pack8(v, inv_delta);
+        if constexpr (F6) {
+            uint32_t lo, hi;
+            quant_f6_8(v, inv_delta, lo, hi);
+            store_f6_piece(lo, hi, t, Q, row_blocks, m, c >> 2);     // K / 8 and NT are multiples of 4: whole quads
+        } else {
+            q[c] = quant_pack8(v, inv_delta);
+        }
     }
 }
 
@@ -212,7 +220,7 @@ __global__ __launch_bounds__(NT) void fwht_quant_ex_kernel(const __half *__restr
 //   lane quantises 8 consecutive values into one packed dword.
 // ------------------------------------------------------------------------------------------
 
-template <bool HAS_PRE>
+template <bool HAS_PRE, bool F6>
 __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__restrict__ X, int64_t ldx, int64_t rows,
                                                             const float *__restrict__ pre, float clip, float post_scale,
                                                             uint8_t *__restrict__ Q, float *__restrict__ scale_out)
@@ -276,18 +284,24 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
         const float4 a = *reinterpret_cast<const float4 *>(s8);
         const float4 b = *reinterpret_cast<const float4 *>(s8 + 4);
         const float y[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        q[64 * j + lane] = quant_pack8(y, inv_delta);
+        if constexpr (F6) {
+            uint32_t lo, hi;
+            quant_f6_8(y, inv_delta, lo, hi);
+            store_f6_piece(lo, hi, lane, Q, (rows + 7) >> 3, m, 16 * j + (lane >> 2));
+        } else {
+            q[64 * j + lane] = quant_pack8(y, inv_delta);
+        }
     }
 }
 
-template <int K>
+template <int K, bool F6 = false>
 hipError_t launch_one(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip,
                       float post_scale, uint8_t *Q, float *scale_out, hipStream_t st)
 {
     constexpr int groups = K / 16;
     constexpr int NT = groups >= 256 ? 256 : (groups >= 128 ? 128 : 64);
     constexpr size_t lds = sizeof(float) * padded_len(K);
-    auto kern = fwht_quant_kernel<K, NT>;
+    auto kern = fwht_quant_kernel<K, NT, F6>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -322,31 +336,42 @@ hipError_t launch_one_ex(const void *X, int64_t rows, int64_t ldx, const float *
 // and the workgroup-per-row kernel has the shorter critical path.
 constexpr int64_t kWaveKernelMinRows = 1024;   // measured: 3.3 - 4.8 us against 4.2 - 5.9 us up to 512 rows, equal at 1024
 
-hipError_t launch_fwht_quant(const void *X, int64_t rows, int64_t K, int64_t ldx, const float *pre,
-                             float clip, float post_scale, uint8_t *Q, float *scale_out, hipStream_t st)
+template <bool HAS_PRE, bool F6>
+hipError_t launch_wave4096(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip, float post_scale,
+                           uint8_t *Q, float *scale_out, hipStream_t st)
 {
-#define SR_CASE(KK) case KK: return launch_one<KK>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
+    constexpr size_t lds = 4 * (4096 + 64) * sizeof(float);
+    const unsigned blocks = (unsigned)((rows + 3) / 4);
+    auto kern = fwht4096_wave_kernel<HAS_PRE, F6>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, static_cast<const __half *>(X), ldx, rows, pre, clip,
+                       post_scale, Q, scale_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_fwht_quant(const void *X, int64_t rows, int64_t K, int64_t ldx, const float *pre,
+                             float clip, float post_scale, uint8_t *Q, float *scale_out, hipStream_t st, bool f6)
+{
     int pick = 0;
     if (const char *env = getenv("SMOOTHROT_FWHT4096")) pick = atoi(env);
     if (K == 4096 && (pick == 1 || (pick == 0 && rows > kWaveKernelMinRows))) {
-        constexpr size_t lds = 4 * (4096 + 64) * sizeof(float);
-        const unsigned blocks = (unsigned)((rows + 3) / 4);
-        hipError_t e;
-        if (pre) {
-            auto kern = fwht4096_wave_kernel<true>;
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, static_cast<const __half *>(X), ldx, rows, pre, clip,
-                               post_scale, Q, scale_out);
-        } else {
-            auto kern = fwht4096_wave_kernel<false>;
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, static_cast<const __half *>(X), ldx, rows, pre, clip,
-                               post_scale, Q, scale_out);
-        }
-        return hipGetLastError();
+        if (pre) return f6 ? launch_wave4096<true, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st)
+                           : launch_wave4096<true, false>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
+        return f6 ? launch_wave4096<false, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st)
+                  : launch_wave4096<false, false>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
     }
+    if (f6) {
+#define SR_CASE(KK) case KK: return launch_one<KK, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
+        switch (K) {                                    // K % 128 == 0
+            SR_CASE(128) SR_CASE(256) SR_CASE(512) SR_CASE(1024) SR_CASE(2048)
+            SR_CASE(4096) SR_CASE(8192) SR_CASE(16384) SR_CASE(32768)
+            SR_CASE(896) SR_CASE(1792) SR_CASE(3584) SR_CASE(7168) SR_CASE(14336) SR_CASE(28672)
+            default: return hipErrorInvalidValue;
+        }
+#undef SR_CASE
+    }
+#define SR_CASE(KK) case KK: return launch_one<KK>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
     switch (K) {
         SR_CASE(64) SR_CASE(128) SR_CASE(256) SR_CASE(512) SR_CASE(1024) SR_CASE(2048)
         SR_CASE(4096) SR_CASE(8192) SR_CASE(16384) SR_CASE(32768)

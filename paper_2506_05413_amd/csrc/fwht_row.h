@@ -208,6 +208,45 @@ __device__ __forceinline__ uint32_t quant_pack8(const float (&y)[8], float inv_d
     return (word - pack_bias()) ^ 0x88888888u;
 }
 
+// ---- the same quantiser writing "f6 tiles" (operand layout of the FP6-MFMA GEMM, see gemm_f6.hip) ----------
+// A code c becomes the 6-bit sign-magnitude field (c < 0 ? 32 : 0) | |c| (the E2M3 pattern of c / 8).  Rounding
+// |y| / Delta to nearest-even and clamping the magnitude to 7 (8 for negative values) gives the same code as
+// clamp(rint(y / Delta), -8, 7); a negative value that rounds to 0 becomes the field 32 (-0), which multiplies
+// like 0.  Eight consecutive values give 48 bits: lo = bits 0..31, hi = bits 32..47.
+__device__ __forceinline__ void quant_f6_8(const float (&y)[8], float inv_delta, uint32_t &lo, uint32_t &hi)
+{
+    const float magic = __uint_as_float(kMagicBits);
+    uint32_t f[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const uint32_t sign = __float_as_uint(y[e]) >> 31;
+        const uint32_t bits = __float_as_uint(fmaf(fabsf(y[e]), inv_delta, magic));
+        f[e] = (min(bits, kMagicBits + 7u + sign) - kMagicBits) | (sign << 5);
+    }
+    lo = f[0] | (f[1] << 6) | (f[2] << 12) | (f[3] << 18) | (f[4] << 24) | (f[5] << 30);
+    hi = (f[5] >> 2) | (f[6] << 4) | (f[7] << 10);
+}
+
+// Four neighbouring lanes (a quad, lane & 3 = 0..3) hold the 48-bit strings of 32 consecutive values = one
+// 24-byte piece of the tile layout: piece p of row m covers k = 32 p .. 32 p + 31.  Lane 0 of the quad stores
+// the first 16 bytes, lane 2 the last 8.  All four lanes must be active.
+__device__ __forceinline__ void store_f6_piece(uint32_t lo, uint32_t hi, int lane, uint8_t *__restrict__ T6,
+                                               int64_t row_blocks, int64_t m, int p)
+{
+    const uint32_t lo_n1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)lo, 0x39, 0xF, 0xF, true);   // from lane + 1 of the quad
+    const uint32_t hi_n1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)hi, 0x39, 0xF, 0xF, true);
+    const uint32_t lo_n2 = (uint32_t)__builtin_amdgcn_mov_dpp((int)lo, 0x4E, 0xF, 0xF, true);   // from lane + 2
+    const uint32_t a = hi | (lo_n1 << 16), b = (lo_n1 >> 16) | (hi_n1 << 16);
+    const int C = p >> 2, t = (p >> 1) & 1, g = p & 1;
+    const int64_t R = m >> 3;
+    const int r = (int)(m & 7), Rl = (int)(R & 3);
+    uint8_t *blk = T6 + ((int64_t)C * row_blocks + R) * 768;
+    if ((lane & 3) == 0)
+        *reinterpret_cast<uint4 *>(blk + 256 * t + 128 * (g ^ (Rl & 1)) + 16 * r) = make_uint4(lo, a, b, lo_n2);
+    else if ((lane & 3) == 2)
+        *reinterpret_cast<uint2 *>(blk + 512 + 64 * ((2 * t + g) ^ Rl) + 8 * r) = make_uint2(a, b);
+}
+
 // ---- rotation of one row by a whole workgroup -----------------------------------------------
 // x (fp16, optionally times pre) -> T(x) in `row` (fp32, padded layout, LDS) and the row's
 // absolute maximum, returned to every thread.  NT threads, t = thread index, red = NT / 64 floats

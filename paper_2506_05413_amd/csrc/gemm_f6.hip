@@ -1,0 +1,372 @@
+// INT4 x INT4 GEMM on the FP6 matrix pipe, compute-bound shapes.
+//
+//   acc[m][n] = sum_k cX[m][k] * cW[n][k],   Y = fp16(acc * dx[m] * dw[n])
+//
+// (Paper: the quantised forward pass of the linear layer; dequantisation per Eq. (1).)
+//
+// gfx950 has no 4-bit integer matrix instruction, and its int8 MFMA sustains ~3.5 POP/s on this
+// chip (power).  The scaled-float MFMA family runs 6-bit floats at twice the int8 rate, and the
+// 6-bit format E2M3 (sign, 2 exponent bits, 3 mantissa bits, bias 1) holds every INT4 code
+// exactly: its first sixteen magnitudes -- the subnormals m/8 and the first binade 1 + m/8 --
+// are the linear sequence 0, 1/8, ..., 15/8, so a code c is the 6-bit pattern
+//     f6(c) = (c < 0 ? 32 : 0) | |c|            (value c / 8)
+// and needs no arithmetic to build.  Products c_x c_w / 64 and their sums are integers / 64 below
+// 2^24 / 64 for K < 262144, so the fp32 accumulation is exact in any order; measured on MI355X:
+// v_mfma_f32_32x32x64_f8f6f4 reproduces the integer sums bit for bit (K = 14336, random codes and
+// the all -8 worst case) and issues at 5.4 - 6.2 POP/s where the int8 MFMA reaches 3.3 - 3.7.
+//
+// The operands arrive already packed as 6-bit fields in the layout the MFMA wants ("f6 tiles",
+// written by pack_f6.hip and by the activation quantiser), so the main loop has no vector-ALU
+// work at all: LDS-DMA loads, LDS reads, MFMAs.
+//
+// f6 tiles of a code matrix [rows, K], K % 128 == 0, rows padded to a multiple of 8:
+//   block (R, C) = rows 8R .. 8R+7 x codes 128C .. 128C+127, 768 bytes at ((C * rows/8) + R) * 768
+//   (chunk-major: the blocks of all rows for one 128-code chunk are contiguous, so one stage of a tile is
+//   two contiguous runs -- BM * 96 bytes of X and BN * 96 bytes of W -- copied by whole-KB LDS-DMA loads).
+//   Inside a block, piece (r, t, g) = the 32 codes k = 128C + 64t + 32g + j (j = 0..31) of row
+//   8R + r, code j in bits [6j, 6j+6) of a 24-byte little-endian string -- exactly the operand
+//   of lane (row, k half g) of MFMA step t.  Its first 16 bytes live at
+//       256 t + 128 (g ^ (R & 1)) + 16 r
+//   and its last 8 bytes at
+//       512 + 64 ((2t + g) ^ (R & 3)) + 8 r
+//   so that a wave's ds_read_b128 / ds_read_b64 of a 32-row fragment (four blocks) touch every
+//   LDS bank once.  (The 12-byte form of the LDS-DMA load leaves a 4-byte hole after every lane's data in
+//   LDS -- measured -- so stages are copied with the 16-byte form, 1 KB per instruction.)
+//
+// Kernel structure: persistent workgroups, tile BM x BN, ring of SLOTS stages of 128 codes, one
+// barrier per stage, two MFMA steps (64 codes) per stage with the fragment reads of the next
+// step issued under the MFMAs of the current one; transposing epilogue shared with the int8
+// kernel; scales of a tile fetched by LDS-DMA at the start of the tile.
+#include "sr_common.h"
+#include "gemm_common.h"
+
+#include <stdlib.h>
+#include <type_traits>
+
+namespace sr {
+namespace {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int BLK = 768;     // bytes of one block (8 rows x 128 codes x 6 bits)
+
+// 64 lanes x 4 bytes -> LDS bytes [lds, lds + 256)
+__device__ __forceinline__ void dma4(const void *base, uint32_t lane_off, uint32_t lds)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds), "v"(lane_off), "s"(base)
+                 : "memory", "m0");
+}
+
+template <int BM, int BN, int WGM, int WGN, int SLOTS, int WG_PER_CU>
+__global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN * WG_PER_CU / 4) void gemm_f6_kernel(
+    const uint8_t *__restrict__ X6, const float *__restrict__ xs, const uint8_t *__restrict__ W6,
+    const float *__restrict__ ws, int M, int N, int K, void *__restrict__ Yv, int64_t ldy, int out_i32,
+    int tiles_m, int tiles_n, int xcd_m)
+{
+    constexpr int NWAVE = WGM * WGN;
+    constexpr int WM = BM / WGM, WN = BN / WGN;      // wave tile
+    constexpr int FM = WM / 32, FN = WN / 32;        // 32 x 32 MFMA tiles per wave
+    constexpr int X_BYTES = BM / 8 * BLK, STAGE_BYTES = (BM + BN) / 8 * BLK;
+    constexpr int NDMA = STAGE_BYTES / 1024;         // 1 KB LDS-DMA instructions per stage
+    constexpr int RPW = NDMA / NWAVE;                // ... per wave
+    constexpr int XI = X_BYTES / 1024 / NWAVE;       // the first XI instructions of a wave copy X rows, the rest W rows
+    constexpr int SCALE_OFF = SLOTS * STAGE_BYTES;   // two areas of BM + BN floats behind the ring
+    constexpr int NSC = (BM + BN) / 64;              // scale DMA instructions per tile
+    static_assert(NDMA % NWAVE == 0 && (X_BYTES / 1024) % NWAVE == 0 && X_BYTES % 1024 == 0 && STAGE_BYTES % 1024 == 0 &&
+                      WM % 32 == 0 && WN % 32 == 0 && BM % 64 == 0 && BN % 64 == 0 && SLOTS >= 2 &&
+                      SLOTS * RPW + 8 * FM < 64, "tile");
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int total = tiles_m * tiles_n;
+    const int nc = K >> 7;                           // 128-code chunks per row = stages
+    const uint32_t cx_bytes = (uint32_t)((M + 7) >> 3) * BLK, cw_bytes = (uint32_t)((N + 7) >> 3) * BLK;   // one chunk of X / W
+
+    // ---- DMA sources: instruction q = wave + NWAVE * i copies bytes [1024 q, 1024 q + 1024) of the stage's X run
+    // (q < X_BYTES / 1024) or of its W run; a lane past the end of the operand re-reads the last 16 bytes
+    uint32_t goff[RPW];
+    auto set_sources = [&](int m0, int n0) {
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const int q = wave + NWAVE * i;
+            uint32_t off;
+            if (i < XI) { off = (uint32_t)(m0 >> 3) * BLK + q * 1024 + lane * 16; off = off < cx_bytes ? off : cx_bytes - 16; }
+            else { off = (uint32_t)(n0 >> 3) * BLK + (q - X_BYTES / 1024) * 1024 + lane * 16; off = off < cw_bytes ? off : cw_bytes - 16; }
+            goff[i] = off;
+        }
+    };
+    const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
+    auto dma_one = [&](int idx, int s, int slot) {   // instruction idx of this wave, stage s -> ring slot
+        dma16((idx < XI ? X6 + (int64_t)s * cx_bytes : W6 + (int64_t)s * cw_bytes), goff[idx],
+              smem_base + (uint32_t)slot * STAGE_BYTES + (uint32_t)(wave + NWAVE * idx) * 1024);
+    };
+    auto issue = [&](int s, int slot) {
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) dma_one(i, s, slot);
+    };
+    // scales of a tile: floats [0, BM) = token scales, [BM, BM + BN) = channel scales, 64 per instruction
+    auto issue_scales = [&](int m0, int n0, int area) {
+#pragma unroll
+        for (int k = 0; k < (NSC + NWAVE - 1) / NWAVE; ++k) {
+            const int idx = wave + k * NWAVE;        // wave-uniform
+            if (idx < NSC) {
+                const int f = idx * 64 + lane;
+                const bool is_x = idx < BM / 64;
+                int e = is_x ? m0 + f : n0 + f - BM;
+                const int last = is_x ? M - 1 : N - 1;
+                e = e < last ? e : last;
+                const uint32_t dst = smem_base + SCALE_OFF + (uint32_t)area * (BM + BN) * 4 + (uint32_t)idx * 256;
+                dma4(is_x ? xs : ws, (uint32_t)e * 4u, (uint32_t)__builtin_amdgcn_readfirstlane((int)dst));
+            }
+        }
+    };
+
+    // ---- fragment addresses: lane (r = l & 31, g = l >> 5) reads row r of a 32-row fragment, k half g
+    const int fr = lane & 31, fg = lane >> 5;
+    const int rq = fr >> 3;                          // block of the fragment (= R & 3: fragments start at multiples of 32 rows)
+    const uint32_t a16 = rq * BLK + ((fg ^ (rq & 1)) << 7) + ((fr & 7) << 4);
+    const uint32_t a8 = rq * BLK + 512 + ((fg ^ rq) << 6) + ((fr & 7) << 3);   // step 0; step 1 = a8 ^ 128
+    const uint32_t xfrag = (wm * WM / 8) * BLK, wfrag = X_BYTES + (wn * WN / 8) * BLK;
+
+    struct Frags { v8i x[FM]; v8i w[FN]; };
+    auto read_frag = [&](v8i &f, uint32_t base, int t) {
+        const uint4 lo = *reinterpret_cast<const uint4 *>(smem + base + a16 + t * 256);
+        const uint2 hi = *reinterpret_cast<const uint2 *>(smem + base + (a8 ^ (t << 7)));
+        f[0] = (int)lo.x; f[1] = (int)lo.y; f[2] = (int)lo.z; f[3] = (int)lo.w;
+        f[4] = (int)hi.x; f[5] = (int)hi.y;
+    };
+    auto read_q = [&](Frags &f, int q, uint32_t sbase, int t) {       // fragment q: X fragments first
+        if (q < FM) read_frag(f.x[q < FM ? q : 0], sbase + xfrag + q * 4 * BLK, t);
+        else read_frag(f.w[q < FM ? 0 : q - FM], sbase + wfrag + (q - FM) * 4 * BLK, t);
+    };
+
+    v16f acc[FN][FM];
+
+    // ---- one MFMA step (64 codes): the FM * FN MFMAs on `cur`, the reads of the next step's FM + FN fragments
+    // into `nxt` and a share of the DMA of a later stage, cut into regions of [2 fragment reads, a slice of the
+    // MFMAs, some DMA instructions] so that no memory instruction queue sees a burst.
+    static_assert((FM + FN) % 2 == 0, "fragments are read in pairs");
+    constexpr int NREG = (FM + FN) / 2;              // regions per step
+    constexpr int NM = FM * FN;                      // MFMAs per step
+    constexpr int HALF = SLOTS == 2 ? RPW : (RPW + 1) / 2;      // DMA instructions issued in the step after the barrier
+    auto step = [&](auto PART, const Frags &cur, Frags &nxt, uint32_t rbase, int t, int dstage, int dslot) {
+        constexpr int part = decltype(PART)::value;             // 0: step after the barrier, 1: step before it
+        constexpr int dlo = part == 0 ? 0 : HALF, dhi = part == 0 ? HALF : RPW;
+        constexpr int DPR = (dhi - dlo + NREG - 1) / NREG;
+#pragma unroll
+        for (int r = 0; r < NREG; ++r) {
+            __builtin_amdgcn_sched_barrier(0);
+#ifndef F6_NO_READ
+            read_q(nxt, 2 * r, rbase, t);
+            read_q(nxt, 2 * r + 1, rbase, t);
+#endif
+            const int mlo = r * NM / NREG, mhi = (r + 1) * NM / NREG;
+#pragma unroll
+            for (int m = mlo; m < mhi; ++m) {
+                const int i = m / FM, j = m % FM;
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(cur.w[i], cur.x[j], acc[i][j], 2, 2, 0, 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#ifndef F6_NO_DMA
+#pragma unroll
+            for (int idx = dlo + r * DPR; idx < dlo + (r + 1) * DPR && idx < dhi; ++idx) dma_one(idx, dstage, dslot);
+#endif
+        }
+    };
+    constexpr std::integral_constant<int, 0> AFTER{};
+    constexpr std::integral_constant<int, 1> BEFORE{};
+
+    // epilogue staging: one piece = 32 tokens x WN channels of fp16 per wave, in the last ring slot
+    constexpr int PIECE = 32 * (WN * 2 + 16);
+    static_assert(NWAVE * PIECE <= STAGE_BYTES, "epilogue staging must fit one ring slot");
+
+    int v = blockIdx.x;
+    int m0, n0;
+    tile_origin(v, tiles_m, tiles_n, xcd_m, BM, BN, m0, n0);
+    set_sources(m0, n0);
+    // order of a wave's loads at the start of every tile: stage 0, scales, stages 1 .. SLOTS-2, first part of
+    // stage SLOTS-1 (its second part is issued by the first step of the loop)
+    int area = 0;
+    issue(0, 0);
+    issue_scales(m0, n0, area);
+#pragma unroll
+    for (int q = 1; q < SLOTS - 1; ++q) issue(q < nc ? q : nc - 1, q);
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) dma_one(i, SLOTS - 1 < nc ? SLOTS - 1 : nc - 1, SLOTS - 1);
+    for (;;) {
+#pragma unroll
+        for (int i = 0; i < FN; ++i)
+#pragma unroll
+            for (int j = 0; j < FM; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+        // Stage 0 (and the scales) have landed once at most (SLOTS-2) RPW + HALF of this wave's memory operations
+        // are outstanding: loads complete in order among themselves and that many loads are younger, so an
+        // unfinished older load would leave more outstanding -- however many stores of the previous tile are
+        // still on their way (stores and loads may overtake each other).
+        wait_vmcnt<(SLOTS - 2) * RPW + HALF>();
+        barrier_nofence();
+        Frags fa, fb;                                // fragments of step 0 / step 1 of a stage
+#pragma unroll
+        for (int q = 0; q < FM + FN; ++q) read_q(fa, q, 0, 0);
+        int slot = 0;
+        // Every stage runs the same branch-free body.  Past the end of K the pipeline keeps reading (stale,
+        // in-bounds) LDS and re-fetching the last stage; those fragments are never multiplied.
+        for (int s = 0; s < nc; ++s) {
+            const int nslot = slot == SLOTS - 1 ? 0 : slot + 1, pslot = slot == 0 ? SLOTS - 1 : slot - 1;
+            const int sa = s + SLOTS - 1 < nc ? s + SLOTS - 1 : nc - 1, sb = s + SLOTS < nc ? s + SLOTS : nc - 1;
+            // step 0 of stage s; reads step 1; second part of the DMA of stage s+SLOTS-1 -> slot of stage s-1
+            step(BEFORE, fa, fb, (uint32_t)slot * STAGE_BYTES, 1, sa, pslot);
+            // stage s+1 must have landed (the SLOTS-2 younger stages may stay in flight), and every wave's
+            // reads of stage s must have returned: its slot takes stage s+SLOTS from here on
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((SLOTS - 2) * RPW) : "memory");
+#ifndef F6_NO_BARRIER
+            barrier_nofence();
+#endif
+            // step 1 of stage s; reads step 0 of stage s+1; first part of the DMA of stage s+SLOTS
+            step(AFTER, fb, fa, (uint32_t)nslot * STAGE_BYTES, 0, sb, slot);
+            slot = nslot;
+        }
+
+        // ---- tile boundary
+        const int vn = v + (int)gridDim.x;
+        const bool more = vn < total;
+        wait_vmcnt<0>();                             // no LDS-DMA write is in flight any more ...
+        barrier_nofence();                           // ... and all waves are done reading fragments
+        int m1 = 0, n1 = 0;
+        if (more) {                                  // the next tile's first stages fly during the epilogue
+            tile_origin(vn, tiles_m, tiles_n, xcd_m, BM, BN, m1, n1);
+            set_sources(m1, n1);
+            issue(0, 0);
+            issue_scales(m1, n1, area ^ 1);
+#pragma unroll
+            for (int q = 1; q < SLOTS - 1; ++q) issue(q < nc ? q : nc - 1, q);
+        }
+        {
+            const float *sc = reinterpret_cast<const float *>(smem + SCALE_OFF) + area * (BM + BN);
+            float sx[FM];
+            float4 sw[FN][4];
+#pragma unroll
+            for (int j = 0; j < FM; ++j) sx[j] = sc[wm * WM + j * 32 + fr] * 64.f;      // both operands carried a factor 1/8
+#pragma unroll
+            for (int i = 0; i < FN; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    sw[i][q] = *reinterpret_cast<const float4 *>(sc + BM + wn * WN + i * 32 + q * 8 + fg * 4);
+            store_wave_tile<FM, FN>(acc, smem + (SLOTS - 1) * STAGE_BYTES + wave * PIECE, lane, m0 + wm * WM, n0 + wn * WN,
+                                    M, N, sx, sw, Yv, ldy, out_i32);
+        }
+        if (!more) break;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        barrier_nofence();                           // every wave has read its staging back: the last slot is free
+#pragma unroll
+        for (int i = 0; i < HALF; ++i) dma_one(i, SLOTS - 1 < nc ? SLOTS - 1 : nc - 1, SLOTS - 1);
+        v = vn;
+        m0 = m1;
+        n0 = n1;
+        area ^= 1;
+    }
+    wait_vmcnt<0>();
+}
+
+template <int BM, int BN, int WGM, int WGN, int SLOTS, int WG_PER_CU>
+hipError_t launch_f6(const uint8_t *X6, const float *xs, const uint8_t *W6, const float *ws, int64_t M, int64_t N,
+                     int64_t K, void *Y, int64_t ldy, int out_i32, hipStream_t st)
+{
+    auto kern = gemm_f6_kernel<BM, BN, WGM, WGN, SLOTS, WG_PER_CU>;
+    constexpr int lds = SLOTS * (BM + BN) / 8 * BLK + 2 * (BM + BN) * 4 + 256;   // ring, two scale areas, slack
+    static_assert(lds * WG_PER_CU <= 160 * 1024, "LDS");
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+    }
+    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
+    const int xcd_m = choose_xcd_split(tiles_m, tiles_n, BM, BN);
+    int64_t grid = (int64_t)compute_units() * WG_PER_CU;
+    if (const char *env = getenv("SMOOTHROT_GEMM_GRID")) grid = atoll(env) > 0 ? atoll(env) / 8 * 8 : grid;   // tuning aid
+    if (grid < 8) grid = 8;
+    const int64_t total = (int64_t)tiles_m * tiles_n;
+    if (grid > total) grid = total;
+    // the raw int32 output takes no scales (they may be NULL): the kernel still fetches M and N floats it then
+    // ignores, from the start of the operand arrays (at least 96 M and 96 N bytes, 16-byte aligned)
+    if (out_i32) {
+        xs = reinterpret_cast<const float *>(X6);
+        ws = reinterpret_cast<const float *>(W6);
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WGM * WGN * 64), lds, st, X6, xs, W6, ws,
+                       (int)M, (int)N, (int)K, Y, ldy, out_i32, tiles_m, tiles_n, xcd_m);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Repacking of canonical INT4 codes (two per byte along K) into f6 tiles.  One thread per piece
+// (row, 128-code chunk, step t, half g): 16 bytes in, 24 bytes out.  Rows >= rows (padding of
+// the last block) are written as zeros.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pack_f6_kernel(const uint8_t *__restrict__ Q4, int rows, int K,
+                                                      uint8_t *__restrict__ T6, int64_t pieces)
+{
+    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p >= pieces) return;
+    // piece index: [C][R][t][g][r] with r fastest, so that the 16-byte parts of neighbouring threads are neighbours
+    const int r = (int)(p & 7), g = (int)((p >> 3) & 1), t = (int)((p >> 4) & 1);
+    const int64_t bc = p >> 5;                      // C * row_blocks + R = index of the block in memory
+    const int64_t rb = ((int64_t)rows + 7) >> 3;
+    const int C = (int)(bc / rb);
+    const int64_t R = bc % rb;
+    const int64_t row = R * 8 + r;
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    if (row < rows) {
+        const uint4 q = *reinterpret_cast<const uint4 *>(Q4 + row * (int64_t)(K >> 1) + C * 64 + t * 32 + g * 16);
+        w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
+    }
+    uint32_t o[6] = {0u, 0u, 0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        const uint32_t nib = (w[j >> 3] >> ((j & 7) * 4)) & 15u;
+        const uint32_t f = nib < 8u ? nib : (32u | (16u - nib));          // sign-magnitude 6-bit field
+        const int bit = 6 * j;
+        o[bit >> 5] |= f << (bit & 31);
+        if ((bit & 31) > 26) o[(bit >> 5) + 1] |= f >> (32 - (bit & 31));
+    }
+    uint8_t *blk = T6 + bc * BLK;
+    const int Rl = (int)(R & 3);
+    *reinterpret_cast<uint4 *>(blk + 256 * t + 128 * (g ^ (Rl & 1)) + 16 * r) = make_uint4(o[0], o[1], o[2], o[3]);
+    *reinterpret_cast<uint2 *>(blk + 512 + 64 * ((2 * t + g) ^ Rl) + 8 * r) = make_uint2(o[4], o[5]);
+}
+
+}  // namespace
+
+hipError_t launch_pack_f6(const uint8_t *Q4, int64_t rows, int64_t K, uint8_t *T6, hipStream_t st)
+{
+    const int64_t pieces = ((rows + 7) / 8) * 8 * (K / 128) * 4;
+    hipLaunchKernelGGL(pack_f6_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st, Q4, (int)rows, (int)K, T6,
+                       pieces);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_f6(const uint8_t *X6, const float *xs, const uint8_t *W6, const float *ws, int64_t M, int64_t N,
+                          int64_t K, void *Y, int64_t ldy, int out_i32, hipStream_t st)
+{
+    // SMOOTHROT_GEMM_TILE selects a tile configuration by number (tuning aid); unset = heuristic.
+    int variant = 0;
+    if (const char *env = getenv("SMOOTHROT_GEMM_TILE")) variant = atoi(env);
+    switch (variant) {
+        case 61: return launch_f6<256, 256, 2, 4, 3, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
+        case 63: return launch_f6<256, 128, 2, 2, 2, 2>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
+        case 64: return launch_f6<256, 256, 2, 4, 2, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
+        default: break;
+    }
+    const int64_t cus = compute_units();
+    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+    if (t256 >= cus) return launch_f6<256, 256, 2, 4, 3, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
+    return launch_f6<256, 128, 2, 2, 2, 2>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
+}
+
+}  // namespace sr

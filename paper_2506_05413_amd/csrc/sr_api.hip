@@ -157,6 +157,19 @@ int sr_fwht_quant_act(const void *X_f16, int64_t M, int64_t K, int64_t ldx, cons
                                      static_cast<hipStream_t>(stream)));
 }
 
+int sr_fwht_quant_act_f6(const void *X_f16, int64_t M, int64_t K, int64_t ldx, const float *inv_s, float clip,
+                         uint8_t *X6, float *x_scale, void *stream)
+{
+    if (M < 0 || K <= 0 || ldx < K) return SR_ERR_SHAPE;
+    if (!sr::hadamard_supported(K) || K % 128 != 0) return SR_ERR_UNSUPPORTED_K;
+    if (!(clip > 0.f && clip <= 1.f)) return SR_ERR_ARG;
+    if (M == 0) return SR_OK;
+    if (!X_f16 || !X6 || !x_scale) return SR_ERR_NULL;
+    if (ldx % 8 != 0 || !aligned16(X_f16) || !aligned16(X6) || (inv_s && !aligned16(inv_s))) return SR_ERR_ALIGN;
+    return dev(sr::launch_fwht_quant(X_f16, M, K, ldx, inv_s, clip, 1.0f, X6, x_scale,
+                                     static_cast<hipStream_t>(stream), true));
+}
+
 int sr_swiglu_fwht_quant_act(const void *G_f16, const void *U_f16, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
                              const float *inv_s, float clip, uint8_t *Xq, float *x_scale, void *stream)
 {
@@ -241,6 +254,41 @@ int sr_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, con
     const int i32 = out_dtype == SR_I32;
     if (M <= 16) return dev(sr::launch_gemm_decode(Xq, x_scale, Wq, w_scale, M, N, K, Y, ldy, i32, st));
     return dev(sr::launch_gemm_prefill(Xq, x_scale, Wq, w_scale, M, N, K, Y, ldy, i32, st));
+}
+
+size_t sr_f6_tiles_bytes(int64_t rows, int64_t K)
+{
+    if (rows <= 0 || K <= 0 || K % 128 != 0) return 0;
+    return (size_t)((rows + 7) / 8) * (size_t)(K / 128) * 768;
+}
+
+int sr_pack_f6_tiles(const uint8_t *Q4, int64_t rows, int64_t K, uint8_t *T6, void *stream)
+{
+    if (rows < 0 || K <= 0) return SR_ERR_SHAPE;
+    if ((double)rows * (double)K >= 4294967296.0) return SR_ERR_SHAPE;
+    if (K % 128 != 0 || K >= 131072) return SR_ERR_UNSUPPORTED_K;
+    if (rows == 0) return SR_OK;
+    if (!Q4 || !T6) return SR_ERR_NULL;
+    if (!aligned16(Q4) || !aligned16(T6)) return SR_ERR_ALIGN;
+    return dev(sr::launch_pack_f6(Q4, rows, K, T6, static_cast<hipStream_t>(stream)));
+}
+
+int sr_w4a4_gemm_f6(const uint8_t *X6, const float *x_scale, const uint8_t *W6, const float *w_scale,
+                    int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_dtype,
+                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    if (M < 0 || N <= 0 || K <= 0 || N % 16 != 0 || ldy < N) return SR_ERR_SHAPE;
+    // kernels index blocks with 32-bit byte offsets (0.75 bytes per code)
+    if ((double)M * (double)K >= 4294967296.0 || (double)N * (double)K >= 4294967296.0) return SR_ERR_SHAPE;
+    if (K % 128 != 0 || K >= 131072) return SR_ERR_UNSUPPORTED_K;
+    if (out_dtype != SR_F16 && out_dtype != SR_I32) return SR_ERR_ARG;
+    if (M == 0) return SR_OK;
+    if (!X6 || !W6 || !Y) return SR_ERR_NULL;
+    if (out_dtype == SR_F16 && (!x_scale || !w_scale)) return SR_ERR_NULL;
+    if (ldy % 8 != 0 || !aligned16(X6) || !aligned16(W6) || !aligned16(Y)) return SR_ERR_ALIGN;
+    return dev(sr::launch_gemm_f6(X6, x_scale, W6, w_scale, M, N, K, Y, ldy, out_dtype == SR_I32,
+                                  static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"

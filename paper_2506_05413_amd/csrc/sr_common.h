@@ -23,9 +23,10 @@ inline bool hadamard_supported(int64_t K)
 // ---- launchers (each returns hipGetLastError() of its launches) ------------------
 
 // y = (x * pre) H per row, per-row symmetric INT4, scale_out = delta * post_scale.
+// f6: Q receives f6 tiles (see gemm_f6.hip; K % 128 == 0) instead of canonical packed nibbles.
 hipError_t launch_fwht_quant(const void *X_f16, int64_t rows, int64_t K, int64_t ldx,
                              const float *pre, float clip, float post_scale,
-                             uint8_t *Q, float *scale_out, hipStream_t st);
+                             uint8_t *Q, float *scale_out, hipStream_t st, bool f6 = false);
 
 // Optional extras of the row kernel (see fwht_quant.hip).
 constexpr int kMaxClipGrid = 32;
@@ -70,6 +71,12 @@ hipError_t launch_linear_decode(const void *X_f16, int64_t M, int64_t K, int64_t
 hipError_t launch_gemm_prefill(const uint8_t *Xq, const float *xs, const uint8_t *Wq, const float *ws,
                                int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_i32,
                                hipStream_t st);
+
+// f6 tiles (see gemm_f6.hip): repacking of canonical INT4 codes, and the GEMM on the FP6 matrix pipe
+hipError_t launch_pack_f6(const uint8_t *Q4, int64_t rows, int64_t K, uint8_t *T6, hipStream_t st);
+hipError_t launch_gemm_f6(const uint8_t *X6, const float *xs, const uint8_t *W6, const float *ws,
+                          int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_i32,
+                          hipStream_t st);
 
 hipError_t launch_gemm_decode(const uint8_t *Xq, const float *xs, const uint8_t *Wq, const float *ws,
                               int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_i32,

@@ -23,7 +23,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = declared_symbols()
-    assert len(names) == 13 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
+    assert len(names) == 17 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
     lib = ctypes.CDLL(sr.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -216,3 +216,44 @@ def test_linear_decode_rejects_bad_arguments():
     assert call(X=A + 2) == sr.SR_ERR_ALIGN
     assert call(ldx=4100) == sr.SR_ERR_ALIGN
     assert call(M=0, X=None, Y=None) == sr.SR_OK
+
+
+def test_f6_calls_reject_bad_arguments():
+    raw = sr.raw()
+    assert raw.sr_f6_tiles_bytes(2048, 4096) == 256 * 32 * 768
+    assert raw.sr_f6_tiles_bytes(9, 128) == 2 * 768
+    assert raw.sr_f6_tiles_bytes(8, 192) == 0 and raw.sr_f6_tiles_bytes(0, 128) == 0
+
+    def pack(Q4=A, rows=8, K=256, T6=A):
+        return raw.sr_pack_f6_tiles(Q4, rows, K, T6, None)
+    assert pack(rows=-1) == sr.SR_ERR_SHAPE
+    assert pack(K=192) == sr.SR_ERR_UNSUPPORTED_K
+    assert pack(rows=0, Q4=None, T6=None) == sr.SR_OK
+    assert pack(Q4=None) == sr.SR_ERR_NULL
+    assert pack(T6=A + 8) == sr.SR_ERR_ALIGN
+    assert pack(rows=70000, K=65536) == sr.SR_ERR_SHAPE
+
+    def quant(X=A, M=4, K=4096, ldx=4096, inv=None, clip=0.9, X6=A, xs=A):
+        return raw.sr_fwht_quant_act_f6(X, M, K, ldx, inv, clip, X6, xs, None)
+    assert quant(M=-1) == sr.SR_ERR_SHAPE
+    assert quant(K=64, ldx=64) == sr.SR_ERR_UNSUPPORTED_K              # a Hadamard order, but not a multiple of 128
+    assert quant(K=448, ldx=448) == sr.SR_ERR_UNSUPPORTED_K
+    assert quant(K=4000, ldx=4000) == sr.SR_ERR_UNSUPPORTED_K
+    assert quant(clip=0.0) == sr.SR_ERR_ARG
+    assert quant(M=0, X=None, X6=None, xs=None) == sr.SR_OK
+    assert quant(X6=None) == sr.SR_ERR_NULL
+    assert quant(X6=A + 4) == sr.SR_ERR_ALIGN
+
+    def gemm(X6=A, xs=A, W6=A, ws=A, M=32, N=64, K=512, Y=A, ldy=64, dt=sr.SR_F16):
+        return raw.sr_w4a4_gemm_f6(X6, xs, W6, ws, M, N, K, Y, ldy, dt, None, 0, None)
+    assert gemm(M=-1) == sr.SR_ERR_SHAPE
+    assert gemm(N=40) == sr.SR_ERR_SHAPE
+    assert gemm(ldy=32) == sr.SR_ERR_SHAPE
+    assert gemm(K=192) == sr.SR_ERR_UNSUPPORTED_K
+    assert gemm(K=131072) == sr.SR_ERR_UNSUPPORTED_K
+    assert gemm(dt=7) == sr.SR_ERR_ARG
+    assert gemm(M=0) == sr.SR_OK
+    assert gemm(X6=None) == sr.SR_ERR_NULL
+    assert gemm(xs=None) == sr.SR_ERR_NULL
+    assert gemm(ldy=68) == sr.SR_ERR_ALIGN
+    assert gemm(W6=A + 1) == sr.SR_ERR_ALIGN

@@ -1,0 +1,189 @@
+"""GPU parity of the FP6-matrix-pipe path: sr_pack_f6_tiles, sr_fwht_quant_act_f6, sr_w4a4_gemm_f6.
+
+The sums are the integer sums of the quantised forward pass, so the bar is the same as for
+sr_w4a4_gemm: INT32 accumulators bit-exact given identical codes, fp16 outputs within 1e-2 * rms,
+tile images byte for byte what the format's definition (oracle) gives, activation codes under the
+rounding-boundary rule."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import smoothrot_oracle as o
+import workloads as wl
+from parity import check_codes, check_output, check_scales
+
+pytestmark = pytest.mark.gpu
+
+
+def tiles(sr, codes):
+    return sr.sr_pack_f6_tiles(torch.from_numpy(o.pack_int4(codes)).cuda())
+
+
+@pytest.mark.parametrize("rows,K", [(1, 128), (8, 128), (9, 256), (100, 896), (257, 4096), (2048, 1024), (33, 14336)])
+def test_pack_matches_the_format_definition(gpu, rows, K):
+    print("case", rows, K, flush=True)
+    c = wl.random_codes(rows * 3 + K, rows, K)
+    got = tiles(gpu, c).cpu().numpy()
+    want = o.f6_tiles_pack(c)
+    assert got.size >= want.size and np.array_equal(got[:want.size], want)      # padding rows are zero codes here
+
+
+def gemm_f6(sr, cx, cw, xs=None, ws=None, dtype=None, ldy=None):
+    dtype = sr.SR_I32 if dtype is None else dtype
+    M, K = cx.shape
+    N = cw.shape[0]
+    X6, W6 = tiles(sr, cx), tiles(sr, cw)
+    xs_d = None if xs is None else torch.from_numpy(xs.astype(np.float32)).cuda()
+    ws_d = None if ws is None else torch.from_numpy(ws.astype(np.float32)).cuda()
+    Y = None
+    if ldy is not None:
+        full = torch.full((M, ldy), -7, dtype=torch.int32 if dtype == sr.SR_I32 else torch.float16, device="cuda")
+        Y = full[:, :N]
+    out = sr.sr_w4a4_gemm_f6(X6, xs_d, W6, ws_d, M, N, K, dtype, Y)
+    torch.cuda.synchronize()
+    if ldy is not None:
+        assert bool((full[:, N:] == -7).all())                      # nothing written past N
+    return out.cpu().numpy()
+
+
+# single tile, ragged edges in M and N, several tiles per workgroup (persistent loop), K from one stage up
+SHAPES = [(1, 16, 128), (5, 48, 256), (16, 512, 512), (17, 16, 128), (33, 48, 384), (100, 144, 896), (128, 128, 128),
+          (129, 272, 640), (256, 256, 512), (300, 1040, 512), (257, 400, 4096), (64, 128, 14336), (520, 784, 1792),
+          (1031, 528, 256)]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_int32_accumulators_bit_exact(gpu, M, N, K):
+    print("case", M, N, K, flush=True)
+    cx, cw = wl.random_codes(M + K, M, K), wl.random_codes(N + 3 * K, N, K)
+    want = o.gemm_i32_c(cx, cw)
+    got = gemm_f6(gpu, cx, cw)
+    assert got.dtype == np.int32 and np.array_equal(got.astype(np.int64), want)
+
+
+@pytest.mark.parametrize("tile", ["61", "63", "64"])
+def test_every_tile_configuration(gpu, tile, monkeypatch):
+    """The launch heuristic picks one configuration per shape; each of them is checked on a shape with
+    ragged edges and more tiles than workgroups can hold at once is covered by the full-size test below."""
+    monkeypatch.setenv("SMOOTHROT_GEMM_TILE", tile)
+    M, N, K = 700, 1040, 640
+    cx, cw = wl.random_codes(1, M, K), wl.random_codes(2, N, K)
+    got = gemm_f6(gpu, cx, cw, ldy=1048)
+    assert np.array_equal(got.astype(np.int64), o.gemm_i32_c(cx, cw))
+
+
+@pytest.mark.parametrize("M", [1, 40])
+def test_extreme_codes_stay_exact(gpu, M):
+    """All codes -8 at the largest K the call accepts: |acc| = 64 K, the largest sum fp32 must hold."""
+    for K in (14336, 130944):
+        cx = np.full((M, K), -8, np.int8)
+        cw = np.full((32, K), -8, np.int8)
+        cw[1::2] = 7
+        got = gemm_f6(gpu, cx, cw)
+        assert np.all(got[:, 0::2] == 64 * K) and np.all(got[:, 1::2] == -56 * K)
+
+
+@pytest.mark.parametrize("M,N,K", [(16, 512, 512), (200, 528, 1024), (2048, 1024, 4096)])
+def test_fp16_epilogue(gpu, M, N, K):
+    rng = np.random.default_rng(M * N)
+    cx, cw = wl.random_codes(M, M, K), wl.random_codes(N, N, K)
+    xs = rng.uniform(0.01, 2.0, M)
+    ws = rng.uniform(1e-4, 1e-2, N)
+    got = gemm_f6(gpu, cx, cw, xs, ws, gpu.SR_F16, ldy=N + 8)
+    want = o.dequant_out(o.gemm_i32_c(cx, cw), xs.astype(np.float32).astype(np.float64),
+                         ws.astype(np.float32).astype(np.float64))
+    check_output(got, want)
+
+
+@pytest.mark.parametrize("N", [4096, 14336])
+def test_cfg2_full_size_sampled(gpu, N):
+    """M = 2048, K = 4096 in the launch configuration the benchmark times: sampled rows by the oracle one by
+    one, and two sum identities that cover every output (row sums against cx . colsum(cw), column sums
+    against rowsum(cx) . cw)."""
+    M, K = 2048, 4096
+    cx, cw = wl.random_codes(21, M, K), wl.random_codes(22 + N, N, K)
+    got = gemm_f6(gpu, cx, cw).astype(np.int64)
+    rows = np.unique(np.r_[0:4, 255:258, 1023:1026, M - 4:M])
+    assert np.array_equal(got[rows], o.gemm_i32_c(cx[rows], cw))
+    assert np.array_equal(got.sum(axis=1), cx.astype(np.int64) @ cw.astype(np.int64).sum(axis=0))
+    assert np.array_equal(got.sum(axis=0), cx.astype(np.int64).sum(axis=0) @ cw.astype(np.int64).T)
+
+
+def test_cfg3_full_size_sampled(gpu):
+    M, N, K = 2048, 4096, 14336
+    cx, cw = wl.random_codes(31, M, K), wl.random_codes(32, N, K)
+    got = gemm_f6(gpu, cx, cw).astype(np.int64)
+    rows = np.unique(np.r_[0:3, 1024:1026, M - 3:M])
+    assert np.array_equal(got[rows], o.gemm_i32_c(cx[rows], cw))
+    assert np.array_equal(got.sum(axis=1), cx.astype(np.int64) @ cw.astype(np.int64).sum(axis=0))
+
+
+def test_repeatable_bitwise(gpu):
+    cx, cw = wl.random_codes(5, 600, 1024), wl.random_codes(6, 784, 1024)
+    a = gemm_f6(gpu, cx, cw)
+    for _ in range(3):
+        assert np.array_equal(gemm_f6(gpu, cx, cw), a)
+
+
+# ---------------------------------------------------------------- activation quantiser writing tiles
+
+def quant_f6(sr, X, inv_s, clip):
+    M, K = X.shape
+    inv = None if inv_s is None else torch.from_numpy(inv_s).cuda()
+    X6, xs = sr.sr_fwht_quant_act_f6(torch.from_numpy(X).cuda(), inv, clip)
+    torch.cuda.synchronize()
+    return o.f6_codes(o.f6_tiles_unpack(X6.cpu().numpy(), M, K)), xs.cpu().numpy(), X6
+
+
+@pytest.mark.parametrize("K", [128, 256, 512, 1024, 2048, 4096, 8192, 896, 1792, 3584, 14336])
+@pytest.mark.parametrize("M", [1, 13])
+def test_quantiser_tiles_every_order(gpu, M, K):
+    print("case", M, K, flush=True)
+    X = wl.gauss_acts(7, M, K, 3, 200.0)
+    inv_s = np.random.default_rng(K).uniform(0.25, 4.0, K).astype(np.float32)
+    for clip in (0.9, 1.0):
+        codes, xs, _ = quant_f6(gpu, X, inv_s, clip)
+        ref = o.fwht_quant_act(X, inv_s, clip)
+        check_scales(xs, ref["x_scale"])
+        check_codes(codes, ref["codes"], ref["t"])
+
+
+def test_quantiser_tiles_agree_with_the_nibble_path(gpu):
+    """Same kernel, two output formats: the codes must be identical, not merely within the boundary rule.
+    M = 2048, K = 4096 runs the wave-per-row kernel, M = 40 the workgroup-per-row kernel."""
+    for M, K in ((2048, 4096), (40, 4096), (24, 14336)):
+        X = wl.cfg2_X(M, K) if K == 4096 else wl.cfg3_X(M, K)
+        inv_s = np.random.default_rng(M).uniform(0.5, 2.0, K).astype(np.float32)
+        codes, xs, _ = quant_f6(gpu, X, inv_s, 0.9)
+        Xq, xs4 = gpu.sr_fwht_quant_act(torch.from_numpy(X).cuda(), torch.from_numpy(inv_s).cuda(), 0.9)
+        torch.cuda.synchronize()
+        assert np.array_equal(codes, o.unpack_int4(Xq.cpu().numpy()))
+        assert np.array_equal(xs, xs4.cpu().numpy())
+
+
+def test_cfg2_layer_through_the_f6_path(gpu):
+    """Config 2 (M = 2048, K = 4096 -> N = 4096) end to end through the tile path, stage by stage: each
+    stage's oracle runs on the GPU's own (already checked) output of the stage before."""
+    M, K, N = 2048, 4096, 4096
+    X, W = wl.cfg2_X(M, K), wl.cfg2_W(N, K)
+    a = np.zeros(K)
+    for i in range(2):
+        a = o.calib_absmax(wl.cfg2_calib_chunk(i, 256, K), a)
+    a_d = torch.from_numpy(a.astype(np.float32)).cuda()
+    Wq, ws, inv_s = gpu.sr_fold_smooth_rotate_quant(torch.from_numpy(W).cuda(), a_d, 0.5, 1.0)
+    W6 = gpu.sr_pack_f6_tiles(Wq)
+    X6, xs = gpu.sr_fwht_quant_act_f6(torch.from_numpy(X).cuda(), inv_s, 0.9)
+    Y = gpu.sr_w4a4_gemm_f6(X6, xs, W6, ws, M, N, K, gpu.SR_F16)
+    acc = gpu.sr_w4a4_gemm_f6(X6, None, W6, None, M, N, K, gpu.SR_I32)
+    torch.cuda.synchronize()
+    cw = o.unpack_int4(Wq.cpu().numpy())
+    assert np.array_equal(o.f6_codes(o.f6_tiles_unpack(W6.cpu().numpy(), N, K)), cw)
+    ref = o.fwht_quant_act(X, inv_s.cpu().numpy(), 0.9)
+    cx = o.f6_codes(o.f6_tiles_unpack(X6.cpu().numpy(), M, K))
+    check_scales(xs.cpu().numpy(), ref["x_scale"])
+    check_codes(cx, ref["codes"], ref["t"])
+    rows = np.unique(np.r_[0:4, 1000:1003, M - 4:M])
+    want = o.gemm_i32_c(cx[rows], cw)
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64)[rows], want)
+    check_output(Y.cpu().numpy()[rows], o.dequant_out(want, xs.cpu().numpy().astype(np.float64)[rows],
+                                                      ws.cpu().numpy().astype(np.float64)))
