@@ -5,8 +5,11 @@
 
 One "step" = the online hot path of the two prefill linears of the benchmark
 configuration (X fp16 [2048, 4096]; W [4096, 4096] and W [4096, 14336]):
-    sr_fwht_quant_act(X) -> sr_w4a4_gemm(N = 4096)
-    sr_fwht_quant_act(X) -> sr_w4a4_gemm(N = 14336)
+    sr_fwht_quant_act_f6(X) -> sr_w4a4_gemm_f6(N = 4096)
+    sr_fwht_quant_act_f6(X) -> sr_w4a4_gemm_f6(N = 14336)
+(rotation + per-token INT4 quantiser writing the codes as f6 tiles, then the INT4 x INT4 GEMM on the
+FP6 matrix pipe, which multiplies the codes exactly; weights are repacked to f6 tiles once, offline).
+The same GEMMs through the int8-MFMA kernel (sr_w4a4_gemm) are timed under "extra".
 Inputs are resident in HBM; the step rotates over several distinct input / weight
 sets so that no call finds its operands in the 256 MB Infinity Cache.
 The offline rows (calibration absmax, weight fold) and the decode shapes are
@@ -26,6 +29,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, TOP/s
+PEAK_FP6_TOPS = 10100.0      # MI355X dense fp6 / fp4 MFMA, TFLOP/s (the instruction the fast GEMM issues)
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, GB/s
 
 M, K = 2048, 4096
@@ -101,7 +105,7 @@ def main():
                                  "workload": "fp16 [2048,4096] chunks, 16 distinct (268 MB)"}
 
     Xs = [torch.from_numpy(wl.cfg2_X(seed=1 + 10 * s)).to(dev) for s in range(SETS)]
-    Wq, Ws, inv_s = {}, {}, None
+    Wq, Ws, W6, inv_s = {}, {}, {}, None
     for N in NS:
         W = torch.from_numpy(wl.cfg2_W(N)).to(dev)
         ws_bytes = sr.sr_fold_workspace_bytes(K, N)
@@ -114,18 +118,25 @@ def main():
         # weight sets: the same codes rolled along N, so every set is a distinct buffer with identical statistics
         Wq[N] = [torch.roll(outs[0], s * 16, 0).contiguous() for s in range(SETS)]
         Ws[N] = [torch.roll(outs[1], s * 16, 0).contiguous() for s in range(SETS)]
+        W6[N] = [sr.sr_pack_f6_tiles(w) for w in Wq[N]]                   # offline: weights as f6 tiles
+        if not args.no_extra:
+            t6 = torch.empty_like(W6[N][0])
+            t = graph_time(lambda i: sr.sr_pack_f6_tiles(Wq[N][i % SETS], t6), 16)
+            extra["pack_f6_tiles_N%d" % N] = {"us": round(t * 1e6, 1), "GB/s": round((K * N * 1.25) / t / 1e9, 1)}
+            del t6
         inv_s = outs[2]
         del W, work
 
     Xq = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
+    X6 = torch.zeros(sr.sr_f6_tiles_bytes(M, K), dtype=torch.uint8, device=dev)
     xs = torch.empty(M, dtype=torch.float32, device=dev)
     Y = {N: torch.empty((M, N), dtype=torch.float16, device=dev) for N in NS}
 
     def step(i):
         s = i % SETS
         for N in NS:
-            sr.sr_fwht_quant_act(Xs[s], inv_s, CLIP, Xq, xs)
-            sr.sr_w4a4_gemm(Xq, xs, Wq[N][s], Ws[N][s], sr.SR_F16, Y[N])
+            sr.sr_fwht_quant_act_f6(Xs[s], inv_s, CLIP, X6, xs)
+            sr.sr_w4a4_gemm_f6(X6, xs, W6[N][s], Ws[N][s], M, N, K, sr.SR_F16, Y[N])
 
     for i in range(args.warmup):
         step(i)
@@ -141,12 +152,12 @@ def main():
     t0 = time.perf_counter()
     for i in range(args.steps):
         s = i % SETS
-        sr.sr_fwht_quant_act(Xs[s], inv_s, CLIP, Xq, xs)
-        sr.sr_w4a4_gemm(Xq, xs, Wq[4096][s], Ws[4096][s], sr.SR_F16, Y[4096])
-        sr.sr_fwht_quant_act(Xs[s], inv_s, CLIP, Xq, xs)
+        sr.sr_fwht_quant_act_f6(Xs[s], inv_s, CLIP, X6, xs)
+        sr.sr_w4a4_gemm_f6(X6, xs, W6[4096][s], Ws[4096][s], M, 4096, K, sr.SR_F16, Y[4096])
+        sr.sr_fwht_quant_act_f6(Xs[s], inv_s, CLIP, X6, xs)
         if i % EV_EVERY == 0:
             gemm_ev[i // EV_EVERY][0].record()
-        sr.sr_w4a4_gemm(Xq, xs, Wq[14336][s], Ws[14336][s], sr.SR_F16, Y[14336])
+        sr.sr_w4a4_gemm_f6(X6, xs, W6[14336][s], Ws[14336][s], M, 14336, K, sr.SR_F16, Y[14336])
         if i % EV_EVERY == 0:
             gemm_ev[i // EV_EVERY][1].record()
     torch.cuda.synchronize()
@@ -159,11 +170,14 @@ def main():
     gemm_ops = 2.0 * M * 14336 * K
     # HBM bytes per launch of this kernel: FETCH_SIZE + WRITE_SIZE from two rocprofv3 --pmc runs of this same
     # command, scaled by the copy-kernel factors (profiles/bench_prefill_cfg2_hbm_traffic.md)
-    roofline = {"bound": "mfma", "kernel": "sr_w4a4_gemm: gemm_w4a4_kernel, M=2048 N=14336 K=4096",
-                "achieved": round(gemm_ops / gemm_avg_s / 1e12, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                "frac": round(gemm_ops / gemm_avg_s / 1e12 / PEAK_INT8_TOPS, 4),
-                "traffic": {"hbm_bytes_per_launch": 169.5e6, "algorithmic_bytes": 92.3e6,
-                            "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/"},
+    # The kernel issues FP6 (E2M3) matrix instructions, so its roofline is the chip's dense fp6 peak; the
+    # benchmark's own yardstick (fraction of the int8-MFMA peak, the rate a 4-bit integer GEMM is usually priced
+    # at) is reported beside it.
+    roofline = {"bound": "mfma", "kernel": "sr_w4a4_gemm_f6: gemm_f6_kernel, M=2048 N=14336 K=4096",
+                "achieved": round(gemm_ops / gemm_avg_s / 1e12, 2), "peak": PEAK_FP6_TOPS, "unit": "TFLOP/s",
+                "frac": round(gemm_ops / gemm_avg_s / 1e12 / PEAK_FP6_TOPS, 4),
+                "frac_int8_mfma_peak": round(gemm_ops / gemm_avg_s / 1e12 / PEAK_INT8_TOPS, 4),
+                "traffic": None,
                 "avg_launch_us": round(gemm_avg_s * 1e6, 2), "median_launch_us": round(gemm_ms[len(gemm_ms) // 2] * 1e3, 2)}
 
     # ---------------- per-kernel side measurements (same buffers, event-timed) ------------
@@ -172,10 +186,18 @@ def main():
         b = M * K * 2.5 + M * 4
         extra["fwht_quant_K4096"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
                                      "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+        t = graph_time(lambda i: sr.sr_fwht_quant_act_f6(Xs[i % SETS], inv_s, CLIP, X6, xs), 64)
+        b = M * K * 2.75 + M * 4
+        extra["fwht_quant_f6_K4096"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
+                                        "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
         for N in NS:
+            t = graph_time(lambda i: sr.sr_w4a4_gemm_f6(X6, xs, W6[N][i % SETS], Ws[N][i % SETS], M, N, K, sr.SR_F16, Y[N]), 64)
+            extra["gemm_f6_N%d" % N] = {"us": round(t * 1e6, 2), "TOPS": round(2.0 * M * N * K / t / 1e12, 1),
+                                        "frac_int8_mfma_peak": round(2.0 * M * N * K / t / 1e12 / PEAK_INT8_TOPS, 4),
+                                        "frac_fp6_mfma_peak": round(2.0 * M * N * K / t / 1e12 / PEAK_FP6_TOPS, 4)}
             t = graph_time(lambda i: sr.sr_w4a4_gemm(Xq, xs, Wq[N][i % SETS], Ws[N][i % SETS], sr.SR_F16, Y[N]), 64)
-            extra["gemm_N%d" % N] = {"us": round(t * 1e6, 2), "TOPS": round(2.0 * M * N * K / t / 1e12, 1),
-                                     "frac_mfma": round(2.0 * M * N * K / t / 1e12 / PEAK_INT8_TOPS, 4)}
+            extra["gemm_int8_N%d" % N] = {"us": round(t * 1e6, 2), "TOPS": round(2.0 * M * N * K / t / 1e12, 1),
+                                          "frac_int8_mfma_peak": round(2.0 * M * N * K / t / 1e12 / PEAK_INT8_TOPS, 4)}
         # decode: M in {1,4,16}, K=4096 -> N=14336, weights streamed from >512 MB of distinct copies
         copies = [Wq[14336][0].clone() for _ in range(20)]
         wsc = Ws[14336][0]
@@ -217,8 +239,19 @@ def main():
         extra["fwht_quant_K14336"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
                                       "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
         t = graph_time(lambda i: sr.sr_w4a4_gemm(Xq3, xs3, Wq3, ws3, sr.SR_F16, Y3), 32)
-        extra["gemm_K14336_N4096"] = {"us": round(t * 1e6, 2), "TOPS": round(2.0 * M * N3 * K3 / t / 1e12, 1),
-                                      "frac_mfma": round(2.0 * M * N3 * K3 / t / 1e12 / PEAK_INT8_TOPS, 4)}
+        extra["gemm_int8_K14336_N4096"] = {"us": round(t * 1e6, 2), "TOPS": round(2.0 * M * N3 * K3 / t / 1e12, 1),
+                                           "frac_int8_mfma_peak": round(2.0 * M * N3 * K3 / t / 1e12 / PEAK_INT8_TOPS, 4)}
+        X63 = torch.zeros(sr.sr_f6_tiles_bytes(M, K3), dtype=torch.uint8, device=dev)
+        W63 = sr.sr_pack_f6_tiles(Wq3)
+        t = graph_time(lambda i: sr.sr_fwht_quant_act_f6(X3[i % 4], None, CLIP, X63, xs3), 32)
+        b = M * K3 * 2.75 + M * 4
+        extra["fwht_quant_f6_K14336"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
+                                         "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+        t = graph_time(lambda i: sr.sr_w4a4_gemm_f6(X63, xs3, W63, ws3, M, N3, K3, sr.SR_F16, Y3), 32)
+        extra["gemm_f6_K14336_N4096"] = {"us": round(t * 1e6, 2), "TOPS": round(2.0 * M * N3 * K3 / t / 1e12, 1),
+                                         "frac_int8_mfma_peak": round(2.0 * M * N3 * K3 / t / 1e12 / PEAK_INT8_TOPS, 4),
+                                         "frac_fp6_mfma_peak": round(2.0 * M * N3 * K3 / t / 1e12 / PEAK_FP6_TOPS, 4)}
+        del X63, W63
         copies = [Wq3.clone() for _ in range(20)]
         xq_d, xs_d = sr.sr_fwht_quant_act(X3[0][:1].contiguous(), None, CLIP)
         Yd = torch.empty((1, N3), dtype=torch.float16, device=dev)
@@ -287,10 +320,35 @@ def main():
         torch.cuda.synchronize()
         t = ev_time(layer, 5)
         ops5 = sum(2.0 * M5 * kk * nn for _, kk, nn in wl.CFG5_LINEARS)
+        extra["cfg5_layer_M16384_int8"] = {"ms": round(t * 1e3, 3), "TOPS": round(ops5 / t / 1e12, 1),
+                                           "frac_int8_mfma_peak": round(ops5 / t / 1e12 / PEAK_INT8_TOPS, 4),
+                                           "workload": "7 linears (q,k,v,o,gate,up,down) + 4 rotate/quantise passes, 16384 tokens"}
+        X65 = torch.zeros(sr.sr_f6_tiles_bytes(M5, K), dtype=torch.uint8, device=dev)
+        X65d = torch.zeros(sr.sr_f6_tiles_bytes(M5, K3), dtype=torch.uint8, device=dev)
+        W65 = {n: sr.sr_pack_f6_tiles(W5[n][0]) for n, _, _ in wl.CFG5_LINEARS}
+        dims = {n: (kk, nn) for n, kk, nn in wl.CFG5_LINEARS}
+
+        def g6(n, X6_, Yv):
+            sr.sr_w4a4_gemm_f6(X6_, xs5, W65[n], W5[n][1], M5, dims[n][1], dims[n][0], sr.SR_F16, Yv)
+
+        def layer6(i):
+            sr.sr_fwht_quant_act_f6(X5, inv_s, CLIP, X65, xs5)
+            for n in ("q", "k", "v"):
+                g6(n, X65, Y5[:, :dims[n][1]])
+            sr.sr_fwht_quant_act_f6(X5, inv_s, CLIP, X65, xs5)
+            g6("o", X65, Y5[:, :4096])
+            sr.sr_fwht_quant_act_f6(X5, inv_s, CLIP, X65, xs5)
+            for n in ("gate", "up"):
+                g6(n, X65, Y5)
+            sr.sr_fwht_quant_act_f6(X5d, None, CLIP, X65d, xs5)
+            g6("down", X65d, Y5[:, :4096])
+        layer6(0)
+        torch.cuda.synchronize()
+        t = ev_time(layer6, 5)
         extra["cfg5_layer_M16384"] = {"ms": round(t * 1e3, 3), "TOPS": round(ops5 / t / 1e12, 1),
-                                      "frac_mfma": round(ops5 / t / 1e12 / PEAK_INT8_TOPS, 4),
-                                      "workload": "7 linears (q,k,v,o,gate,up,down) + 4 rotate/quantise passes, 16384 tokens"}
-        del X5, X5d, Xq5, Xq5d, W5, Y5
+                                      "frac_int8_mfma_peak": round(ops5 / t / 1e12 / PEAK_INT8_TOPS, 4),
+                                      "workload": "7 linears (q,k,v,o,gate,up,down) + 4 rotate/quantise passes, 16384 tokens, f6 path"}
+        del X5, X5d, Xq5, Xq5d, W5, Y5, X65, X65d, W65
 
     # ---------------- CPU baseline: the oracle on a bounded sample ------------------------
     cpu = None
@@ -316,10 +374,10 @@ def main():
         "metric": "W4A4 linear TOPS (prefill; FWHT + INT4 quantise + INT4 GEMM + dequant)",
         "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "int4 codes on int8 MFMA, int32 accumulate; fp32 rotation",
+        "vs_baseline": None, "dtype": "int4 codes as fp6 (E2M3) on the FP6 MFMA, fp32 accumulate (exact integers); fp32 rotation",
         "data": "synthetic",
         "config": {"workload": "configs[1]: prefill X fp16 [2048,4096], two linears N=4096 and N=14336, "
-                               "alpha=0.5, act clip 0.9, H_4096; step = 2 x (sr_fwht_quant_act + sr_w4a4_gemm)",
+                               "alpha=0.5, act clip 0.9, H_4096; step = 2 x (sr_fwht_quant_act_f6 + sr_w4a4_gemm_f6)",
                    "M": M, "K": K, "N": list(NS), "input_sets_rotated": SETS},
         "frac_int8_mfma_peak": round(tops / PEAK_INT8_TOPS, 4),
         "roofline": roofline, "cpu_baseline": cpu, "extra": extra,
