@@ -23,7 +23,7 @@ namespace {
 
 // F6: Q receives f6 tiles (operands of the FP6-MFMA GEMM) instead of packed nibbles; K % 128 == 0 then.
 template <int K, int NT, bool F6>
-__global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict__ X, int64_t ldx,
+__global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict__ X, int64_t ldx, int64_t rows,
                                                         const float *__restrict__ pre, float clip,
                                                         float post_scale, uint8_t *__restrict__ Q,
                                                         float *__restrict__ scale_out)
@@ -32,7 +32,15 @@ __global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict
     __shared__ float red[NT / 64];
 
     const int t = threadIdx.x;
-    const int64_t m = blockIdx.x;
+    int64_t m = blockIdx.x;
+    if constexpr (F6) {
+        // The eight rows of a tile block (768 contiguous bytes per 128 codes) should be written from ONE XCD at
+        // about the same time, so that its L2 assembles whole lines: workgroups are dealt round-robin to the 8
+        // XCDs, so workgroup w = 8 a + x (XCD x) takes row r = a % 8 of row block 8 (a / 8) + x.
+        const int64_t w = blockIdx.x, x = w & 7, a = w >> 3;
+        m = 64 * (a >> 3) + 8 * x + (a & 7);
+        if (m >= rows) return;                           // the grid is rounded up to a multiple of 64
+    }
     const float amax = rotate_row_absmax<K, NT>(X + m * ldx, pre, row, red, t);
 
     // Delta = clip * absmax / 7 (1 for an all-zero row), Eq. (1) with the signed range
@@ -42,7 +50,7 @@ __global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict
 
     // ---- quantise 8 contiguous values -> one packed dword (or 48 bits of a tile piece) ---------
     uint32_t *q = reinterpret_cast<uint32_t *>(Q + m * (int64_t)(K / 2));
-    const int64_t row_blocks = ((int64_t)gridDim.x + 7) >> 3;
+    const int64_t row_blocks = (rows + 7) >> 3;
     for (int c = t; c < K / 8; c += NT) {
         const float *src = row + pad(8 * c);
         const float4 a = *reinterpret_cast<const float4 *>(src);
@@ -228,7 +236,13 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
     constexpr int K = 4096, ROWF = K + 64;               // floats per wave-private row incl. padding
     extern __shared__ float smem_rows[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t m = (int64_t)blockIdx.x * 4 + wave;
+    int64_t m = (int64_t)blockIdx.x * 4 + wave;
+    if constexpr (F6) {
+        // both halves of a tile block (8 rows) from the same XCD: workgroup w = 8 a + x (XCD x) takes half
+        // a % 2 of row block 8 (a / 2) + x (see the workgroup-per-row kernel)
+        const int64_t w = blockIdx.x, x = w & 7, a = w >> 3;
+        m = 8 * (8 * (a >> 1) + x) + 4 * (a & 1) + wave;
+    }
     if (m >= rows) return;                               // no barrier below: waves are independent
     float *buf = smem_rows + wave * ROWF;
     const __half *x = X + m * ldx;
@@ -307,8 +321,9 @@ hipError_t launch_one(const void *X, int64_t rows, int64_t ldx, const float *pre
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)rows), dim3(NT), lds, st,
-                       static_cast<const __half *>(X), ldx, pre, clip, post_scale, Q, scale_out);
+    const unsigned grid = F6 ? (unsigned)((rows + 63) / 64 * 64) : (unsigned)rows;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st,
+                       static_cast<const __half *>(X), ldx, rows, pre, clip, post_scale, Q, scale_out);
     return hipGetLastError();
 }
 
@@ -341,7 +356,7 @@ hipError_t launch_wave4096(const void *X, int64_t rows, int64_t ldx, const float
                            uint8_t *Q, float *scale_out, hipStream_t st)
 {
     constexpr size_t lds = 4 * (4096 + 64) * sizeof(float);
-    const unsigned blocks = (unsigned)((rows + 3) / 4);
+    const unsigned blocks = F6 ? (unsigned)((rows + 63) / 64 * 16) : (unsigned)((rows + 3) / 4);
     auto kern = fwht4096_wave_kernel<HAS_PRE, F6>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;

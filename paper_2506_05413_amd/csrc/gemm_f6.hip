@@ -68,14 +68,16 @@ __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN * WG_PER_CU / 4) void gem
     constexpr int WM = BM / WGM, WN = BN / WGN;      // wave tile
     constexpr int FM = WM / 32, FN = WN / 32;        // 32 x 32 MFMA tiles per wave
     constexpr int X_BYTES = BM / 8 * BLK, STAGE_BYTES = (BM + BN) / 8 * BLK;
-    constexpr int NDMA = STAGE_BYTES / 1024;         // 1 KB LDS-DMA instructions per stage
-    constexpr int RPW = NDMA / NWAVE;                // ... per wave
-    constexpr int XI = X_BYTES / 1024 / NWAVE;       // the first XI instructions of a wave copy X rows, the rest W rows
+    // 1 KB LDS-DMA instructions per stage: NXI for the X run, NWI for the W run; every wave issues XI + WI of
+    // them -- where the count does not divide by the waves, the last ones wrap around and copy a KB a second
+    // time (same data to the same place), so that all waves keep the same number of loads in flight
+    constexpr int NXI = X_BYTES / 1024, NWI = (STAGE_BYTES - X_BYTES) / 1024;
+    constexpr int XI = (NXI + NWAVE - 1) / NWAVE, WI = (NWI + NWAVE - 1) / NWAVE;
+    constexpr int RPW = XI + WI;
     constexpr int SCALE_OFF = SLOTS * STAGE_BYTES;   // two areas of BM + BN floats behind the ring
     constexpr int NSC = (BM + BN) / 64;              // scale DMA instructions per tile
-    static_assert(NDMA % NWAVE == 0 && (X_BYTES / 1024) % NWAVE == 0 && X_BYTES % 1024 == 0 && STAGE_BYTES % 1024 == 0 &&
-                      WM % 32 == 0 && WN % 32 == 0 && BM % 64 == 0 && BN % 64 == 0 && SLOTS >= 2 &&
-                      SLOTS * RPW + 8 * FM < 64, "tile");
+    static_assert(X_BYTES % 1024 == 0 && STAGE_BYTES % 1024 == 0 && WM % 32 == 0 && WN % 32 == 0 && BM % 64 == 0 &&
+                      BN % 64 == 0 && SLOTS >= 2 && SLOTS * RPW < 64, "tile");
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
@@ -86,23 +88,25 @@ __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN * WG_PER_CU / 4) void gem
     const int nc = K >> 7;                           // 128-code chunks per row = stages
     const uint32_t cx_bytes = (uint32_t)((M + 7) >> 3) * BLK, cw_bytes = (uint32_t)((N + 7) >> 3) * BLK;   // one chunk of X / W
 
-    // ---- DMA sources: instruction q = wave + NWAVE * i copies bytes [1024 q, 1024 q + 1024) of the stage's X run
-    // (q < X_BYTES / 1024) or of its W run; a lane past the end of the operand re-reads the last 16 bytes
-    uint32_t goff[RPW];
+    // ---- DMA sources: X instruction q copies bytes [1024 q, 1024 q + 1024) of the stage's X run, W instruction q
+    // of its W run; a lane past the end of the operand re-reads the last 16 bytes
+    uint32_t goff[RPW], ldst[RPW];
+#pragma unroll
+    for (int i = 0; i < RPW; ++i)
+        ldst[i] = i < XI ? (uint32_t)((wave + NWAVE * i) % NXI) * 1024 : X_BYTES + (uint32_t)((wave + NWAVE * (i - XI)) % NWI) * 1024;
     auto set_sources = [&](int m0, int n0) {
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
-            const int q = wave + NWAVE * i;
             uint32_t off;
-            if (i < XI) { off = (uint32_t)(m0 >> 3) * BLK + q * 1024 + lane * 16; off = off < cx_bytes ? off : cx_bytes - 16; }
-            else { off = (uint32_t)(n0 >> 3) * BLK + (q - X_BYTES / 1024) * 1024 + lane * 16; off = off < cw_bytes ? off : cw_bytes - 16; }
+            if (i < XI) { off = (uint32_t)(m0 >> 3) * BLK + ldst[i] + lane * 16; off = off < cx_bytes ? off : cx_bytes - 16; }
+            else { off = (uint32_t)(n0 >> 3) * BLK + (ldst[i] - X_BYTES) + lane * 16; off = off < cw_bytes ? off : cw_bytes - 16; }
             goff[i] = off;
         }
     };
     const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
     auto dma_one = [&](int idx, int s, int slot) {   // instruction idx of this wave, stage s -> ring slot
         dma16((idx < XI ? X6 + (int64_t)s * cx_bytes : W6 + (int64_t)s * cw_bytes), goff[idx],
-              smem_base + (uint32_t)slot * STAGE_BYTES + (uint32_t)(wave + NWAVE * idx) * 1024);
+              smem_base + (uint32_t)slot * STAGE_BYTES + ldst[idx]);
     };
     auto issue = [&](int s, int slot) {
 #pragma unroll
@@ -361,12 +365,19 @@ hipError_t launch_gemm_f6(const uint8_t *X6, const float *xs, const uint8_t *W6,
         case 61: return launch_f6<256, 256, 2, 4, 3, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
         case 63: return launch_f6<256, 128, 2, 2, 2, 2>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
         case 64: return launch_f6<256, 256, 2, 4, 2, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
+        case 65: return launch_f6<256, 128, 4, 2, 4, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
+        case 66: return launch_f6<256, 128, 4, 2, 3, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
         default: break;
     }
+    // 256 x 256 tiles (eight waves of 128 x 64) run ~15 % faster per output than 256 x 128 tiles (eight waves of
+    // 64 x 64: more LDS traffic per MFMA), so the small tile is taken only where it saves whole rounds:
+    // measured at M = 2048, K = 4096: N = 14336 63.8 us against 77.6 us; N = 4096 (128 big tiles on 256 CUs)
+    // 28.9 us against 24.3 us.  Four-wave workgroups (one wave per SIMD) lost everywhere.
     const int64_t cus = compute_units();
-    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
-    if (t256 >= cus) return launch_f6<256, 256, 2, 4, 3, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
-    return launch_f6<256, 128, 2, 2, 2, 2>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
+    auto rounds = [&](int64_t bm, int64_t bn) { return (((M + bm - 1) / bm) * ((N + bn - 1) / bn) + cus - 1) / cus; };
+    if (rounds(256, 256) * 256 * 256 * 85 <= rounds(256, 128) * 256 * 128 * 100)
+        return launch_f6<256, 256, 2, 4, 3, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
+    return launch_f6<256, 128, 4, 2, 4, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
 }
 
 }  // namespace sr

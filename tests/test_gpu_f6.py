@@ -61,7 +61,7 @@ def test_int32_accumulators_bit_exact(gpu, M, N, K):
     assert got.dtype == np.int32 and np.array_equal(got.astype(np.int64), want)
 
 
-@pytest.mark.parametrize("tile", ["61", "63", "64"])
+@pytest.mark.parametrize("tile", ["61", "63", "64", "65", "66"])
 def test_every_tile_configuration(gpu, tile, monkeypatch):
     """The launch heuristic picks one configuration per shape; each of them is checked on a shape with
     ragged edges and more tiles than workgroups can hold at once is covered by the full-size test below."""
