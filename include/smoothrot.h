@@ -248,7 +248,7 @@ SR_API int sr_w4a4_linear_decode(const void *X_f16, int64_t M, int64_t K, int64_
  *   (all row blocks of one 128-code chunk are contiguous);
  *   inside it, piece (r, t, g) = codes k = 128 C + 64 t + 32 g + j, j = 0..31, of row 8 R + r,
  *   code j in bits [6j, 6j+6) of a 24-byte little-endian string, whose first 16 bytes sit at
- *   256 t + 128 (g ^ (R & 1)) + 16 r and whose last 8 bytes at 512 + 64 ((2t + g) ^ (R & 3)) + 8 r.
+ *   256 t + 128 (g ^ (R & 1)) + 16 r and whose last 8 bytes at 512 + 128 (g ^ (R & 1)) + 16 r + 8 t.
  * ------------------------------------------------------------------------------------------ */
 
 /* Bytes of the f6-tile form of a [rows, K] code matrix (0 if K % 128 != 0 or a size is <= 0). */

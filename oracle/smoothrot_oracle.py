@@ -427,7 +427,7 @@ def f6_field(codes) -> np.ndarray:
 
 
 def _f6_piece_offsets(R: int, r: int, t: int, g: int):
-    return 256 * t + 128 * (g ^ (R & 1)) + 16 * r, 512 + 64 * ((2 * t + g) ^ (R & 3)) + 8 * r
+    return 256 * t + 128 * (g ^ (R & 1)) + 16 * r, 512 + 128 * (g ^ (R & 1)) + 16 * r + 8 * t
 
 
 def f6_tiles_pack(codes: np.ndarray) -> np.ndarray:
@@ -435,7 +435,7 @@ def f6_tiles_pack(codes: np.ndarray) -> np.ndarray:
     codes to a multiple of 8).  Block (R, C) = rows 8R..8R+7 x codes 128C..128C+127 is 768 bytes at
     ((C * rows/8) + R) * 768; piece (r, t, g) = codes k = 128C + 64t + 32g + j, j = 0..31, of row
     8R + r as a 192-bit little-endian string (code j in bits 6j..6j+5); its first 16 bytes sit at
-    256t + 128(g ^ (R & 1)) + 16r, its last 8 bytes at 512 + 64((2t + g) ^ (R & 3)) + 8r."""
+    256t + 128(g ^ (R & 1)) + 16r, its last 8 bytes at 512 + 128(g ^ (R & 1)) + 16r + 8t."""
     rows, K = codes.shape
     assert K % 128 == 0
     rb, nc = (rows + 7) // 8, K // 128

@@ -244,7 +244,7 @@ __device__ __forceinline__ void store_f6_piece(uint32_t lo, uint32_t hi, int lan
     if ((lane & 3) == 0)
         *reinterpret_cast<uint4 *>(blk + 256 * t + 128 * (g ^ (Rl & 1)) + 16 * r) = make_uint4(lo, a, b, lo_n2);
     else if ((lane & 3) == 2)
-        *reinterpret_cast<uint2 *>(blk + 512 + 64 * ((2 * t + g) ^ Rl) + 8 * r) = make_uint2(a, b);
+        *reinterpret_cast<uint2 *>(blk + 512 + 128 * (g ^ (Rl & 1)) + 16 * r + 8 * t) = make_uint2(a, b);
 }
 
 // ---- rotation of one row by a whole workgroup -----------------------------------------------

@@ -28,9 +28,11 @@
 //   of lane (row, k half g) of MFMA step t.  Its first 16 bytes live at
 //       256 t + 128 (g ^ (R & 1)) + 16 r
 //   and its last 8 bytes at
-//       512 + 64 ((2t + g) ^ (R & 3)) + 8 r
-//   so that a wave's ds_read_b128 / ds_read_b64 of a 32-row fragment (four blocks) touch every
-//   LDS bank once.  (The 12-byte form of the LDS-DMA load leaves a 4-byte hole after every lane's data in
+//       512 + 128 (g ^ (R & 1)) + 16 r + 8 t
+//   i.e. the tails of the two steps share one 16-byte slot, so that a stage of a fragment is three
+//   ds_read_b128 (LDS serves those at twice the bytes per clock of narrower reads -- measured -- and
+//   LDS time, not MFMA time, bounded the first version that read the tails 8 bytes at a time), each
+//   touching every LDS bank once over a 32-row fragment (four blocks).  (The 12-byte form of the LDS-DMA load leaves a 4-byte hole after every lane's data in
 //   LDS -- measured -- so stages are copied with the 16-byte form, 1 KB per instruction.)
 //
 // Kernel structure: persistent workgroups, tile BM x BN, ring of SLOTS stages of 128 codes, one
@@ -132,20 +134,24 @@ __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN * WG_PER_CU / 4) void gem
     // ---- fragment addresses: lane (r = l & 31, g = l >> 5) reads row r of a 32-row fragment, k half g
     const int fr = lane & 31, fg = lane >> 5;
     const int rq = fr >> 3;                          // block of the fragment (= R & 3: fragments start at multiples of 32 rows)
-    const uint32_t a16 = rq * BLK + ((fg ^ (rq & 1)) << 7) + ((fr & 7) << 4);
-    const uint32_t a8 = rq * BLK + 512 + ((fg ^ rq) << 6) + ((fr & 7) << 3);   // step 0; step 1 = a8 ^ 128
+    const uint32_t a16 = rq * BLK + ((fg ^ (rq & 1)) << 7) + ((fr & 7) << 4);   // step 0; step 1 at + 256; tails at + 512
     const uint32_t xfrag = (wm * WM / 8) * BLK, wfrag = X_BYTES + (wn * WN / 8) * BLK;
 
     struct Frags { v8i x[FM]; v8i w[FN]; };
-    auto read_frag = [&](v8i &f, uint32_t base, int t) {
-        const uint4 lo = *reinterpret_cast<const uint4 *>(smem + base + a16 + t * 256);
-        const uint2 hi = *reinterpret_cast<const uint2 *>(smem + base + (a8 ^ (t << 7)));
-        f[0] = (int)lo.x; f[1] = (int)lo.y; f[2] = (int)lo.z; f[3] = (int)lo.w;
-        f[4] = (int)hi.x; f[5] = (int)hi.y;
-    };
-    auto read_q = [&](Frags &f, int q, uint32_t sbase, int t) {       // fragment q: X fragments first
-        if (q < FM) read_frag(f.x[q < FM ? q : 0], sbase + xfrag + q * 4 * BLK, t);
-        else read_frag(f.w[q < FM ? 0 : q - FM], sbase + wfrag + (q - FM) * 4 * BLK, t);
+    uint2 tail1[FM + FN];                            // tails of step 1, read together with those of step 0
+    // fragment q of a stage (X fragments first), step t: step 0 also fetches the 16 bytes holding both tails
+    auto read_q = [&](Frags &f, int q, uint32_t sbase, int t) {
+        const uint32_t base = sbase + (q < FM ? xfrag + q * 4 * BLK : wfrag + (q - FM) * 4 * BLK) + a16;
+        v8i &d = q < FM ? f.x[q < FM ? q : 0] : f.w[q < FM ? 0 : q - FM];
+        const uint4 lo = *reinterpret_cast<const uint4 *>(smem + base + t * 256);
+        d[0] = (int)lo.x; d[1] = (int)lo.y; d[2] = (int)lo.z; d[3] = (int)lo.w;
+        if (t == 0) {
+            const uint4 tl = *reinterpret_cast<const uint4 *>(smem + base + 512);
+            d[4] = (int)tl.x; d[5] = (int)tl.y;
+            tail1[q] = make_uint2(tl.z, tl.w);
+        } else {
+            d[4] = (int)tail1[q].x; d[5] = (int)tail1[q].y;
+        }
     };
 
     v16f acc[FN][FM];
@@ -342,7 +348,7 @@ __global__ __launch_bounds__(256) void pack_f6_kernel(const uint8_t *__restrict_
     uint8_t *blk = T6 + bc * BLK;
     const int Rl = (int)(R & 3);
     *reinterpret_cast<uint4 *>(blk + 256 * t + 128 * (g ^ (Rl & 1)) + 16 * r) = make_uint4(o[0], o[1], o[2], o[3]);
-    *reinterpret_cast<uint2 *>(blk + 512 + 64 * ((2 * t + g) ^ Rl) + 8 * r) = make_uint2(o[4], o[5]);
+    *reinterpret_cast<uint2 *>(blk + 512 + 128 * (g ^ (Rl & 1)) + 16 * r + 8 * t) = make_uint2(o[4], o[5]);
 }
 
 }  // namespace

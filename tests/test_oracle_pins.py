@@ -589,8 +589,12 @@ def test_f6_tiles_hand_placed_codes():
     assert img[256 + 48] == 1 and np.count_nonzero(img) == 1
     img = image(8, 0, 1)                                 # R=1: second block of chunk 0; g flips with R & 1
     assert img[768 + 128] == 1 and np.count_nonzero(img) == 1
-    img = image(8, 31, 1)                                # R=1 tail: 512 + 64 * ((0) ^ 1) + 7
-    assert img[768 + 512 + 64 + 7] == 4 and np.count_nonzero(img) == 1
+    img = image(8, 31, 1)                                # R=1 tail: 512 + 128 * (0 ^ 1) + 7
+    assert img[768 + 512 + 128 + 7] == 4 and np.count_nonzero(img) == 1
+    img = image(0, 64 + 31, 1)                           # t=1 tail shares the 16-byte slot of the t=0 tail: + 8
+    assert img[512 + 8 + 7] == 4 and np.count_nonzero(img) == 1
+    img = image(5, 32 + 64 + 31, -1)                     # r=5, t=1, g=1: 512 + 128 + 80 + 8, field 33 << 2 in the last byte
+    assert img[512 + 128 + 80 + 8 + 7] == (33 << 2) & 255 and np.count_nonzero(img) == 1
     img = image(0, 128, 1)                               # chunk C=1 starts after both row blocks of chunk 0
     assert img[2 * 768] == 1 and np.count_nonzero(img) == 1
 
