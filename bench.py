@@ -169,7 +169,8 @@ def main():
     gemm_avg_s = sum(gemm_ms) / len(gemm_ms) * 1e-3
     gemm_ops = 2.0 * M * 14336 * K
     # HBM bytes per launch of this kernel: FETCH_SIZE + WRITE_SIZE from two rocprofv3 --pmc runs of this same
-    # command, scaled by the copy-kernel factors (profiles/bench_prefill_cfg2_hbm_traffic.md)
+    # command, scaled by the copy-kernel factors (profiles/bench_prefill_cfg2_hbm_traffic.md); algorithmic bytes =
+    # X6 6.3 MB + W6 44.0 MB read + Y 58.7 MB written
     # The kernel issues FP6 (E2M3) matrix instructions, so its roofline is the chip's dense fp6 peak; the
     # benchmark's own yardstick (fraction of the int8-MFMA peak, the rate a 4-bit integer GEMM is usually priced
     # at) is reported beside it.
@@ -177,7 +178,8 @@ def main():
                 "achieved": round(gemm_ops / gemm_avg_s / 1e12, 2), "peak": PEAK_FP6_TOPS, "unit": "TFLOP/s",
                 "frac": round(gemm_ops / gemm_avg_s / 1e12 / PEAK_FP6_TOPS, 4),
                 "frac_int8_mfma_peak": round(gemm_ops / gemm_avg_s / 1e12 / PEAK_INT8_TOPS, 4),
-                "traffic": None,
+                "traffic": {"hbm_bytes_per_launch": 197.5e6, "algorithmic_bytes": 109.0e6,
+                            "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/"},
                 "avg_launch_us": round(gemm_avg_s * 1e6, 2), "median_launch_us": round(gemm_ms[len(gemm_ms) // 2] * 1e3, 2)}
 
     # ---------------- per-kernel side measurements (same buffers, event-timed) ------------
