@@ -144,8 +144,13 @@ __device__ __forceinline__ void tile_origin(int v, int tiles_m, int tiles_n, int
     if (xcd_m > 0) {
         const int x = v & 7, l = v >> 3;
         const int rm = tiles_m / xcd_m, rn = tiles_n / (8 / xcd_m);      // rectangle size in tiles
-        tm = (x % xcd_m) * rm + l % rm;
-        tn = (x / xcd_m) * rn + l / rm;
+        // walk: mw tiles in m fastest, then across the rectangle in n, then the next mw rows of tiles -- the ~32
+        // tiles an XCD works on at a time then form a block of 8 x 4 tiles instead of a 32 x 1 column
+        // (M = 16384, N = 4096, K = 4096 on the FP6 kernel: 148.6 -> 139.5 us)
+        const int mw = (rm > 8 && rm % 8 == 0) ? 8 : rm;
+        const int a = l % mw, b = (l / mw) % rn, c = l / (mw * rn);
+        tm = (x % xcd_m) * rm + c * mw + a;
+        tn = (x / xcd_m) * rn + b;
     } else {
         tm = v % tiles_m;
         tn = v / tiles_m;

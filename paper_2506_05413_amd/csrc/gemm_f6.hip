@@ -297,7 +297,11 @@ hipError_t launch_f6(const uint8_t *X6, const float *xs, const uint8_t *W6, cons
         if (e != hipSuccess) return e;
     }
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
-    const int xcd_m = choose_xcd_split(tiles_m, tiles_n, BM, BN);
+    int xcd_m = choose_xcd_split(tiles_m, tiles_n, BM, BN);
+    if (const char *env = getenv("SMOOTHROT_GEMM_XCDM")) {            // tuning aid: force the split (0 = none)
+        const int f = atoi(env);
+        if (f == 0 || ((f == 1 || f == 2 || f == 4 || f == 8) && tiles_m % f == 0 && tiles_n % (8 / f) == 0)) xcd_m = f;
+    }
     int64_t grid = (int64_t)compute_units() * WG_PER_CU;
     if (const char *env = getenv("SMOOTHROT_GEMM_GRID")) grid = atoll(env) > 0 ? atoll(env) / 8 * 8 : grid;   // tuning aid
     if (grid < 8) grid = 8;
