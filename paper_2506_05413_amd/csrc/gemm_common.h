@@ -51,7 +51,9 @@ __device__ __forceinline__ float acc_f32(float a) { return a; }
 __device__ __forceinline__ int acc_i32(int a) { return a >> 8; }
 __device__ __forceinline__ int acc_i32(float a) { return (int)(a * 64.f); }
 
-template <int FM, int FN, typename V16>
+// CG = MFMA column tiles staged at a time (FN by default; fewer where the staging area is small): the rows
+// written to memory are then CG * 64 bytes long.
+template <int FM, int FN, int CG = FN, typename V16>
 __device__ __forceinline__ void store_wave_tile(const V16 (&acc)[FN][FM], uint8_t *stage, int lane, int m_base, int n_base,
                                                 int M, int N, const float (&sx)[FM], const float4 (&sw)[FN][4],
                                                 void *__restrict__ Yv, int64_t ldy, int out_i32)
@@ -72,34 +74,38 @@ __device__ __forceinline__ void store_wave_tile(const V16 (&acc)[FN][FM], uint8_
                                       acc_i32(acc[i][j][4 * q + 3]));
                 }
     } else {
-        constexpr int RS = WN * 2 + 16;
-        constexpr int CPR = WN * 2 / 16;
+        constexpr int GW = CG * 32;                          // channels per staged group
+        constexpr int RS = GW * 2 + 16;
+        constexpr int CPR = GW * 2 / 16;
         constexpr int RPI = 64 / CPR;
         const int c = lane % CPR, r0 = lane / CPR;
 #pragma unroll
         for (int j = 0; j < FM; ++j) {
 #pragma unroll
-            for (int i = 0; i < FN; ++i)
+            for (int i0 = 0; i0 < FN; i0 += CG) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int nl = i * 32 + q * 8 + fg * 4;
-                    union { __half h[4]; uint2 u; } o;
-                    o.h[0] = __float2half_rn(acc_f32(acc[i][j][4 * q]) * sx[j] * sw[i][q].x);
-                    o.h[1] = __float2half_rn(acc_f32(acc[i][j][4 * q + 1]) * sx[j] * sw[i][q].y);
-                    o.h[2] = __float2half_rn(acc_f32(acc[i][j][4 * q + 2]) * sx[j] * sw[i][q].z);
-                    o.h[3] = __float2half_rn(acc_f32(acc[i][j][4 * q + 3]) * sx[j] * sw[i][q].w);
-                    *reinterpret_cast<uint2 *>(stage + fr * RS + nl * 2) = o.u;
+                for (int i = i0; i < i0 + CG && i < FN; ++i)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int nl = (i - i0) * 32 + q * 8 + fg * 4;
+                        union { __half h[4]; uint2 u; } o;
+                        o.h[0] = __float2half_rn(acc_f32(acc[i][j][4 * q]) * sx[j] * sw[i][q].x);
+                        o.h[1] = __float2half_rn(acc_f32(acc[i][j][4 * q + 1]) * sx[j] * sw[i][q].y);
+                        o.h[2] = __float2half_rn(acc_f32(acc[i][j][4 * q + 2]) * sx[j] * sw[i][q].z);
+                        o.h[3] = __float2half_rn(acc_f32(acc[i][j][4 * q + 3]) * sx[j] * sw[i][q].w);
+                        *reinterpret_cast<uint2 *>(stage + fr * RS + nl * 2) = o.u;
+                    }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+#pragma unroll
+                for (int r = r0; r < 32; r += RPI) {
+                    const int m = m_base + j * 32 + r, nloc = i0 * 32 + c * 8, n = n_base + nloc;
+                    const u32x4 v = *reinterpret_cast<const u32x4 *>(stage + r * RS + c * 16);
+                    // streamed once, never read back by this kernel: keep it from displacing operand panels in L2
+                    if (lane < RPI * CPR && nloc < WN && m < M && n < N)
+                        __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(static_cast<__half *>(Yv) + (int64_t)m * ldy + n));
                 }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-#pragma unroll
-            for (int r = r0; r < 32; r += RPI) {
-                const int m = m_base + j * 32 + r, n = n_base + c * 8;
-                const u32x4 v = *reinterpret_cast<const u32x4 *>(stage + r * RS + c * 16);
-                // streamed once, never read back by this kernel: keep it from displacing operand panels in L2
-                if (lane < RPI * CPR && m < M && n < N)
-                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(static_cast<__half *>(Yv) + (int64_t)m * ldy + n));
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         }
     }
 }

@@ -60,11 +60,14 @@ __device__ __forceinline__ void dma4(const void *base, uint32_t lane_off, uint32
                  : "memory", "m0");
 }
 
-template <int BM, int BN, int WGM, int WGN, int SLOTS, int WG_PER_CU>
-__global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN * WG_PER_CU / 4) void gemm_f6_kernel(
+// The work of one workgroup: tiles v0, v0 + vstep, ... (< total) of the tile grid tiles_m x tiles_n that starts
+// at output channel n_off.  CG = MFMA column tiles staged at a time by the epilogue.
+template <int BM, int BN, int WGM, int WGN, int SLOTS, int CG>
+__device__ __forceinline__ void f6_tiles(
     const uint8_t *__restrict__ X6, const float *__restrict__ xs, const uint8_t *__restrict__ W6,
-    const float *__restrict__ ws, int M, int N, int K, void *__restrict__ Yv, int64_t ldy, int out_i32,
-    int tiles_m, int tiles_n, int xcd_m)
+    const float *__restrict__ ws, const int M, const int N, const int K, void *__restrict__ Yv, const int64_t ldy,
+    const int out_i32, const int tiles_m, const int tiles_n, const int xcd_m, const int n_off, const int v0,
+    const int vstep, const int total)
 {
     constexpr int NWAVE = WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN;      // wave tile
@@ -86,7 +89,6 @@ __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN * WG_PER_CU / 4) void gem
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WGM, wn = wave / WGM;
-    const int total = tiles_m * tiles_n;
     const int nc = K >> 7;                           // 128-code chunks per row = stages
     const uint32_t cx_bytes = (uint32_t)((M + 7) >> 3) * BLK, cw_bytes = (uint32_t)((N + 7) >> 3) * BLK;   // one chunk of X / W
 
@@ -159,8 +161,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN * WG_PER_CU / 4) void gem
     // ---- one MFMA step (64 codes): the FM * FN MFMAs on `cur`, the reads of the next step's FM + FN fragments
     // into `nxt` and a share of the DMA of a later stage, cut into regions of [2 fragment reads, a slice of the
     // MFMAs, some DMA instructions] so that no memory instruction queue sees a burst.
-    static_assert((FM + FN) % 2 == 0, "fragments are read in pairs");
-    constexpr int NREG = (FM + FN) / 2;              // regions per step
+    constexpr int NREG = (FM + FN + 1) / 2;          // regions per step (fragments are read in pairs)
     constexpr int NM = FM * FN;                      // MFMAs per step
     constexpr int HALF = SLOTS == 2 ? RPW : (RPW + 1) / 2;      // DMA instructions issued in the step after the barrier
     auto step = [&](auto PART, const Frags &cur, Frags &nxt, uint32_t rbase, int t, int dstage, int dslot) {
@@ -172,7 +173,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN * WG_PER_CU / 4) void gem
             __builtin_amdgcn_sched_barrier(0);
 #ifndef F6_NO_READ
             read_q(nxt, 2 * r, rbase, t);
-            read_q(nxt, 2 * r + 1, rbase, t);
+            if (2 * r + 1 < FM + FN) read_q(nxt, 2 * r + 1, rbase, t);
 #endif
             const int mlo = r * NM / NREG, mhi = (r + 1) * NM / NREG;
 #pragma unroll
@@ -190,13 +191,14 @@ __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN * WG_PER_CU / 4) void gem
     constexpr std::integral_constant<int, 0> AFTER{};
     constexpr std::integral_constant<int, 1> BEFORE{};
 
-    // epilogue staging: one piece = 32 tokens x WN channels of fp16 per wave, in the last ring slot
-    constexpr int PIECE = 32 * (WN * 2 + 16);
+    // epilogue staging: one piece = 32 tokens x CG * 32 channels of fp16 per wave, in the last ring slot
+    constexpr int PIECE = 32 * (CG * 64 + 16);
     static_assert(NWAVE * PIECE <= STAGE_BYTES, "epilogue staging must fit one ring slot");
 
-    int v = blockIdx.x;
+    int v = v0;
     int m0, n0;
     tile_origin(v, tiles_m, tiles_n, xcd_m, BM, BN, m0, n0);
+    n0 += n_off;
     set_sources(m0, n0);
     // order of a wave's loads at the start of every tile: stage 0, scales, stages 1 .. SLOTS-2, first part of
     // stage SLOTS-1 (its second part is issued by the first step of the loop)
@@ -244,13 +246,14 @@ __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN * WG_PER_CU / 4) void gem
         }
 
         // ---- tile boundary
-        const int vn = v + (int)gridDim.x;
+        const int vn = v + vstep;
         const bool more = vn < total;
         wait_vmcnt<0>();                             // no LDS-DMA write is in flight any more ...
         barrier_nofence();                           // ... and all waves are done reading fragments
         int m1 = 0, n1 = 0;
         if (more) {                                  // the next tile's first stages fly during the epilogue
             tile_origin(vn, tiles_m, tiles_n, xcd_m, BM, BN, m1, n1);
+            n1 += n_off;
             set_sources(m1, n1);
             issue(0, 0);
             issue_scales(m1, n1, area ^ 1);
@@ -268,7 +271,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN * WG_PER_CU / 4) void gem
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
                     sw[i][q] = *reinterpret_cast<const float4 *>(sc + BM + wn * WN + i * 32 + q * 8 + fg * 4);
-            store_wave_tile<FM, FN>(acc, smem + (SLOTS - 1) * STAGE_BYTES + wave * PIECE, lane, m0 + wm * WM, n0 + wn * WN,
+            store_wave_tile<FM, FN, CG>(acc, smem + (SLOTS - 1) * STAGE_BYTES + wave * PIECE, lane, m0 + wm * WM, n0 + wn * WN,
                                     M, N, sx, sw, Yv, ldy, out_i32);
         }
         if (!more) break;
@@ -284,12 +287,24 @@ __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN * WG_PER_CU / 4) void gem
     wait_vmcnt<0>();
 }
 
+constexpr int f6_lds_bytes(int BM, int BN, int SLOTS) { return SLOTS * (BM + BN) / 8 * BLK + 2 * (BM + BN) * 4 + 256; }   // ring, two scale areas, slack
+
+template <int BM, int BN, int WGM, int WGN, int SLOTS, int WG_PER_CU>
+__global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN * WG_PER_CU / 4) void gemm_f6_kernel(
+    const uint8_t *__restrict__ X6, const float *__restrict__ xs, const uint8_t *__restrict__ W6,
+    const float *__restrict__ ws, int M, int N, int K, void *__restrict__ Yv, int64_t ldy, int out_i32,
+    int tiles_m, int tiles_n, int xcd_m)
+{
+    f6_tiles<BM, BN, WGM, WGN, SLOTS, BN / WGN / 32>(X6, xs, W6, ws, M, N, K, Yv, ldy, out_i32, tiles_m, tiles_n, xcd_m, 0,
+                                                     (int)blockIdx.x, (int)gridDim.x, tiles_m * tiles_n);
+}
+
 template <int BM, int BN, int WGM, int WGN, int SLOTS, int WG_PER_CU>
 hipError_t launch_f6(const uint8_t *X6, const float *xs, const uint8_t *W6, const float *ws, int64_t M, int64_t N,
                      int64_t K, void *Y, int64_t ldy, int out_i32, hipStream_t st)
 {
     auto kern = gemm_f6_kernel<BM, BN, WGM, WGN, SLOTS, WG_PER_CU>;
-    constexpr int lds = SLOTS * (BM + BN) / 8 * BLK + 2 * (BM + BN) * 4 + 256;   // ring, two scale areas, slack
+    constexpr int lds = f6_lds_bytes(BM, BN, SLOTS);
     static_assert(lds * WG_PER_CU <= 160 * 1024, "LDS");
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -382,11 +397,16 @@ hipError_t launch_gemm_f6(const uint8_t *X6, const float *xs, const uint8_t *W6,
     // 256 x 256 tiles (eight waves of 128 x 64) run ~15 % faster per output than 256 x 128 tiles (eight waves of
     // 64 x 64: more LDS traffic per MFMA), so the small tile is taken only where it saves whole rounds:
     // measured at M = 2048, K = 4096: N = 14336 63.8 us against 77.6 us; N = 4096 (128 big tiles on 256 CUs)
-    // 28.9 us against 24.3 us.  Four-wave workgroups (one wave per SIMD) lost everywhere.
+    // 28.9 us against 24.3 us.  Four-wave workgroups (one wave per SIMD) lost everywhere.  N = 14336 at M = 2048 is
+    // 448 big tiles = 1.75 rounds; a launch mixing one round of 256-wide with one round of 192-wide tiles (every CU
+    // then works 1.75 tile times) was built and measured: 63.3 us against 61.9 us -- the second, three-quarters
+    // filled round of the plain schedule already runs faster (fewer CUs draw power and share L2), so it was dropped.
     const int64_t cus = compute_units();
-    auto rounds = [&](int64_t bm, int64_t bn) { return (((M + bm - 1) / bm) * ((N + bn - 1) / bn) + cus - 1) / cus; };
-    if (rounds(256, 256) * 256 * 256 * 85 <= rounds(256, 128) * 256 * 128 * 100)
-        return launch_f6<256, 256, 2, 4, 3, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
+    const int64_t tm = (M + 255) / 256;
+    auto rounds = [&](int64_t tiles) { return (tiles + cus - 1) / cus; };
+    const int64_t cost_big = rounds(tm * ((N + 255) / 256)) * 256 * 256 * 85;
+    const int64_t cost_small = rounds(tm * ((N + 127) / 128)) * 256 * 128 * 100;
+    if (cost_big <= cost_small) return launch_f6<256, 256, 2, 4, 3, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
     return launch_f6<256, 128, 4, 2, 4, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
 }
 
