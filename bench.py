@@ -269,6 +269,12 @@ def main():
         b = M * K3 * 4.5 + M * 4
         extra["swiglu_fwht_quant_K14336"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
                                              "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+        X63 = torch.zeros(sr.sr_f6_tiles_bytes(M, K3), dtype=torch.uint8, device=dev)
+        t = graph_time(lambda i: sr.sr_swiglu_fwht_quant_act_f6(GU[i % 3][0], GU[i % 3][1], None, CLIP, X63, xs3), 24)
+        b = M * K3 * 4.75 + M * 4
+        extra["swiglu_fwht_quant_f6_K14336"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
+                                                "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+        del X63
         del GU
         # head-wise Hadamard (32 heads of 128, across heads) + quantiser on the benchmark activations
         t = graph_time(lambda i: sr.sr_fwht_quant_act_heads(Xs[i % SETS], 32, True, inv_s, CLIP, Xq, xs), 64)

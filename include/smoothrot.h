@@ -274,6 +274,12 @@ SR_API int sr_fwht_quant_act_f6(const void *X_f16, int64_t M, int64_t K, int64_t
                          const float *inv_s, float clip,
                          uint8_t *X6, float *x_scale, void *stream);
 
+/* sr_swiglu_fwht_quant_act writing f6 tiles (the down-projection input of a gated FFN on the fast path);
+ * arguments as there, X6 / K as in sr_fwht_quant_act_f6. */
+SR_API int sr_swiglu_fwht_quant_act_f6(const void *G_f16, const void *U_f16, int64_t M, int64_t K,
+                                int64_t ldg, int64_t ldu, const float *inv_s, float clip,
+                                uint8_t *X6, float *x_scale, void *stream);
+
 /*
  * sr_w4a4_gemm on f6-tile operands: same sums (exact), same epilogue, same outputs.
  *   X6 = tiles of the activation codes [M, K], W6 = tiles of the weight codes [N, K].

@@ -39,6 +39,7 @@ _SIGNATURES = {
     "sr_f6_tiles_bytes": (_sz, [_i64, _i64]),
     "sr_pack_f6_tiles": (_int, [_vp, _i64, _i64, _vp, _vp]),
     "sr_fwht_quant_act_f6": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _vp]),
+    "sr_swiglu_fwht_quant_act_f6": (_int, [_vp, _vp, _i64, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _vp]),
     "sr_w4a4_gemm_f6": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _int, _vp, _sz, _vp]),
     "sr_w4a4_linear_decode": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _vp]),
 }
@@ -282,4 +283,20 @@ def sr_fwht_quant_act_f6(X, inv_s, clip: float = 0.9, X6=None, x_scale=None):
     ldx = X.stride(0) if M > 1 else K
     _check(raw().sr_fwht_quant_act_f6(_ptr(X), M, K, ldx, _ptr(inv_s), clip, _ptr(X6), _ptr(x_scale), _stream()),
            "sr_fwht_quant_act_f6")
+    return X6, x_scale
+
+
+def sr_swiglu_fwht_quant_act_f6(G, U, inv_s, clip: float = 0.9, X6=None, x_scale=None):
+    """G, U fp16 [M, K] -> f6 tiles and scales of silu(G) * U (smoothed, rotated, quantised)."""
+    _dev(G, torch.float16, "G"); _dev(U, torch.float16, "U")
+    M, K = U.shape
+    if tuple(G.shape) != (M, K):
+        raise ValueError("G and U must have the same shape")
+    if X6 is None:
+        X6 = torch.zeros(max(sr_f6_tiles_bytes(M, K), 16), dtype=torch.uint8, device=U.device)
+    x_scale = torch.empty(M, dtype=torch.float32, device=U.device) if x_scale is None else x_scale
+    ldg = G.stride(0) if M > 1 else K
+    ldu = U.stride(0) if M > 1 else K
+    _check(raw().sr_swiglu_fwht_quant_act_f6(_ptr(G), _ptr(U), M, K, ldg, ldu, _ptr(inv_s), clip, _ptr(X6),
+                                             _ptr(x_scale), _stream()), "sr_swiglu_fwht_quant_act_f6")
     return X6, x_scale

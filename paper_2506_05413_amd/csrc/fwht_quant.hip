@@ -75,8 +75,8 @@ __global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict
 //              (paper, "Quantization" settings for the weights), first minimum in grid order
 // Kept apart from the plain kernel so that the hot path carries none of these branches.
 // ------------------------------------------------------------------------------------------
-template <int K, int NT>
-__global__ __launch_bounds__(NT) void fwht_quant_ex_kernel(const __half *__restrict__ X, int64_t ldx,
+template <int K, int NT, bool F6>
+__global__ __launch_bounds__(NT) void fwht_quant_ex_kernel(const __half *__restrict__ X, int64_t ldx, int64_t rows,
                                                            const float *__restrict__ pre, float clip,
                                                            float post_scale, uint8_t *__restrict__ Q,
                                                            float *__restrict__ scale_out, const RowExtras ex)
@@ -91,7 +91,12 @@ __global__ __launch_bounds__(NT) void fwht_quant_ex_kernel(const __half *__restr
     __shared__ double err_w[kMaxClipGrid][NW];
 
     const int t = threadIdx.x;
-    const int64_t m = blockIdx.x;
+    int64_t m = blockIdx.x;
+    if constexpr (F6) {                                  // rows of a tile block from one XCD (see fwht_quant_kernel)
+        const int64_t w = blockIdx.x, x8 = w & 7, a = w >> 3;
+        m = 64 * (a >> 3) + 8 * x8 + (a & 7);
+        if (m >= rows) return;
+    }
     const __half *x = X + m * ldx;
     const __half *gt = ex.gate ? ex.gate + m * ex.ldg : nullptr;
     const uint32_t mask = KRON ? 0xFFFFFFFFu : ex.had_mask;
@@ -213,7 +218,13 @@ __global__ __launch_bounds__(NT) void fwht_quant_ex_kernel(const __half *__restr
         const float4 a = *reinterpret_cast<const float4 *>(src);
         const float4 b = *reinterpret_cast<const float4 *>(src + 4);
         const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        q[c] = quant_pack8(v, inv_delta);
+        if constexpr (F6) {
+            uint32_t lo, hi;
+            quant_f6_8(v, inv_delta, lo, hi);
+            store_f6_piece(lo, hi, t, Q, (rows + 7) >> 3, m, c >> 2);
+        } else {
+            q[c] = quant_pack8(v, inv_delta);
+        }
     }
 }
 
@@ -327,21 +338,22 @@ hipError_t launch_one(const void *X, int64_t rows, int64_t ldx, const float *pre
     return hipGetLastError();
 }
 
-template <int K>
+template <int K, bool F6 = false>
 hipError_t launch_one_ex(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip,
                          float post_scale, uint8_t *Q, float *scale_out, const RowExtras &ex, hipStream_t st)
 {
     constexpr int groups = K / 16;
     constexpr int NT = groups >= 256 ? 256 : (groups >= 128 ? 128 : 64);
     constexpr size_t lds = sizeof(float) * padded_len(K);
-    auto kern = fwht_quant_ex_kernel<K, NT>;
+    auto kern = fwht_quant_ex_kernel<K, NT, F6>;
     if (lds > 40 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)rows), dim3(NT), lds, st,
-                       static_cast<const __half *>(X), ldx, pre, clip, post_scale, Q, scale_out, ex);
+    const unsigned grid = F6 ? (unsigned)((rows + 63) / 64 * 64) : (unsigned)rows;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st,
+                       static_cast<const __half *>(X), ldx, rows, pre, clip, post_scale, Q, scale_out, ex);
     return hipGetLastError();
 }
 
@@ -398,8 +410,18 @@ hipError_t launch_fwht_quant(const void *X, int64_t rows, int64_t K, int64_t ldx
 
 hipError_t launch_fwht_quant_ex(const void *X, int64_t rows, int64_t K, int64_t ldx, const float *pre,
                                 float clip, float post_scale, uint8_t *Q, float *scale_out,
-                                const RowExtras &ex, hipStream_t st)
+                                const RowExtras &ex, hipStream_t st, bool f6)
 {
+    if (f6) {
+#define SR_CASE(KK) case KK: return launch_one_ex<KK, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, ex, st);
+        switch (K) {                                    // K % 128 == 0
+            SR_CASE(128) SR_CASE(256) SR_CASE(512) SR_CASE(1024) SR_CASE(2048)
+            SR_CASE(4096) SR_CASE(8192) SR_CASE(16384) SR_CASE(32768)
+            SR_CASE(896) SR_CASE(1792) SR_CASE(3584) SR_CASE(7168) SR_CASE(14336) SR_CASE(28672)
+            default: return hipErrorInvalidValue;
+        }
+#undef SR_CASE
+    }
 #define SR_CASE(KK) case KK: return launch_one_ex<KK>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, ex, st);
     switch (K) {
         SR_CASE(64) SR_CASE(128) SR_CASE(256) SR_CASE(512) SR_CASE(1024) SR_CASE(2048)

@@ -188,6 +188,24 @@ int sr_swiglu_fwht_quant_act(const void *G_f16, const void *U_f16, int64_t M, in
                                         static_cast<hipStream_t>(stream)));
 }
 
+int sr_swiglu_fwht_quant_act_f6(const void *G_f16, const void *U_f16, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
+                                const float *inv_s, float clip, uint8_t *X6, float *x_scale, void *stream)
+{
+    if (M < 0 || K <= 0 || ldg < K || ldu < K) return SR_ERR_SHAPE;
+    if (!sr::hadamard_supported(K) || K % 128 != 0) return SR_ERR_UNSUPPORTED_K;
+    if (!(clip > 0.f && clip <= 1.f)) return SR_ERR_ARG;
+    if (M == 0) return SR_OK;
+    if (!G_f16 || !U_f16 || !X6 || !x_scale) return SR_ERR_NULL;
+    if (ldg % 8 != 0 || ldu % 8 != 0 || !aligned16(G_f16) || !aligned16(U_f16) || !aligned16(X6) ||
+        (inv_s && !aligned16(inv_s)))
+        return SR_ERR_ALIGN;
+    sr::RowExtras ex;
+    ex.gate = static_cast<const __half *>(G_f16);
+    ex.ldg = ldg;
+    return dev(sr::launch_fwht_quant_ex(U_f16, M, K, ldu, inv_s, clip, 1.0f, X6, x_scale, ex,
+                                        static_cast<hipStream_t>(stream), true));
+}
+
 int sr_fwht_quant_act_heads(const void *X_f16, int64_t M, int64_t K, int64_t ldx, int64_t n_heads, int across,
                             const float *inv_s, float clip, uint8_t *Xq, float *x_scale, void *stream)
 {

@@ -41,7 +41,7 @@ struct RowExtras {
 
 hipError_t launch_fwht_quant_ex(const void *X_f16, int64_t rows, int64_t K, int64_t ldx,
                                 const float *pre, float clip, float post_scale,
-                                uint8_t *Q, float *scale_out, const RowExtras &ex, hipStream_t st);
+                                uint8_t *Q, float *scale_out, const RowExtras &ex, hipStream_t st, bool f6 = false);
 
 hipError_t launch_calib_absmax(const void *X_f16, int64_t T, int64_t K, int64_t ldx,
                                float *absmax_io, hipStream_t st);

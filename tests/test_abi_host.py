@@ -23,7 +23,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = declared_symbols()
-    assert len(names) == 17 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
+    assert len(names) == 18 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
     lib = ctypes.CDLL(sr.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -243,6 +243,15 @@ def test_f6_calls_reject_bad_arguments():
     assert quant(M=0, X=None, X6=None, xs=None) == sr.SR_OK
     assert quant(X6=None) == sr.SR_ERR_NULL
     assert quant(X6=A + 4) == sr.SR_ERR_ALIGN
+
+    def swiglu(G=A, U=A, M=4, K=14336, ldg=14336, ldu=14336, inv=None, clip=0.9, X6=A, xs=A):
+        return raw.sr_swiglu_fwht_quant_act_f6(G, U, M, K, ldg, ldu, inv, clip, X6, xs, None)
+    assert swiglu(ldg=4096) == sr.SR_ERR_SHAPE
+    assert swiglu(K=448, ldg=448, ldu=448) == sr.SR_ERR_UNSUPPORTED_K
+    assert swiglu(clip=1.5) == sr.SR_ERR_ARG
+    assert swiglu(G=None) == sr.SR_ERR_NULL
+    assert swiglu(X6=A + 2) == sr.SR_ERR_ALIGN
+    assert swiglu(M=0) == sr.SR_OK
 
     def gemm(X6=A, xs=A, W6=A, ws=A, M=32, N=64, K=512, Y=A, ldy=64, dt=sr.SR_F16):
         return raw.sr_w4a4_gemm_f6(X6, xs, W6, ws, M, N, K, Y, ldy, dt, None, 0, None)

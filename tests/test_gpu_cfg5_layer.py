@@ -70,4 +70,15 @@ def test_layer_group(gpu, group):
         want = o.dequant_out(acc[ROWS], xs.cpu().numpy()[ROWS], ws.cpu().numpy())
         check_output(Y[ROWS], want, name + " Y")
         assert np.isfinite(Y).all()
-        del acc, Y, cx_all, cw_all
+        # the same linear through the FP6-pipe path (the one the benchmark times): identical codes, hence
+        # identical accumulators everywhere, and the same dequantised output
+        W6 = gpu.sr_pack_f6_tiles(Wq)
+        X6, xs6 = gpu.sr_fwht_quant_act_f6(Xd, inv_s, 0.9)
+        acc6 = gpu.sr_w4a4_gemm_f6(X6, None, W6, None, M, N, K, gpu.SR_I32)
+        Y6 = gpu.sr_w4a4_gemm_f6(X6, xs6, W6, ws, M, N, K, gpu.SR_F16)
+        torch.cuda.synchronize()
+        assert np.array_equal(xs6.cpu().numpy(), xs.cpu().numpy())
+        assert np.array_equal(o.f6_codes(o.f6_tiles_unpack(X6.cpu().numpy(), M, K)[ROWS]), cx_all[ROWS])
+        assert np.array_equal(acc6.cpu().numpy().astype(np.int64), acc)
+        check_output(Y6.cpu().numpy()[ROWS], want, name + " Y (f6 path)")
+        del acc, Y, cx_all, cw_all, acc6, Y6, X6, W6

@@ -161,6 +161,23 @@ def test_quantiser_tiles_agree_with_the_nibble_path(gpu):
         assert np.array_equal(xs, xs4.cpu().numpy())
 
 
+@pytest.mark.parametrize("M,K", [(5, 896), (24, 14336), (9, 4096)])
+def test_gated_prologue_tiles(gpu, M, K):
+    """silu(gate) * up fused in front of the rotation, tile output: codes under the boundary rule against the
+    oracle, and identical to the nibble output of the same kernel."""
+    G, U = wl.gate_up(3, M, K, 2, 300.0)
+    inv_s = np.random.default_rng(K + M).uniform(0.5, 2.0, K).astype(np.float32)
+    Gd, Ud, inv_d = torch.from_numpy(G).cuda(), torch.from_numpy(U).cuda(), torch.from_numpy(inv_s).cuda()
+    X6, xs = gpu.sr_swiglu_fwht_quant_act_f6(Gd, Ud, inv_d, 0.9)
+    Xq, xs4 = gpu.sr_swiglu_fwht_quant_act(Gd, Ud, inv_d, 0.9)
+    torch.cuda.synchronize()
+    codes = o.f6_codes(o.f6_tiles_unpack(X6.cpu().numpy(), M, K))
+    ref = o.fwht_quant_swiglu(G, U, inv_s, 0.9)
+    check_scales(xs.cpu().numpy(), ref["x_scale"])
+    check_codes(codes, ref["codes"], ref["t"])
+    assert np.array_equal(codes, o.unpack_int4(Xq.cpu().numpy())) and np.array_equal(xs.cpu().numpy(), xs4.cpu().numpy())
+
+
 def test_cfg2_layer_through_the_f6_path(gpu):
     """Config 2 (M = 2048, K = 4096 -> N = 4096) end to end through the tile path, stage by stage: each
     stage's oracle runs on the GPU's own (already checked) output of the stage before."""
