@@ -141,10 +141,12 @@ __device__ __forceinline__ void f6_tiles(
 
     struct Frags { v8i x[FM]; v8i w[FN]; };
     uint2 tail1[FM + FN];                            // tails of step 1, read together with those of step 0
-    // fragment q of a stage (X fragments first), step t: step 0 also fetches the 16 bytes holding both tails
+    // fragment q of a stage, step t: step 0 also fetches the 16 bytes holding both tails.  The W fragments come
+    // first and the MFMAs below walk the X fragments in the outer loop, so that the fragments read last in a step
+    // are the ones the next step needs last (with X first, the first MFMA of a step waited for the last read).
     auto read_q = [&](Frags &f, int q, uint32_t sbase, int t) {
-        const uint32_t base = sbase + (q < FM ? xfrag + q * 4 * BLK : wfrag + (q - FM) * 4 * BLK) + a16;
-        v8i &d = q < FM ? f.x[q < FM ? q : 0] : f.w[q < FM ? 0 : q - FM];
+        const uint32_t base = sbase + (q < FN ? wfrag + q * 4 * BLK : xfrag + (q - FN) * 4 * BLK) + a16;
+        v8i &d = q < FN ? f.w[q < FN ? q : 0] : f.x[q < FN ? 0 : q - FN];
         const uint4 lo = *reinterpret_cast<const uint4 *>(smem + base + t * 256);
         d[0] = (int)lo.x; d[1] = (int)lo.y; d[2] = (int)lo.z; d[3] = (int)lo.w;
         if (t == 0) {
@@ -163,6 +165,8 @@ __device__ __forceinline__ void f6_tiles(
     // MFMAs, some DMA instructions] so that no memory instruction queue sees a burst.
     constexpr int NREG = (FM + FN + 1) / 2;          // regions per step (fragments are read in pairs)
     constexpr int NM = FM * FN;                      // MFMAs per step
+    // (Tried: the two waves of a SIMD issuing their DMA in different steps, so that they are not held up at the
+    // same moments -- 1 - 2 % slower.)
     constexpr int HALF = SLOTS == 2 ? RPW : (RPW + 1) / 2;      // DMA instructions issued in the step after the barrier
     auto step = [&](auto PART, const Frags &cur, Frags &nxt, uint32_t rbase, int t, int dstage, int dslot) {
         constexpr int part = decltype(PART)::value;             // 0: step after the barrier, 1: step before it
@@ -178,7 +182,7 @@ __device__ __forceinline__ void f6_tiles(
             const int mlo = r * NM / NREG, mhi = (r + 1) * NM / NREG;
 #pragma unroll
             for (int m = mlo; m < mhi; ++m) {
-                const int i = m / FM, j = m % FM;
+                const int j = m / FN, i = m % FN;
                 acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(cur.w[i], cur.x[j], acc[i][j], 2, 2, 0, 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
