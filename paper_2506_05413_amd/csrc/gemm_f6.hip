@@ -163,7 +163,10 @@ __device__ __forceinline__ void f6_tiles(
     // ---- one MFMA step (64 codes): the FM * FN MFMAs on `cur`, the reads of the next step's FM + FN fragments
     // into `nxt` and a share of the DMA of a later stage, cut into regions of [2 fragment reads, a slice of the
     // MFMAs, some DMA instructions] so that no memory instruction queue sees a burst.
-    constexpr int NREG = (FM + FN + 1) / 2;          // regions per step (fragments are read in pairs)
+    // regions per step: fragments read in pairs -- measured against 1, 2 and FM + FN regions (M = 2048, N = 14336,
+    // K = 4096: 68.9, 63.1, 65.7 us against 62.0 us)
+    constexpr int NREG = (FM + FN + 1) / 2;
+    constexpr int FPRG = (FM + FN + NREG - 1) / NREG;   // fragments read per region
     constexpr int NM = FM * FN;                      // MFMAs per step
     // (Tried: the two waves of a SIMD issuing their DMA in different steps, so that they are not held up at the
     // same moments -- 1 - 2 % slower.)
@@ -176,8 +179,8 @@ __device__ __forceinline__ void f6_tiles(
         for (int r = 0; r < NREG; ++r) {
             __builtin_amdgcn_sched_barrier(0);
 #ifndef F6_NO_READ
-            read_q(nxt, 2 * r, rbase, t);
-            if (2 * r + 1 < FM + FN) read_q(nxt, 2 * r + 1, rbase, t);
+#pragma unroll
+            for (int q = r * FPRG; q < (r + 1) * FPRG && q < FM + FN; ++q) read_q(nxt, q, rbase, t);
 #endif
             const int mlo = r * NM / NREG, mhi = (r + 1) * NM / NREG;
 #pragma unroll
