@@ -29,11 +29,14 @@
 //       256 t + 128 (g ^ (R & 1)) + 16 r
 //   and its last 8 bytes at
 //       512 + 128 (g ^ (R & 1)) + 16 r + 8 t
-//   i.e. the tails of the two steps share one 16-byte slot, so that a stage of a fragment is three
-//   ds_read_b128 (LDS serves those at twice the bytes per clock of narrower reads -- measured -- and
-//   LDS time, not MFMA time, bounded the first version that read the tails 8 bytes at a time), each
-//   touching every LDS bank once over a 32-row fragment (four blocks).  (The 12-byte form of the LDS-DMA load leaves a 4-byte hole after every lane's data in
-//   LDS -- measured -- so stages are copied with the 16-byte form, 1 KB per instruction.)
+//   i.e. the tails of the two steps share one 16-byte slot of the same (g, r) pattern as the first parts; a
+//   32-row fragment (four blocks) then touches every LDS bank once per read.  The compiler reads each step's
+//   half of the slot with 8-byte reads paired over two fragments (ds_read2st64_b64).  Measured in one process
+//   against the first layout (tails in separate, XOR-swizzled 8-byte slots): M = 2048, N = 14336, K = 4096
+//   69.8 -> 65.8 us, 4096 x 4096 x 14336 116.7 -> 108.1 us; forcing whole 16-byte tail reads (ds_read_b128,
+//   the other half kept in registers for the next step) was 1 - 5 % slower than leaving the split to the compiler.
+//   (The 12-byte form of the LDS-DMA load leaves a 4-byte hole after every lane's data in LDS -- measured -- so
+//   stages are copied with the 16-byte form, 1 KB per instruction.)
 //
 // Kernel structure: persistent workgroups, tile BM x BN, ring of SLOTS stages of 128 codes, one
 // barrier per stage, two MFMA steps (64 codes) per stage with the fragment reads of the next

@@ -61,6 +61,20 @@ def test_int32_accumulators_bit_exact(gpu, M, N, K):
     assert got.dtype == np.int32 and np.array_equal(got.astype(np.int64), want)
 
 
+def test_seeded_random_shapes(gpu):
+    """Twenty seeded shapes (M up to 700, N a multiple of 16 up to 1200, K a multiple of 128 up to 1536) through
+    whatever configuration the launch heuristic picks: accumulators bit-exact, nothing written past N."""
+    rng = np.random.default_rng(20250605)
+    for case in range(20):
+        M = int(rng.integers(1, 701))
+        N = 16 * int(rng.integers(1, 76))
+        K = 128 * int(rng.integers(1, 13))
+        print("case", case, M, N, K, flush=True)
+        cx, cw = wl.random_codes(1000 + case, M, K), wl.random_codes(2000 + case, N, K)
+        got = gemm_f6(gpu, cx, cw, ldy=N + 8)
+        assert np.array_equal(got.astype(np.int64), o.gemm_i32_c(cx, cw)), (M, N, K)
+
+
 @pytest.mark.parametrize("tile", ["61", "63", "64", "65", "66"])
 def test_every_tile_configuration(gpu, tile, monkeypatch):
     """The launch heuristic picks one configuration per shape; each of them is checked on a shape with
