@@ -181,7 +181,7 @@ __device__ __forceinline__ void f6_tiles(
 #pragma unroll
         for (int r = 0; r < NREG; ++r) {
             __builtin_amdgcn_sched_barrier(0);
-#ifndef F6_NO_READ
+#ifndef F6_NO_READ                                       // (timing aid: the fragment reads compiled out -- results are then wrong)
 #pragma unroll
             for (int q = r * FPRG; q < (r + 1) * FPRG && q < FM + FN; ++q) read_q(nxt, q, rbase, t);
 #endif
@@ -192,7 +192,7 @@ __device__ __forceinline__ void f6_tiles(
                 acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(cur.w[i], cur.x[j], acc[i][j], 2, 2, 0, 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
-#ifndef F6_NO_DMA
+#ifndef F6_NO_DMA                                        // (timing aid: no loads in the loop -- results are then wrong)
 #pragma unroll
             for (int idx = dlo + r * DPR; idx < dlo + (r + 1) * DPR && idx < dhi; ++idx) dma_one(idx, dstage, dslot);
 #endif
@@ -247,9 +247,7 @@ __device__ __forceinline__ void f6_tiles(
             // stage s+1 must have landed (the SLOTS-2 younger stages may stay in flight), and every wave's
             // reads of stage s must have returned: its slot takes stage s+SLOTS from here on
             asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((SLOTS - 2) * RPW) : "memory");
-#ifndef F6_NO_BARRIER
             barrier_nofence();
-#endif
             // step 1 of stage s; reads step 0 of stage s+1; first part of the DMA of stage s+SLOTS
             step(AFTER, fb, fa, (uint32_t)nslot * STAGE_BYTES, 0, sb, slot);
             slot = nslot;
