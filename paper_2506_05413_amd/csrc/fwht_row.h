@@ -215,16 +215,23 @@ __device__ __forceinline__ uint32_t quant_pack8(const float (&y)[8], float inv_d
 // like 0.  Eight consecutive values give 48 bits: lo = bits 0..31, hi = bits 32..47.
 __device__ __forceinline__ void quant_f6_8(const float (&y)[8], float inv_delta, uint32_t &lo, uint32_t &hi)
 {
+    // t = magic + magnitude + 32 sign per value; the fields are packed by shift-adds modulo 2^32 with the magic
+    // constant still inside and its packed image subtracted once (its two low bits are zero, so the shift right
+    // of the field that straddles the two words commutes with the subtraction)
     const float magic = __uint_as_float(kMagicBits);
-    uint32_t f[8];
+    uint32_t t[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const uint32_t sign = __float_as_uint(y[e]) >> 31;
         const uint32_t bits = __float_as_uint(fmaf(fabsf(y[e]), inv_delta, magic));
-        f[e] = (min(bits, kMagicBits + 7u + sign) - kMagicBits) | (sign << 5);
+        t[e] = min(bits, kMagicBits + 7u + sign) + (sign << 5);
     }
-    lo = f[0] | (f[1] << 6) | (f[2] << 12) | (f[3] << 18) | (f[4] << 24) | (f[5] << 30);
-    hi = (f[5] >> 2) | (f[6] << 4) | (f[7] << 10);
+    constexpr uint32_t c_lo = kMagicBits + (kMagicBits << 6) + (kMagicBits << 12) + (kMagicBits << 18) + (kMagicBits << 24) +
+                              (kMagicBits << 30);
+    constexpr uint32_t c_hi = (kMagicBits >> 2) + (kMagicBits << 4) + (kMagicBits << 10);
+    static_assert((kMagicBits & 3u) == 0, "the straddling field relies on it");
+    lo = t[0] + (t[1] << 6) + (t[2] << 12) + (t[3] << 18) + (t[4] << 24) + (t[5] << 30) - c_lo;
+    hi = (t[5] >> 2) + (t[6] << 4) + (t[7] << 10) - c_hi;
 }
 
 // Four neighbouring lanes (a quad, lane & 3 = 0..3) hold the 48-bit strings of 32 consecutive values = one
