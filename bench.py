@@ -255,12 +255,13 @@ def main():
                                          "frac_fp6_mfma_peak": round(2.0 * M * N3 * K3 / t / 1e12 / PEAK_FP6_TOPS, 4)}
         del X63, W63
         copies = [Wq3.clone() for _ in range(20)]
-        xq_d, xs_d = sr.sr_fwht_quant_act(X3[0][:1].contiguous(), None, CLIP)
-        Yd = torch.empty((1, N3), dtype=torch.float16, device=dev)
-        t = graph_time(lambda i: sr.sr_w4a4_gemm(xq_d, xs_d, copies[i % 20], ws3, sr.SR_F16, Yd), 100)
-        b = N3 * K3 / 2 + K3 / 2 + 2 * N3
-        extra["decode_M1_14336x4096"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
-                                         "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+        for Md in (1, 4, 16):
+            xq_d, xs_d = sr.sr_fwht_quant_act(X3[0][:Md].contiguous(), None, CLIP)
+            Yd = torch.empty((Md, N3), dtype=torch.float16, device=dev)
+            t = graph_time(lambda i: sr.sr_w4a4_gemm(xq_d, xs_d, copies[i % 20], ws3, sr.SR_F16, Yd), 100)
+            b = N3 * K3 / 2 + Md * K3 / 2 + 2 * Md * N3
+            extra["decode_M%d_14336x4096" % Md] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
+                                                    "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
         del copies, X3
         # ---- rows around the core path -----------------------------------------------------------
         # gated-FFN prologue fused into the K = 14336 rotation + quantiser (two fp16 inputs per value)

@@ -106,6 +106,57 @@ def test_cfg4_decode_shapes(gpu, M, K, N):
     assert np.array_equal(gpu_gemm(gpu, cx, cw).astype(np.int64), o.gemm_i32_c(cx, cw))
 
 
+# The three decode kernels (forced through the library's tuning switch, so that each one is checked on
+# every shape, not only where the dispatcher would pick it): 1 = dot product (at most 2 tokens), 2 = MFMA with a
+# workgroup per 16 channels, 3 = streaming MFMA.  Shapes: K with a half-empty last 256-code slab (448, 576,
+# 4160), a single 16-channel group, output lines that are not whole (N % 64 != 0), more channels than one pass
+# of the streaming kernel takes (20000; 8208 at K = 4160), rows longer than one pass over K (14336, 16000).
+DECODE_SHAPES = [(1, 16, 64), (2, 48, 448), (3, 16, 64), (5, 80, 4096), (8, 4096, 4096), (7, 16, 14336), (9, 32, 576),
+                 (16, 512, 512), (16, 256, 448), (12, 48, 192), (16, 12816, 576), (6, 12816, 256), (16, 20000, 128),
+                 (5, 8208, 4160), (13, 1040, 16000), (16, 4096, 8192), (4, 14336, 4096), (16, 4096, 14336), (2, 1024, 16000)]
+
+
+def per_kernel(shapes):
+    """(kernel, M, N, K) for every kernel that takes M tokens (the dot-product kernel: at most two)."""
+    return [(k,) + tuple(sh) for sh in shapes for k in ("1", "2", "3") if k != "1" or sh[0] <= 2]
+
+
+@pytest.mark.parametrize("kernel,M,N,K", per_kernel(DECODE_SHAPES))
+def test_every_decode_kernel_bit_exact(gpu, monkeypatch, kernel, M, N, K):
+    print("case", kernel, M, N, K, flush=True)
+    monkeypatch.setenv("SMOOTHROT_DECODE_KERNEL", kernel)
+    cx, cw = wl.random_codes(7 * M + K, M, K), wl.random_codes(N + 5 * K, N, K)
+    got = gpu_gemm(gpu, cx, cw)
+    assert np.array_equal(got.astype(np.int64), o.gemm_i32_c(cx, cw))
+
+
+@pytest.mark.parametrize("kernel,M", [(k, M) for (k, M) in per_kernel([(1,), (2,), (16,)])])
+def test_every_decode_kernel_extreme_codes(gpu, monkeypatch, kernel, M):
+    monkeypatch.setenv("SMOOTHROT_DECODE_KERNEL", kernel)
+    K = 131008
+    cx = np.full((M, K), -8, np.int8)
+    cw = np.full((48, K), -8, np.int8)
+    cw[1::2] = 7
+    got = gpu_gemm(gpu, cx, cw)
+    assert np.all(got[:, 0::2] == 64 * K) and np.all(got[:, 1::2] == -56 * K)
+
+
+@pytest.mark.parametrize("kernel,M,N,K", per_kernel([(2, 4096, 4096), (4, 14336, 4096), (11, 528, 1088), (16, 4096, 14336)]))
+def test_every_decode_kernel_fp16_and_leading_dimension(gpu, monkeypatch, kernel, M, N, K):
+    monkeypatch.setenv("SMOOTHROT_DECODE_KERNEL", kernel)
+    rng = np.random.default_rng(M * N + int(kernel))
+    cx, cw = wl.random_codes(3, M, K), wl.random_codes(4, N, K)
+    xs = np.exp(rng.standard_normal(M) * 0.5).astype(np.float32) * 0.05
+    ws = np.exp(rng.standard_normal(N) * 0.3).astype(np.float32) * 1e-3
+    acc = o.gemm_i32_c(cx, cw)
+    want = o.dequant_out(acc, xs, ws)
+    got = gpu_gemm(gpu, cx, cw, xs, ws, gpu.SR_F16, ldy=N + 24)
+    check_output(got, want, "Y %dx%dx%d kernel %s" % (M, N, K, kernel))
+    # fp16 rounding plus the two fp32 roundings of the dequantisation are the only error sources
+    assert np.all(np.abs(got.astype(np.float64) - want) <= np.abs(want) * (2.0 ** -10 + 2.0 ** -21) + 1e-7)
+    assert np.array_equal(gpu_gemm(gpu, cx, cw, ldy=N + 8).astype(np.int64), acc)
+
+
 def test_repeatable_bitwise(gpu):
     cx, cw = wl.random_codes(41, 300, 1024), wl.random_codes(42, 512, 1024)
     a = gpu_gemm(gpu, cx, cw)
