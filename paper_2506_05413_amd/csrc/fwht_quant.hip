@@ -161,8 +161,7 @@ __global__ __launch_bounds__(NT) void fwht_quant_ex_kernel(const __half *__restr
         amax = fmaxf(amax, fmaxf(fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))),
                                  fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w)))));
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+    amax = max_of_wave(amax);
     if ((t & 63) == 0) red[t >> 6] = amax;
     __syncthreads();
     amax = red[0];
@@ -290,8 +289,7 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
     float amax = 0.f;
 #pragma unroll
     for (int r = 0; r < 64; r += 2) amax = fmaxf(fmaxf(amax, fabsf(v[r])), fabsf(v[r + 1]));
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+    amax = max_of_wave(amax);
     const float delta = (amax == 0.f) ? 1.f : (clip * amax) / 7.f;
     const float inv_delta = 1.f / delta;
     if (lane == 0) scale_out[m] = (amax == 0.f) ? 1.f : delta * post_scale;

@@ -378,8 +378,7 @@ __device__ __forceinline__ float rotate_loaded_row_absmax(const RowLoad<K, NT> &
     }
 
     // ---- row absmax ----------------------------------------------------------------------
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+    amax = max_of_wave(amax);
     if ((t & 63) == 0) red[t >> 6] = amax;
     __syncthreads();
     amax = red[0];

@@ -73,7 +73,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_decode_kernel(const uint8_t *__r
 {
     constexpr int NA = 2 * G;                               // weight row sets of 8 channels
     constexpr int XROW = 144;                               // bytes from one staged row to the next
-    __shared__ int red[NW][NA][SETS][4][16];
+    __shared__ int red[NW][2][NA][SETS][4][16];
     __shared__ __attribute__((aligned(16))) uint8_t stage[NW][NA + SETS][8 * XROW];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r8 = lane >> 3, chunk = (lane & 7) * 16;      // load order: row of the set, byte offset inside a slab
@@ -169,16 +169,19 @@ __global__ __launch_bounds__(NW * 64) void gemm_decode_kernel(const uint8_t *__r
     }
 
     // accumulator entry [i][j] sits in lane (j, i >> 2), register i & 3.  Output (channel 8 a + r, token 8 b + t)
-    // = entries [r][t] + [r + 8][t + 8]: lane t + 16 (r >> 2) and the lane 40 above it.
+    // = entries [r][t] + [r + 8][t + 8]: lane t + 16 (r >> 2) and the lane 40 above it.  Both halves go to LDS
+    // as they are (no lane exchange) and are added with the waves' partial sums.
+    {
+        const int half = lane >> 5, l2 = lane - 40 * half;             // upper half: lanes 40..47, 56..63 -> 0..7, 16..23
+        const bool holds = half ? (lane & 8) != 0 : (lane & 8) == 0;
 #pragma unroll
-    for (int a = 0; a < NA; ++a)
+        for (int a = 0; a < NA; ++a)
 #pragma unroll
-        for (int b = 0; b < SETS; ++b)
+            for (int b = 0; b < SETS; ++b)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int both = acc[a][b][v] + __shfl(acc[a][b][v], (lane + 40) & 63, 64);
-                if (lane < 32 && !(lane & 8)) red[wave][a][b][v][(lane & 7) + 8 * (lane >> 4)] = both;
-            }
+                for (int v = 0; v < 4; ++v)
+                    if (holds) red[wave][half][a][b][v][(l2 & 7) + 8 * (l2 >> 4)] = acc[a][b][v];
+    }
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < PER; ++k) {
@@ -188,7 +191,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_decode_kernel(const uint8_t *__r
         const int t = m & 7, b = m >> 3, r = nn & 7, a = nn >> 3;
         int sum = 0;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) sum += red[w][a][b][r & 3][t + 8 * (r >> 2)];
+        for (int w = 0; w < NW; ++w) sum += red[w][0][a][b][r & 3][t + 8 * (r >> 2)] + red[w][1][a][b][r & 3][t + 8 * (r >> 2)];
         sum >>= 8;                                         // both operands carried the factor 16
         if (out_i32) static_cast<int32_t *>(Yv)[(int64_t)m * ldy + n] = sum;
         else static_cast<__half *>(Yv)[(int64_t)m * ldy + n] = __float2half_rn((float)sum * fx[k] * fw[k]);
@@ -397,9 +400,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_decode_dot_kernel(const uint8_t 
 #pragma unroll
         for (int m = 0; m < MT; ++m) {
             int v = acc[g][m];
-            v += __shfl_xor(v, 1, 64);
-            v += __shfl_xor(v, 2, 64);
-            v += __shfl_xor(v, 4, 64);
+            v = sum_of_8_lanes(v);
             if (c == 0) red[wave][m][g * 8 + r] = v;
         }
     __syncthreads();

@@ -53,10 +53,15 @@ __global__ __launch_bounds__(256) void kv_quant_kernel(const __half *__restrict_
             float mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
             float mn = fminf(fminf(fminf(v[0], v[1]), fminf(v[2], v[3])), fminf(fminf(v[4], v[5]), fminf(v[6], v[7])));
             // D % G == 0 and chunks % LPG == 0: a lane group never straddles rows or the end of the data
+            if constexpr (LPG == 16) {                     // the paper's group of 128 values: no LDS round trips
+                mx = max_of_16_lanes(mx);
+                mn = min_of_16_lanes(mn);
+            } else {
 #pragma unroll
-            for (int off = LPG / 2; off >= 1; off >>= 1) {
-                mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-                mn = fminf(mn, __shfl_xor(mn, off, 64));
+                for (int off = LPG / 2; off >= 1; off >>= 1) {
+                    mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+                    mn = fminf(mn, __shfl_xor(mn, off, 64));
+                }
             }
             const float hi = clip * mx, lo = clip * mn;
             const float delta = (hi == lo) ? 1.f : (hi - lo) / 15.f;

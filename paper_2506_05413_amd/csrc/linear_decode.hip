@@ -125,9 +125,7 @@ __global__ __launch_bounds__(LD_NT) void linear_decode_kernel(const __half *__re
 #pragma unroll
         for (int m = 0; m < LD_MT; ++m) {
             int v = acc[g][m];
-            v += __shfl_xor(v, 1, 64);
-            v += __shfl_xor(v, 2, 64);
-            v += __shfl_xor(v, 4, 64);
+            v = sum_of_8_lanes(v);
             if (c == 0) part[(wave * LD_MT + m) * (8 * G) + ((g + (int)blockIdx.x) % G) * 8 + r] = v;
         }
     __syncthreads();

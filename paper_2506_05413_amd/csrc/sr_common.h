@@ -20,6 +20,50 @@ inline bool hadamard_supported(int64_t K)
     return K % 28 == 0 && is_pow2(K / 28) && K % 64 == 0 && K <= kMaxKronK;
 }
 
+// ---- reductions over lanes without LDS traffic (device) ------------------------------------------
+// __shfl_xor compiles to ds_bpermute_b32 here: every step of a reduction then waits for a round trip
+// through the LDS crossbar.  DPP lane permutations are operand modifiers of ordinary vector
+// instructions.  Controls: 0xB1 / 0x4E = quad_perm [1,0,3,2] / [2,3,0,1] (lane ^ 1, lane ^ 2),
+// 0x141 = row_half_mirror (lane i <-> 7 - i of 8), 0x140 = row_mirror (i <-> 15 - i of 16),
+// 0x142 / 0x143 = row_bcast15 / row_bcast31 (last lane of a row of 16 / of 32 lanes to the next ones).
+template <int CTRL, int ROW_MASK = 0xF> __device__ __forceinline__ int lane_perm(int v)
+{
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, ROW_MASK, 0xF, false);      // disabled rows keep their own value
+}
+template <int CTRL, int ROW_MASK = 0xF> __device__ __forceinline__ float lane_perm(float v)
+{
+    return __int_as_float(lane_perm<CTRL, ROW_MASK>(__float_as_int(v)));
+}
+// every lane of an aligned group of 8 / 16 lanes receives the group's result
+__device__ __forceinline__ int sum_of_8_lanes(int v)
+{
+    v += lane_perm<0xB1>(v);
+    v += lane_perm<0x4E>(v);
+    return v + lane_perm<0x141>(v);
+}
+__device__ __forceinline__ float max_of_16_lanes(float v)
+{
+    v = fmaxf(v, lane_perm<0xB1>(v));
+    v = fmaxf(v, lane_perm<0x4E>(v));
+    v = fmaxf(v, lane_perm<0x141>(v));
+    return fmaxf(v, lane_perm<0x140>(v));
+}
+__device__ __forceinline__ float min_of_16_lanes(float v)
+{
+    v = fminf(v, lane_perm<0xB1>(v));
+    v = fminf(v, lane_perm<0x4E>(v));
+    v = fminf(v, lane_perm<0x141>(v));
+    return fminf(v, lane_perm<0x140>(v));
+}
+// maximum over the wave, returned to every lane (through lane 63, which collects the four rows)
+__device__ __forceinline__ float max_of_wave(float v)
+{
+    v = max_of_16_lanes(v);
+    v = fmaxf(v, lane_perm<0x142, 0xA>(v));
+    v = fmaxf(v, lane_perm<0x143, 0xC>(v));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
 // ---- launchers (each returns hipGetLastError() of its launches) ------------------
 
 // y = (x * pre) H per row, per-row symmetric INT4, scale_out = delta * post_scale.
