@@ -110,20 +110,6 @@ __device__ __forceinline__ void store_wave_tile(const V16 (&acc)[FN][FM], uint8_
     }
 }
 
-// compute units of the current device (asked once per process and device)
-inline int compute_units()
-{
-    static int cached[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
-    }
-    return cached[dev];
-}
-
 // Split of the tile grid over the 8 XCDs (each with its own L2): XCD x = v & 7 gets the rectangle
 // (x % xcd_m, x / xcd_m) of an xcd_m x (8 / xcd_m) split and walks it m fastest.  Measured (FETCH_SIZE,
 // M = 2048, K = 4096, int8 kernel): two halves in m by four blocks in n reads 112 MB through the fabric at

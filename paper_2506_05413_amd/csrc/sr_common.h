@@ -28,7 +28,9 @@ inline bool hadamard_supported(int64_t K)
 // 0x142 / 0x143 = row_bcast15 / row_bcast31 (last lane of a row of 16 / of 32 lanes to the next ones).
 template <int CTRL, int ROW_MASK = 0xF> __device__ __forceinline__ int lane_perm(int v)
 {
-    return __builtin_amdgcn_update_dpp(v, v, CTRL, ROW_MASK, 0xF, false);      // disabled rows keep their own value
+    // all rows enabled: every lane has a source, and the compiler can fold the move into the instruction that uses it
+    if constexpr (ROW_MASK == 0xF) return __builtin_amdgcn_mov_dpp(v, CTRL, 0xF, 0xF, true);
+    else return __builtin_amdgcn_update_dpp(v, v, CTRL, ROW_MASK, 0xF, false);  // disabled rows keep their own value
 }
 template <int CTRL, int ROW_MASK = 0xF> __device__ __forceinline__ float lane_perm(float v)
 {
@@ -48,13 +50,6 @@ __device__ __forceinline__ float max_of_16_lanes(float v)
     v = fmaxf(v, lane_perm<0x141>(v));
     return fmaxf(v, lane_perm<0x140>(v));
 }
-__device__ __forceinline__ float min_of_16_lanes(float v)
-{
-    v = fminf(v, lane_perm<0xB1>(v));
-    v = fminf(v, lane_perm<0x4E>(v));
-    v = fminf(v, lane_perm<0x141>(v));
-    return fminf(v, lane_perm<0x140>(v));
-}
 // maximum over the wave, returned to every lane (through lane 63, which collects the four rows)
 __device__ __forceinline__ float max_of_wave(float v)
 {
@@ -62,6 +57,21 @@ __device__ __forceinline__ float max_of_wave(float v)
     v = fmaxf(v, lane_perm<0x142, 0xA>(v));
     v = fmaxf(v, lane_perm<0x143, 0xC>(v));
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+// ---- device properties (host) ---------------------------------------------------------
+// compute units of the current device (asked once per process and device)
+inline int compute_units()
+{
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
 }
 
 // ---- launchers (each returns hipGetLastError() of its launches) ------------------
