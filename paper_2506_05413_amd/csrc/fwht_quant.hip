@@ -21,6 +21,9 @@
 namespace sr {
 namespace {
 
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned int v6u __attribute__((ext_vector_type(6)));
+
 // F6: Q receives f6 tiles (operands of the FP6-MFMA GEMM) instead of packed nibbles; K % 128 == 0 then.
 template <int K, int NT, bool F6>
 __global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict__ X, int64_t ldx, int64_t rows,
@@ -243,7 +246,7 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
                                                             const float *__restrict__ pre, float clip, float post_scale,
                                                             uint8_t *__restrict__ Q, float *__restrict__ scale_out)
 {
-    constexpr int K = 4096, ROWF = K + 64;               // floats per wave-private row incl. padding
+    constexpr int K = 4096, ROWF = F6 ? K + 576 : K + 64;   // floats per wave-private row incl. padding
     extern __shared__ float smem_rows[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int64_t m = (int64_t)blockIdx.x * 4 + wave;
@@ -294,24 +297,53 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
     const float inv_delta = 1.f / delta;
     if (lane == 0) scale_out[m] = (amax == 0.f) ? 1.f : delta * post_scale;
 
-    float *dst = buf + 520 * (lane >> 3) + (lane & 7);
+    if constexpr (F6) {
+        // ---- f6 tiles: every lane converts two pieces of 32 consecutive values ---------------------------------
+        // The E2M3 grid is uniform (1/8) up to 1.875, so the hardware conversion of (code units / 8), which rounds
+        // to nearest-even, yields exactly the field of rint(y / Delta); only the one-sided clamp (+7, -8) is done
+        // here.  v_cvt_scalef32_2xpk16_fp6_f32 takes the even values in its first operand and the odd ones in its
+        // second, divides by its scale operand (a power of two) and returns the 32 fields in order, 6 bits each.
+        // Back through LDS with 4 floats of padding per 32 and 8 per 512 (element i at i + 4 (i >> 5) + 8 (i >> 9)):
+        // the scattered writes below and the 16-byte reads of 32 values per lane are both free of bank conflicts.
+        float *dst = buf + 584 * (lane >> 3) + (lane & 7);
 #pragma unroll
-    for (int r = 0; r < 64; ++r) dst[8 * r] = v[r];
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        for (int r = 0; r < 64; ++r) dst[8 * r + 4 * (r >> 2)] = v[r];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        const int64_t R = m >> 3, row_blocks = (rows + 7) >> 3;
+        const int r8 = (int)(m & 7), swz = (int)(R & 1);
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            const int p = lane + 64 * pass;                  // piece p of the row: k = 32 p .. 32 p + 31
+            const float *s32 = buf + 36 * p + 8 * (p >> 4);
+            v16f ev, od;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const float4 q = *reinterpret_cast<const float4 *>(s32 + 4 * k);
+                ev[2 * k] = __builtin_amdgcn_fmed3f(q.x * inv_delta, -8.f, 7.f);
+                od[2 * k] = __builtin_amdgcn_fmed3f(q.y * inv_delta, -8.f, 7.f);
+                ev[2 * k + 1] = __builtin_amdgcn_fmed3f(q.z * inv_delta, -8.f, 7.f);
+                od[2 * k + 1] = __builtin_amdgcn_fmed3f(q.w * inv_delta, -8.f, 7.f);
+            }
+            const v6u f = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(ev, od, 8.f);
+            const int C = p >> 2, t = (p >> 1) & 1, g = p & 1;
+            uint8_t *blk = Q + ((int64_t)C * row_blocks + R) * 768;
+            *reinterpret_cast<uint4 *>(blk + 256 * t + 128 * (g ^ swz) + 16 * r8) = make_uint4(f[0], f[1], f[2], f[3]);
+            *reinterpret_cast<uint2 *>(blk + 512 + 128 * (g ^ swz) + 16 * r8 + 8 * t) = make_uint2(f[4], f[5]);
+        }
+    } else {
+        float *dst = buf + 520 * (lane >> 3) + (lane & 7);
+#pragma unroll
+        for (int r = 0; r < 64; ++r) dst[8 * r] = v[r];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
 
-    // ---- quantise: 8 consecutive values -> one dword -------------------------------------------
-    uint32_t *q = reinterpret_cast<uint32_t *>(Q + m * (int64_t)(K / 2));
+        // ---- quantise: 8 consecutive values -> one dword ---------------------------------------
+        uint32_t *q = reinterpret_cast<uint32_t *>(Q + m * (int64_t)(K / 2));
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const float *s8 = buf + 520 * j + 8 * lane;
-        const float4 a = *reinterpret_cast<const float4 *>(s8);
-        const float4 b = *reinterpret_cast<const float4 *>(s8 + 4);
-        const float y[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        if constexpr (F6) {
-            uint32_t lo, hi;
-            quant_f6_8(y, inv_delta, lo, hi);
-            store_f6_piece(lo, hi, lane, Q, (rows + 7) >> 3, m, 16 * j + (lane >> 2));
-        } else {
+        for (int j = 0; j < 8; ++j) {
+            const float *s8 = buf + 520 * j + 8 * lane;
+            const float4 a = *reinterpret_cast<const float4 *>(s8);
+            const float4 b = *reinterpret_cast<const float4 *>(s8 + 4);
+            const float y[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
             q[64 * j + lane] = quant_pack8(y, inv_delta);
         }
     }
@@ -365,7 +397,7 @@ template <bool HAS_PRE, bool F6>
 hipError_t launch_wave4096(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip, float post_scale,
                            uint8_t *Q, float *scale_out, hipStream_t st)
 {
-    constexpr size_t lds = 4 * (4096 + 64) * sizeof(float);
+    constexpr size_t lds = 4 * (4096 + (F6 ? 576 : 64)) * sizeof(float);
     const unsigned blocks = F6 ? (unsigned)((rows + 63) / 64 * 16) : (unsigned)((rows + 3) / 4);
     auto kern = fwht4096_wave_kernel<HAS_PRE, F6>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
