@@ -264,8 +264,11 @@ SR_API size_t sr_f6_tiles_bytes(int64_t rows, int64_t K);
 SR_API int sr_pack_f6_tiles(const uint8_t *Q4, int64_t rows, int64_t K, uint8_t *T6, void *stream);
 
 /*
- * sr_fwht_quant_act writing the activation codes as f6 tiles (same rotation, same quantiser, same
- * scales; the codes are the ones sr_fwht_quant_act would pack as nibbles).
+ * sr_fwht_quant_act writing the activation codes as f6 tiles (same rotation, same scales, same
+ * quantiser: clamp(rint(y / Delta), -8, 7), Eq. (1)).  The rounding is done by the hardware
+ * FP6 conversion of the fp32 product y * (1 / Delta) instead of a fused multiply-add, so a code
+ * may differ from the one sr_fwht_quant_act packs where y / Delta sits on a rounding boundary
+ * (both are within the rounding freedom of the fp32 rotation).
  *   X6   out, sr_f6_tiles_bytes(M, K) bytes, 16-byte aligned; the rows that pad the last block of
  *        8 are left unwritten (the GEMM never stores their outputs)
  *   K    a supported Hadamard order that is a multiple of 128

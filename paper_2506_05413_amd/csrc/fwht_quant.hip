@@ -21,9 +21,6 @@
 namespace sr {
 namespace {
 
-typedef float v16f __attribute__((ext_vector_type(16)));
-typedef unsigned int v6u __attribute__((ext_vector_type(6)));
-
 // F6: Q receives f6 tiles (operands of the FP6-MFMA GEMM) instead of packed nibbles; K % 128 == 0 then.
 template <int K, int NT, bool F6>
 __global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict__ X, int64_t ldx, int64_t rows,
@@ -51,19 +48,19 @@ __global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict
     const float inv_delta = 1.f / delta;
     if (t == 0) scale_out[m] = (amax == 0.f) ? 1.f : delta * post_scale;
 
-    // ---- quantise 8 contiguous values -> one packed dword (or 48 bits of a tile piece) ---------
-    uint32_t *q = reinterpret_cast<uint32_t *>(Q + m * (int64_t)(K / 2));
-    const int64_t row_blocks = (rows + 7) >> 3;
-    for (int c = t; c < K / 8; c += NT) {
-        const float *src = row + pad(8 * c);
-        const float4 a = *reinterpret_cast<const float4 *>(src);
-        const float4 b = *reinterpret_cast<const float4 *>(src + 4);
-        const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        if constexpr (F6) {
-            uint32_t lo, hi;
-            quant_f6_8(v, inv_delta, lo, hi);
-            store_f6_piece(lo, hi, t, Q, row_blocks, m, c >> 2);     // K / 8 and NT are multiples of 4: whole quads
-        } else {
+    if constexpr (F6) {
+        // ---- 32 contiguous values -> one 24-byte piece of a tile (the padding of 4 floats per 64 keeps the
+        // 16-byte reads of 16 neighbouring threads on distinct banks) -----------------------------------------
+        const int64_t row_blocks = (rows + 7) >> 3;
+        for (int p = t; p < K / 32; p += NT) quant_store_f6_piece(row + pad(32 * p), inv_delta, Q, row_blocks, m, p);
+    } else {
+        // ---- quantise 8 contiguous values -> one packed dword ---------------------------------------------
+        uint32_t *q = reinterpret_cast<uint32_t *>(Q + m * (int64_t)(K / 2));
+        for (int c = t; c < K / 8; c += NT) {
+            const float *src = row + pad(8 * c);
+            const float4 a = *reinterpret_cast<const float4 *>(src);
+            const float4 b = *reinterpret_cast<const float4 *>(src + 4);
+            const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
             q[c] = quant_pack8(v, inv_delta);
         }
     }
@@ -214,17 +211,15 @@ __global__ __launch_bounds__(NT) void fwht_quant_ex_kernel(const __half *__restr
     const float inv_delta = 1.f / delta;
     if (t == 0) scale_out[m] = (amax == 0.f) ? 1.f : delta * post_scale;
 
-    uint32_t *q = reinterpret_cast<uint32_t *>(Q + m * (int64_t)(K / 2));
-    for (int c = t; c < K / 8; c += NT) {
-        const float *src = row + pad(8 * c);
-        const float4 a = *reinterpret_cast<const float4 *>(src);
-        const float4 b = *reinterpret_cast<const float4 *>(src + 4);
-        const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        if constexpr (F6) {
-            uint32_t lo, hi;
-            quant_f6_8(v, inv_delta, lo, hi);
-            store_f6_piece(lo, hi, t, Q, (rows + 7) >> 3, m, c >> 2);
-        } else {
+    if constexpr (F6) {
+        for (int p = t; p < K / 32; p += NT) quant_store_f6_piece(row + pad(32 * p), inv_delta, Q, (rows + 7) >> 3, m, p);
+    } else {
+        uint32_t *q = reinterpret_cast<uint32_t *>(Q + m * (int64_t)(K / 2));
+        for (int c = t; c < K / 8; c += NT) {
+            const float *src = row + pad(8 * c);
+            const float4 a = *reinterpret_cast<const float4 *>(src);
+            const float4 b = *reinterpret_cast<const float4 *>(src + 4);
+            const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
             q[c] = quant_pack8(v, inv_delta);
         }
     }
@@ -298,37 +293,18 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
     if (lane == 0) scale_out[m] = (amax == 0.f) ? 1.f : delta * post_scale;
 
     if constexpr (F6) {
-        // ---- f6 tiles: every lane converts two pieces of 32 consecutive values ---------------------------------
-        // The E2M3 grid is uniform (1/8) up to 1.875, so the hardware conversion of (code units / 8), which rounds
-        // to nearest-even, yields exactly the field of rint(y / Delta); only the one-sided clamp (+7, -8) is done
-        // here.  v_cvt_scalef32_2xpk16_fp6_f32 takes the even values in its first operand and the odd ones in its
-        // second, divides by its scale operand (a power of two) and returns the 32 fields in order, 6 bits each.
+        // ---- f6 tiles: every lane converts two pieces of 32 consecutive values (quant_store_f6_piece) -----------
         // Back through LDS with 4 floats of padding per 32 and 8 per 512 (element i at i + 4 (i >> 5) + 8 (i >> 9)):
         // the scattered writes below and the 16-byte reads of 32 values per lane are both free of bank conflicts.
         float *dst = buf + 584 * (lane >> 3) + (lane & 7);
 #pragma unroll
         for (int r = 0; r < 64; ++r) dst[8 * r + 4 * (r >> 2)] = v[r];
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        const int64_t R = m >> 3, row_blocks = (rows + 7) >> 3;
-        const int r8 = (int)(m & 7), swz = (int)(R & 1);
+        const int64_t row_blocks = (rows + 7) >> 3;
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
             const int p = lane + 64 * pass;                  // piece p of the row: k = 32 p .. 32 p + 31
-            const float *s32 = buf + 36 * p + 8 * (p >> 4);
-            v16f ev, od;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const float4 q = *reinterpret_cast<const float4 *>(s32 + 4 * k);
-                ev[2 * k] = __builtin_amdgcn_fmed3f(q.x * inv_delta, -8.f, 7.f);
-                od[2 * k] = __builtin_amdgcn_fmed3f(q.y * inv_delta, -8.f, 7.f);
-                ev[2 * k + 1] = __builtin_amdgcn_fmed3f(q.z * inv_delta, -8.f, 7.f);
-                od[2 * k + 1] = __builtin_amdgcn_fmed3f(q.w * inv_delta, -8.f, 7.f);
-            }
-            const v6u f = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(ev, od, 8.f);
-            const int C = p >> 2, t = (p >> 1) & 1, g = p & 1;
-            uint8_t *blk = Q + ((int64_t)C * row_blocks + R) * 768;
-            *reinterpret_cast<uint4 *>(blk + 256 * t + 128 * (g ^ swz) + 16 * r8) = make_uint4(f[0], f[1], f[2], f[3]);
-            *reinterpret_cast<uint2 *>(blk + 512 + 128 * (g ^ swz) + 16 * r8 + 8 * t) = make_uint2(f[4], f[5]);
+            quant_store_f6_piece(buf + 36 * p + 8 * (p >> 4), inv_delta, Q, row_blocks, m, p);
         }
     } else {
         float *dst = buf + 520 * (lane >> 3) + (lane & 7);

@@ -209,49 +209,37 @@ __device__ __forceinline__ uint32_t quant_pack8(const float (&y)[8], float inv_d
 }
 
 // ---- the same quantiser writing "f6 tiles" (operand layout of the FP6-MFMA GEMM, see gemm_f6.hip) ----------
-// A code c becomes the 6-bit sign-magnitude field (c < 0 ? 32 : 0) | |c| (the E2M3 pattern of c / 8).  Rounding
-// |y| / Delta to nearest-even and clamping the magnitude to 7 (8 for negative values) gives the same code as
-// clamp(rint(y / Delta), -8, 7); a negative value that rounds to 0 becomes the field 32 (-0), which multiplies
-// like 0.  Eight consecutive values give 48 bits: lo = bits 0..31, hi = bits 32..47.
-__device__ __forceinline__ void quant_f6_8(const float (&y)[8], float inv_delta, uint32_t &lo, uint32_t &hi)
+// A code c becomes the 6-bit sign-magnitude field (c < 0 ? 32 : 0) | |c| (the E2M3 pattern of c / 8).  The E2M3
+// grid is uniform (steps of 1/8) up to 1.875, so the hardware conversion of (y / Delta) / 8, which rounds to
+// nearest-even, yields exactly the field of rint(y / Delta); only the one-sided clamp (+7, -8) is done here.  A
+// negative value that rounds to 0 becomes the field 32 (-0), which multiplies like 0.
+// v_cvt_scalef32_2xpk16_fp6_f32 takes the even values of 32 consecutive ones in its first operand and the odd
+// ones in its second, divides by its scale operand (a power of two) and returns the 32 fields in order, 6 bits
+// each (checked value by value on the device: every code, every tie, both zeros, values beyond the clamp).
+//
+// One thread quantises the 32 consecutive values at s32 (16-byte aligned) = piece p of row m (k = 32 p ..
+// 32 p + 31) and stores its 24 bytes: the first 16 and the last 8 go to different places of the tile block.
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned int v6u __attribute__((ext_vector_type(6)));
+__device__ __forceinline__ void quant_store_f6_piece(const float *s32, float inv_delta, uint8_t *__restrict__ T6,
+                                                     int64_t row_blocks, int64_t m, int p)
 {
-    // t = magic + magnitude + 32 sign per value; the fields are packed by shift-adds modulo 2^32 with the magic
-    // constant still inside and its packed image subtracted once (its two low bits are zero, so the shift right
-    // of the field that straddles the two words commutes with the subtraction)
-    const float magic = __uint_as_float(kMagicBits);
-    uint32_t t[8];
+    v16f ev, od;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const uint32_t sign = __float_as_uint(y[e]) >> 31;
-        const uint32_t bits = __float_as_uint(fmaf(fabsf(y[e]), inv_delta, magic));
-        t[e] = min(bits, kMagicBits + 7u + sign) + (sign << 5);
+    for (int k = 0; k < 8; ++k) {
+        const float4 q = *reinterpret_cast<const float4 *>(s32 + 4 * k);
+        ev[2 * k] = __builtin_amdgcn_fmed3f(q.x * inv_delta, -8.f, 7.f);
+        od[2 * k] = __builtin_amdgcn_fmed3f(q.y * inv_delta, -8.f, 7.f);
+        ev[2 * k + 1] = __builtin_amdgcn_fmed3f(q.z * inv_delta, -8.f, 7.f);
+        od[2 * k + 1] = __builtin_amdgcn_fmed3f(q.w * inv_delta, -8.f, 7.f);
     }
-    constexpr uint32_t c_lo = kMagicBits + (kMagicBits << 6) + (kMagicBits << 12) + (kMagicBits << 18) + (kMagicBits << 24) +
-                              (kMagicBits << 30);
-    constexpr uint32_t c_hi = (kMagicBits >> 2) + (kMagicBits << 4) + (kMagicBits << 10);
-    static_assert((kMagicBits & 3u) == 0, "the straddling field relies on it");
-    lo = t[0] + (t[1] << 6) + (t[2] << 12) + (t[3] << 18) + (t[4] << 24) + (t[5] << 30) - c_lo;
-    hi = (t[5] >> 2) + (t[6] << 4) + (t[7] << 10) - c_hi;
-}
-
-// Four neighbouring lanes (a quad, lane & 3 = 0..3) hold the 48-bit strings of 32 consecutive values = one
-// 24-byte piece of the tile layout: piece p of row m covers k = 32 p .. 32 p + 31.  Lane 0 of the quad stores
-// the first 16 bytes, lane 2 the last 8.  All four lanes must be active.
-__device__ __forceinline__ void store_f6_piece(uint32_t lo, uint32_t hi, int lane, uint8_t *__restrict__ T6,
-                                               int64_t row_blocks, int64_t m, int p)
-{
-    const uint32_t lo_n1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)lo, 0x39, 0xF, 0xF, true);   // from lane + 1 of the quad
-    const uint32_t hi_n1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)hi, 0x39, 0xF, 0xF, true);
-    const uint32_t lo_n2 = (uint32_t)__builtin_amdgcn_mov_dpp((int)lo, 0x4E, 0xF, 0xF, true);   // from lane + 2
-    const uint32_t a = hi | (lo_n1 << 16), b = (lo_n1 >> 16) | (hi_n1 << 16);
+    const v6u f = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(ev, od, 8.f);
     const int C = p >> 2, t = (p >> 1) & 1, g = p & 1;
     const int64_t R = m >> 3;
-    const int r = (int)(m & 7), Rl = (int)(R & 3);
+    const int r = (int)(m & 7), swz = (int)(R & 1);
     uint8_t *blk = T6 + ((int64_t)C * row_blocks + R) * 768;
-    if ((lane & 3) == 0)
-        *reinterpret_cast<uint4 *>(blk + 256 * t + 128 * (g ^ (Rl & 1)) + 16 * r) = make_uint4(lo, a, b, lo_n2);
-    else if ((lane & 3) == 2)
-        *reinterpret_cast<uint2 *>(blk + 512 + 128 * (g ^ (Rl & 1)) + 16 * r + 8 * t) = make_uint2(a, b);
+    *reinterpret_cast<uint4 *>(blk + 256 * t + 128 * (g ^ swz) + 16 * r) = make_uint4(f[0], f[1], f[2], f[3]);
+    *reinterpret_cast<uint2 *>(blk + 512 + 128 * (g ^ swz) + 16 * r + 8 * t) = make_uint2(f[4], f[5]);
 }
 
 // ---- rotation of one row by a whole workgroup -----------------------------------------------

@@ -163,10 +163,11 @@ def test_quantiser_tiles_every_order(gpu, M, K):
 
 
 def test_quantiser_tiles_agree_with_the_nibble_path(gpu):
-    """Same rotation, two output formats.  The workgroup-per-row kernels (M = 40, M = 24) round both formats with
-    the same instructions: identical codes.  The wave-per-row kernel (K = 4096, more than 1024 rows) rounds its
-    tile fields with the hardware FP6 conversion and its nibbles with the fused multiply-add: each is held to
-    the rounding-boundary rule against the oracle, and the two may differ only there."""
+    """Same rotation, two output formats.  The tile fields are rounded by the hardware FP6 conversion of the
+    fp32 product y * (1 / Delta), the nibbles by a fused multiply-add with the rounding constant: each is held to
+    the rounding-boundary rule against the oracle, the scales are identical, and the two sets of codes may differ
+    only at such boundaries (a handful per million).  M = 2048, K = 4096 runs the wave-per-row kernel, the others
+    the workgroup-per-row kernel."""
     for M, K in ((2048, 4096), (40, 4096), (24, 14336)):
         X = wl.cfg2_X(M, K) if K == 4096 else wl.cfg3_X(M, K)
         inv_s = np.random.default_rng(M).uniform(0.5, 2.0, K).astype(np.float32)
@@ -175,13 +176,10 @@ def test_quantiser_tiles_agree_with_the_nibble_path(gpu):
         torch.cuda.synchronize()
         codes4 = o.unpack_int4(Xq.cpu().numpy())
         assert np.array_equal(xs, xs4.cpu().numpy())
-        if M > 1024 and K == 4096:
-            ref = o.fwht_quant_act(X, inv_s, 0.9)
-            check_codes(codes, ref["codes"], ref["t"])
-            check_codes(codes4, ref["codes"], ref["t"])
-            assert np.count_nonzero(codes != codes4) <= 1e-5 * codes.size
-        else:
-            assert np.array_equal(codes, codes4)
+        ref = o.fwht_quant_act(X, inv_s, 0.9)
+        check_codes(codes, ref["codes"], ref["t"])
+        check_codes(codes4, ref["codes"], ref["t"])
+        assert np.count_nonzero(codes != codes4) <= max(2, 1e-5 * codes.size)
 
 
 @pytest.mark.parametrize("M", [1025, 1030, 1100])
@@ -203,7 +201,7 @@ def test_quantiser_tiles_wave_kernel(gpu, M, smooth):
 @pytest.mark.parametrize("M,K", [(5, 896), (24, 14336), (9, 4096)])
 def test_gated_prologue_tiles(gpu, M, K):
     """silu(gate) * up fused in front of the rotation, tile output: codes under the boundary rule against the
-    oracle, and identical to the nibble output of the same kernel."""
+    oracle; same scales as the nibble output of the same kernel, codes apart only at rounding boundaries."""
     G, U = wl.gate_up(3, M, K, 2, 300.0)
     inv_s = np.random.default_rng(K + M).uniform(0.5, 2.0, K).astype(np.float32)
     Gd, Ud, inv_d = torch.from_numpy(G).cuda(), torch.from_numpy(U).cuda(), torch.from_numpy(inv_s).cuda()
@@ -214,7 +212,9 @@ def test_gated_prologue_tiles(gpu, M, K):
     ref = o.fwht_quant_swiglu(G, U, inv_s, 0.9)
     check_scales(xs.cpu().numpy(), ref["x_scale"])
     check_codes(codes, ref["codes"], ref["t"])
-    assert np.array_equal(codes, o.unpack_int4(Xq.cpu().numpy())) and np.array_equal(xs.cpu().numpy(), xs4.cpu().numpy())
+    codes4 = o.unpack_int4(Xq.cpu().numpy())
+    check_codes(codes4, ref["codes"], ref["t"])
+    assert np.count_nonzero(codes != codes4) <= max(2, 1e-5 * codes.size) and np.array_equal(xs.cpu().numpy(), xs4.cpu().numpy())
 
 
 def test_cfg2_layer_through_the_f6_path(gpu):
