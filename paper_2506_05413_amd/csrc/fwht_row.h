@@ -255,13 +255,16 @@ struct RowLoad {
     float4 p[NG][4];                                       // the matching 16 values of `pre`, if any
 };
 
-template <int K, int NT>
+// ALWAYS: threads beyond the row load group 0 instead of nothing, so that the loads sit in straight-line code
+// (for a caller that issues further loads behind these and wants the compiler to count them in its waits).
+template <int K, int NT, bool ALWAYS = false>
 __device__ __forceinline__ void row_load(const __half *__restrict__ x, const float *__restrict__ pre, const int t,
                                          RowLoad<K, NT> &ld)
 {
 #pragma unroll
     for (int i = 0; i < RowLoad<K, NT>::NG; ++i) {
-        const int g = t + i * NT;
+        int g = t + i * NT;
+        if (ALWAYS) g = g < K / 16 ? g : 0;
         if (g < K / 16) {
             ld.u[i][0] = *reinterpret_cast<const uint4 *>(x + 16 * g);
             ld.u[i][1] = *reinterpret_cast<const uint4 *>(x + 16 * g + 8);

@@ -49,11 +49,18 @@ __global__ __launch_bounds__(LD_NT) void linear_decode_kernel(const __half *__re
 
     // ---- the first token row's loads go first (they are what the rotation waits for) ...
     RowLoad<K, LD_NT> xld;
-    row_load<K, LD_NT>(X, pre, t, xld);
+    row_load<K, LD_NT, true>(X, pre, t, xld);
 
-    // ---- ... then all weight loads of this workgroup, up front -------------------------------
+    // ---- ... the channel scale of this thread's output (fetched now, used last: a load after the reduction would
+    // put one more memory latency at the end of the kernel) ...
+    static_assert(8 * G <= LD_NT, "one output per thread");
+    const float w_scale = (t < 8 * G && n0 + t < N) ? ws[n0 + t] : 0.f;
+
+    // ---- ... then all weight loads of this workgroup, up front, every one unconditional: a load under a
+    // branch would make the compiler wait for ALL outstanding loads before the rotation may touch the row, and the
+    // rotation would then start when the last weight has arrived instead of running while they travel
+    static_assert(NSLAB % LD_NW == 0 && Kb % 128 == 0, "every wave owns whole slabs");
     u32x4 w[G][U];
-    const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         // register slot g holds row group (g + workgroup index) mod G: at any moment the workgroups of the
@@ -62,15 +69,16 @@ __global__ __launch_bounds__(LD_NT) void linear_decode_kernel(const __half *__re
         n = n < N ? n : N - 1;                                          // ragged last workgroup: re-read the last row
         const uint8_t *wp = Wq + (int64_t)n * Kb + c * 16;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int off = (wave + LD_NW * u) * 128;
-            w[g][u] = (off + c * 16 < Kb) ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + off)) : zero;
-        }
+        for (int u = 0; u < U; ++u)
+            w[g][u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + (wave + LD_NW * u) * 128));
     }
 
-    // ---- rotate + quantise the token rows into LDS --------------------------------------------
-    for (int m = 0; m < M; ++m) {
-        if (m > 0) row_load<K, LD_NT>(X + m * ldx, pre, t, xld);
+    // nothing of the rotation may be scheduled ahead of the weight loads (its first instructions wait for the row)
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- rotate + quantise the token row into LDS (M = 1: the host rejects more) ----------------
+    {
+        constexpr int m = 0;
         const float amax = rotate_loaded_row_absmax<K, LD_NT>(xld, pre, row, red, t);
         const float delta = (amax == 0.f) ? 1.f : (clip * amax) / 7.f;
         const float inv_delta = 1.f / delta;
@@ -100,10 +108,10 @@ __global__ __launch_bounds__(LD_NT) void linear_decode_kernel(const __half *__re
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int off = (wave + LD_NW * u) * 128 + c * 16;             // byte offset inside a row of codes
-        if (off < Kb) {
+        {
 #pragma unroll
             for (int m = 0; m < LD_MT; ++m) {
-                if (m < M) {
+                {
                     const u32x4 x = *reinterpret_cast<const u32x4 *>(xq + m * (K / 8) + off / 4);
 #pragma unroll
                     for (int g = 0; g < G; ++g) {
@@ -129,13 +137,11 @@ __global__ __launch_bounds__(LD_NT) void linear_decode_kernel(const __half *__re
             if (c == 0) part[(wave * LD_MT + m) * (8 * G) + ((g + (int)blockIdx.x) % G) * 8 + r] = v;
         }
     __syncthreads();
-    for (int o = t; o < M * 8 * G; o += LD_NT) {
-        const int m = o / (8 * G), j = o % (8 * G), n = n0 + j;
-        if (n >= N) continue;
+    if (t < 8 * G && n0 + t < N) {                                      // M = 1: output t of the workgroup
         int sum = 0;
 #pragma unroll
-        for (int wv = 0; wv < LD_NW; ++wv) sum += part[(wv * LD_MT + m) * (8 * G) + j];
-        Y[(int64_t)m * ldy + n] = __float2half_rn((float)sum * sx[m] * ws[n]);
+        for (int wv = 0; wv < LD_NW; ++wv) sum += part[wv * LD_MT * (8 * G) + t];
+        Y[n0 + t] = __float2half_rn((float)sum * sx[0] * w_scale);
     }
 }
 
