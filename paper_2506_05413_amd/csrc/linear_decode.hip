@@ -163,12 +163,20 @@ hipError_t launch_ld(const void *X, int64_t M, int64_t ldx, const float *pre, fl
     return hipGetLastError();
 }
 
-// largest G in {1, 2, 4, 8} with G <= gmax that still leaves at least ~256 workgroups (or G = 1)
+// Row groups of 8 channels per workgroup: every workgroup repeats the rotation, so few large workgroups are
+// cheaper, but the chip should be filled in whole rounds -- the G <= gmax with the least (rounds x G), ties to
+// the larger G (14336 channels on 256 CUs: G = 7 gives exactly 256 workgroups, G = 8 would leave 32 CUs idle).
 inline int pick_g(int64_t N, int gmax)
 {
-    int G = 1;
-    while (2 * G <= gmax && N / (16 * G) >= 224) G *= 2;
-    return G;
+    const int64_t cus = compute_units();
+    int best = 1;
+    int64_t best_cost = -1;
+    for (int g = 1; g <= gmax; ++g) {
+        const int64_t blocks = (N + 8 * g - 1) / (8 * g);
+        const int64_t cost = ((blocks + cus - 1) / cus) * g;
+        if (best_cost < 0 || cost <= best_cost) { best = g; best_cost = cost; }
+    }
+    return best;
 }
 
 }  // namespace
@@ -179,13 +187,14 @@ hipError_t launch_linear_decode(const void *X, int64_t M, int64_t K, int64_t ldx
                                 const uint8_t *Wq, const float *ws, int64_t N, void *Y, int64_t ldy,
                                 uint8_t *Xq_out, float *xs_out, hipStream_t st)
 {
-#define SR_LD(KK, GG) return launch_ld<KK, GG>(X, M, ldx, pre, clip, Wq, ws, N, Y, ldy, Xq_out, xs_out, st)
+#define SR_LD(KK, GG) case GG: return launch_ld<KK, GG>(X, M, ldx, pre, clip, Wq, ws, N, Y, ldy, Xq_out, xs_out, st)
     switch (K) {
-        case 2048: switch (pick_g(N, 8)) { case 8: SR_LD(2048, 8); case 4: SR_LD(2048, 4); case 2: SR_LD(2048, 2); default: SR_LD(2048, 1); }
-        case 4096: switch (pick_g(N, 8)) { case 8: SR_LD(4096, 8); case 4: SR_LD(4096, 4); case 2: SR_LD(4096, 2); default: SR_LD(4096, 1); }
-        case 8192: switch (pick_g(N, 4)) { case 4: SR_LD(8192, 4); case 2: SR_LD(8192, 2); default: SR_LD(8192, 1); }
-        default: return hipErrorInvalidValue;
+        case 2048: switch (pick_g(N, 8)) { SR_LD(2048, 1); SR_LD(2048, 2); SR_LD(2048, 3); SR_LD(2048, 4); SR_LD(2048, 5); SR_LD(2048, 6); SR_LD(2048, 7); SR_LD(2048, 8); default: break; } break;
+        case 4096: switch (pick_g(N, 8)) { SR_LD(4096, 1); SR_LD(4096, 2); SR_LD(4096, 3); SR_LD(4096, 4); SR_LD(4096, 5); SR_LD(4096, 6); SR_LD(4096, 7); SR_LD(4096, 8); default: break; } break;
+        case 8192: switch (pick_g(N, 4)) { SR_LD(8192, 1); SR_LD(8192, 2); SR_LD(8192, 3); SR_LD(8192, 4); default: break; } break;
+        default: break;
     }
+    return hipErrorInvalidValue;
 #undef SR_LD
 }
 
