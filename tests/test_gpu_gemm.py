@@ -157,6 +157,25 @@ def test_every_decode_kernel_fp16_and_leading_dimension(gpu, monkeypatch, kernel
     assert np.array_equal(gpu_gemm(gpu, cx, cw, ldy=N + 8).astype(np.int64), acc)
 
 
+def test_decode_seeded_random_shapes(gpu, monkeypatch):
+    """Thirty seeded shapes (M up to 16, N a multiple of 16 up to 9600, K a multiple of 64 up to 6144) through
+    every decode kernel that takes them and through the dispatcher's own choice: accumulators bit-exact, nothing
+    written past N."""
+    rng = np.random.default_rng(20250606)
+    for case in range(30):
+        M = int(rng.integers(1, 17))
+        N = 16 * int(rng.integers(1, 601))
+        K = 64 * int(rng.integers(1, 97))
+        cx, cw = wl.random_codes(3000 + case, M, K), wl.random_codes(4000 + case, N, K)
+        want = o.gemm_i32_c(cx, cw)
+        for kernel in ("0", "1", "2", "3"):
+            if kernel == "1" and M > 2:
+                continue
+            print("case", case, M, N, K, "kernel", kernel, flush=True)
+            monkeypatch.setenv("SMOOTHROT_DECODE_KERNEL", kernel)
+            assert np.array_equal(gpu_gemm(gpu, cx, cw, ldy=N + 8).astype(np.int64), want), (M, N, K, kernel)
+
+
 def test_repeatable_bitwise(gpu):
     cx, cw = wl.random_codes(41, 300, 1024), wl.random_codes(42, 512, 1024)
     a = gpu_gemm(gpu, cx, cw)
