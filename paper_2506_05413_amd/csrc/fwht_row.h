@@ -253,13 +253,14 @@ struct RowLoad {
     static constexpr int NG = (K / 16 + NT - 1) / NT;      // groups of 16 values per thread
     uint4 u[NG][2];
     float4 p[NG][4];                                       // the matching 16 values of `pre`, if any
+    uint4 gu[NG][2];                                       // the matching 16 values of the gate row, if any
 };
 
 // ALWAYS: threads beyond the row load group 0 instead of nothing, so that the loads sit in straight-line code
 // (for a caller that issues further loads behind these and wants the compiler to count them in its waits).
-template <int K, int NT, bool ALWAYS = false>
+template <int K, int NT, bool ALWAYS = false, bool GATE = false>
 __device__ __forceinline__ void row_load(const __half *__restrict__ x, const float *__restrict__ pre, const int t,
-                                         RowLoad<K, NT> &ld)
+                                         RowLoad<K, NT> &ld, const __half *__restrict__ gate = nullptr)
 {
 #pragma unroll
     for (int i = 0; i < RowLoad<K, NT>::NG; ++i) {
@@ -268,6 +269,10 @@ __device__ __forceinline__ void row_load(const __half *__restrict__ x, const flo
         if (g < K / 16) {
             ld.u[i][0] = *reinterpret_cast<const uint4 *>(x + 16 * g);
             ld.u[i][1] = *reinterpret_cast<const uint4 *>(x + 16 * g + 8);
+            if constexpr (GATE) {
+                ld.gu[i][0] = *reinterpret_cast<const uint4 *>(gate + 16 * g);
+                ld.gu[i][1] = *reinterpret_cast<const uint4 *>(gate + 16 * g + 8);
+            }
             if (pre) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) ld.p[i][q] = *reinterpret_cast<const float4 *>(pre + 16 * g + 4 * q);
@@ -276,7 +281,9 @@ __device__ __forceinline__ void row_load(const __half *__restrict__ x, const flo
     }
 }
 
-template <int K, int NT>
+// GATE: x = silu(gate) * x in fp32 before the smoothing factors (the down-projection input of a gated FFN,
+// paper Fig. 2: sigma(gate) (.) up, then 1/s, Hadamard, quantiser).
+template <int K, int NT, bool GATE = false>
 __device__ __forceinline__ float rotate_loaded_row_absmax(const RowLoad<K, NT> &ld, const float *__restrict__ pre,
                                                           float *row, float *red, const int t)
 {
@@ -296,6 +303,17 @@ __device__ __forceinline__ float rotate_loaded_row_absmax(const RowLoad<K, NT> &
             float v[16];
 #pragma unroll
             for (int e = 0; e < 16; ++e) v[e] = __half2float(raw.h[e]);
+            if constexpr (GATE) {
+                union { uint4 u[2]; __half h[16]; } graw;
+                graw.u[0] = ld.gu[i][0];
+                graw.u[1] = ld.gu[i][1];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float gv = __half2float(graw.h[e]);
+                    // silu(g) = g / (1 + exp(-g)); exp(-g) = inf for very negative g gives g * 0 = -0
+                    v[e] *= gv * __builtin_amdgcn_rcpf(1.f + __expf(-gv));
+                }
+            }
             if (pre) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -379,13 +397,14 @@ __device__ __forceinline__ float rotate_loaded_row_absmax(const RowLoad<K, NT> &
     return amax;
 }
 
-template <int K, int NT>
+template <int K, int NT, bool GATE = false>
 __device__ __forceinline__ float rotate_row_absmax(const __half *__restrict__ x, const float *__restrict__ pre,
-                                                   float *row, float *red, const int t)
+                                                   float *row, float *red, const int t,
+                                                   const __half *__restrict__ gate = nullptr)
 {
     RowLoad<K, NT> ld;
-    row_load<K, NT>(x, pre, t, ld);
-    return rotate_loaded_row_absmax<K, NT>(ld, pre, row, red, t);
+    row_load<K, NT, false, GATE>(x, pre, t, ld, gate);
+    return rotate_loaded_row_absmax<K, NT, GATE>(ld, pre, row, red, t);
 }
 
 }  // namespace
