@@ -237,10 +237,12 @@ __global__ __launch_bounds__(NT) void fwht_quant_ex_kernel(const __half *__restr
 //   lane quantises 8 consecutive values into one packed dword.
 // ------------------------------------------------------------------------------------------
 
-template <bool HAS_PRE, bool F6>
+// MASKED: head-wise transform -- only the index bits set in had_mask are butterflied (uniform branches).
+template <bool HAS_PRE, bool F6, bool MASKED = false>
 __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__restrict__ X, int64_t ldx, int64_t rows,
                                                             const float *__restrict__ pre, float clip, float post_scale,
-                                                            uint8_t *__restrict__ Q, float *__restrict__ scale_out)
+                                                            uint8_t *__restrict__ Q, float *__restrict__ scale_out,
+                                                            uint32_t had_mask)
 {
     constexpr int K = 4096, ROWF = F6 ? K + 576 : K + 64;   // floats per wave-private row incl. padding
     extern __shared__ float smem_rows[];
@@ -271,7 +273,8 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
             v[8 * j + 4] *= s1.x; v[8 * j + 5] *= s1.y; v[8 * j + 6] *= s1.z; v[8 * j + 7] *= s1.w;
         }
     }
-    butterflies<6>(v);
+    if constexpr (MASKED) butterflies_masked<6>(v, (had_mask & 7u) | (((had_mask >> 9) & 7u) << 3));   // register bits = index bits 0,1,2,9,10,11
+    else butterflies<6>(v);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         float *d = buf + 520 * j + 8 * lane;             // element 512 j + 8 l + e lives at 520 j + 8 l + e
@@ -284,7 +287,8 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
     const float *src = buf + 520 * (lane >> 3) + (lane & 7);
 #pragma unroll
     for (int r = 0; r < 64; ++r) v[r] = src[8 * r];
-    butterflies<6>(v);
+    if constexpr (MASKED) butterflies_masked<6>(v, (had_mask >> 3) & 63u);                            // index bits 3..8
+    else butterflies<6>(v);
     float amax = 0.f;
 #pragma unroll
     for (int r = 0; r < 64; r += 2) amax = fmaxf(fmaxf(amax, fabsf(v[r])), fabsf(v[r + 1]));
@@ -391,17 +395,17 @@ hipError_t launch_one_ex(const void *X, int64_t rows, int64_t ldx, const float *
 // and the workgroup-per-row kernel has the shorter critical path.
 constexpr int64_t kWaveKernelMinRows = 1024;   // measured: 3.3 - 4.8 us against 4.2 - 5.9 us up to 512 rows, equal at 1024
 
-template <bool HAS_PRE, bool F6>
+template <bool HAS_PRE, bool F6, bool MASKED = false>
 hipError_t launch_wave4096(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip, float post_scale,
-                           uint8_t *Q, float *scale_out, hipStream_t st)
+                           uint8_t *Q, float *scale_out, hipStream_t st, uint32_t had_mask = 0xFFFFFFFFu)
 {
     constexpr size_t lds = 4 * (4096 + (F6 ? 576 : 64)) * sizeof(float);
     const unsigned blocks = F6 ? (unsigned)((rows + 63) / 64 * 16) : (unsigned)((rows + 3) / 4);
-    auto kern = fwht4096_wave_kernel<HAS_PRE, F6>;
+    auto kern = fwht4096_wave_kernel<HAS_PRE, F6, MASKED>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, static_cast<const __half *>(X), ldx, rows, pre, clip,
-                       post_scale, Q, scale_out);
+                       post_scale, Q, scale_out, had_mask);
     return hipGetLastError();
 }
 
@@ -440,6 +444,13 @@ hipError_t launch_fwht_quant_ex(const void *X, int64_t rows, int64_t K, int64_t 
                                 float clip, float post_scale, uint8_t *Q, float *scale_out,
                                 const RowExtras &ex, hipStream_t st, bool f6)
 {
+    // head-wise transform of many rows of 4096: the wave-per-row kernel with the unselected butterflies skipped
+    if (K == 4096 && !ex.gate && ex.n_grid == 0 && rows > kWaveKernelMinRows) {
+        if (pre) return f6 ? launch_wave4096<true, true, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, ex.had_mask)
+                           : launch_wave4096<true, false, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, ex.had_mask);
+        return f6 ? launch_wave4096<false, true, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, ex.had_mask)
+                  : launch_wave4096<false, false, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, ex.had_mask);
+    }
     // the gate alone (the FFN down-projection input) goes through the plain kernel: fewer passes over the row
     // than the general kernel below (K = 14336, 2048 rows: 52 against 68 us)
     if (ex.gate && ex.n_grid == 0 && (ex.had_mask == 0xFFFFFFFFu || !is_pow2(K))) {

@@ -90,6 +90,23 @@ def test_heads(gpu, K, nh, across):
     check_codes(o.unpack_int4(Xq.cpu().numpy()), ref["codes"], ref["t"])
 
 
+@pytest.mark.parametrize("nh", [32, 2, 512, 1])
+@pytest.mark.parametrize("across", [True, False])
+@pytest.mark.parametrize("smooth", [True, False])
+def test_heads_many_rows_of_4096(gpu, nh, across, smooth):
+    """More than 1024 rows of 4096: the head-wise transform runs in the wave-per-row kernel (a ragged row count,
+    heads that split the register bits of both of its phases)."""
+    M, K = 1029, 4096
+    rng = np.random.default_rng(nh + 7 * across)
+    X = wl.to_f16_sat(rng.standard_normal((M, K)).astype(np.float32) * (1 + 300 * (rng.random(K) < 0.002)))
+    inv_s = np.exp(rng.standard_normal(K) * 0.5).astype(np.float32) if smooth else None
+    Xq, xs = gpu.sr_fwht_quant_act_heads(dev(X), nh, across, None if inv_s is None else dev(inv_s), 0.9)
+    torch.cuda.synchronize()
+    ref = o.fwht_quant_act_heads(X, nh, across, inv_s, 0.9)
+    check_scales(xs.cpu().numpy(), ref["x_scale"])
+    check_codes(o.unpack_int4(Xq.cpu().numpy()), ref["codes"], ref["t"])
+
+
 def test_heads_unit_vectors(gpu):
     """X = 3 e_k, clip 1: codes are 7 * (row k of the head-wise matrix), zero outside its support."""
     K, nh = 4096, 32
