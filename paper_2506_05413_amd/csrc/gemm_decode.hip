@@ -210,8 +210,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_decode_kernel(const uint8_t *__r
 // resident activation fragments (row = token) in the matrix pipe: every entry of the 16 x 16
 // product is used.  Per weight load this leaves 12 vector-ALU instructions and no activation
 // traffic at all, where the kernel above re-reads and re-widens the activations in every
-// workgroup.  The waves' partial sums are integers and are added into LDS with ds_add
-// (exact, order-free).
+// workgroup.  Every wave leaves its integer partial sums in LDS as they are (16 bytes per lane)
+// and the first waves add the 16 copies (exact, order-free; measured against ds_add into one
+// copy: 8.1 -> 7.9 us at 16 tokens, and nothing to clear).
 // Units of one 128-byte output line go to workgroups of the same XCD (blockIdx & 7), so that
 // a line of Y is assembled in one L2.
 // ------------------------------------------------------------------------------------------
@@ -223,7 +224,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_stream_kernel(const uint8_t 
 {
     constexpr int NW = 16, XROW = 144, PAIRS = (UPW + 1) / 2;
     static_assert(UPW <= 8, "one output per thread and pass");
-    __shared__ int red[PAIRS][4][64];
+    extern __shared__ __attribute__((aligned(16))) v4i red[];          // [NW][PAIRS][64]: a wave's accumulators as they are
     __shared__ __attribute__((aligned(16))) uint8_t stage[NW][2][8 * XROW];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r8 = lane >> 3, chunk = (lane & 7) * 16;      // load order: row of the piece, byte offset inside a slab
@@ -248,19 +249,19 @@ __global__ __launch_bounds__(1024) void gemm_decode_stream_kernel(const uint8_t 
         unpack16(h0, f[0][0], f[0][1]);
         unpack16(h1, f[1][0], f[1][1]);
     };
-    // this thread's output of a pass: token om, unit slot oj, channel orow of the unit
-    const int orow = threadIdx.x & 7, oj = (threadIdx.x >> 3) % UPW, om = threadIdx.x / (8 * UPW);
+    // Outputs of a pass: thread (q = t >> 6, l = t & 63) of the first PAIRS waves adds the 16 waves' copies of
+    // accumulator lane l of pair q.  Entry [i][tok] (operand row i, token tok) sits in lane tok + 16 (i >> 2),
+    // register i & 3: the thread owns token l & 15 and the four channels 4 ((l >> 4) & 1) .. + 3 of unit slot
+    // 2 q + (l >> 5).
+    const int oq = threadIdx.x >> 6, om = lane & 15, oj = 2 * oq + (lane >> 5), orow = 4 * ((lane >> 4) & 1);
 
     for (int e0 = wg; unit_of(e0) < units; e0 += WGX * UPW) {
-        // red[] is cleared here; the barrier that separates this from the additions waits until the wave is done
-        // with its weights (one placed after the loads would hold every wave until most of the weights have
-        // arrived: the CU accepts loads only as fast as earlier ones return)
-        for (int t = threadIdx.x; t < PAIRS * 256; t += NW * 64) (&red[0][0][0])[t] = 0;
         const int ou = unit_of(e0 + oj * WGX), on = 8 * ou + orow;
-        const bool ovalid = om < M && ou < units;
+        const bool ovalid = oq < PAIRS && oj < UPW && om < M && ou < units;
         // dequantisation factors, fetched ahead of the weights and multiplied only at the end (a product taken
         // here would make the wave wait for them before it issues its weight loads)
-        const float fx = (ovalid && !out_i32) ? xs[om] : 0.f, fw = (ovalid && !out_i32) ? ws[on] : 0.f;
+        const float fx = (ovalid && !out_i32) ? xs[om] : 0.f;
+        const float4 fw = (ovalid && !out_i32) ? *reinterpret_cast<const float4 *>(ws + on) : make_float4(0.f, 0.f, 0.f, 0.f);
 
         const uint8_t *wrow[UPW];
 #pragma unroll
@@ -313,20 +314,28 @@ __global__ __launch_bounds__(1024) void gemm_decode_stream_kernel(const uint8_t 
                 }
         }
 
-        // accumulator entry [i][t] (operand row i, token t) sits in lane t + 16 (i >> 2), register i & 3
-        __syncthreads();
+        // every wave leaves its accumulators in LDS as they are (16 bytes per lane and pair, no atomics, nothing
+        // to clear); the outputs are summed by the first PAIRS waves
 #pragma unroll
-        for (int q = 0; q < PAIRS; ++q)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) atomicAdd(&red[q][v][lane], acc[q][v]);
+        for (int q = 0; q < PAIRS; ++q) red[(wave * PAIRS + q) * 64 + lane] = acc[q];
         __syncthreads();
         if (ovalid) {
-            const int i = 8 * (oj & 1) + orow;
-            const int sum = red[oj >> 1][i & 3][om + 16 * (i >> 2)] >> 8;      // both operands carried the factor 16
-            if (out_i32) static_cast<int32_t *>(Yv)[(int64_t)om * ldy + on] = sum;
-            else static_cast<__half *>(Yv)[(int64_t)om * ldy + on] = __float2half_rn((float)sum * fx * fw);
+            v4i sum = red[oq * 64 + lane];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) sum += red[(w * PAIRS + oq) * 64 + lane];
+            sum >>= 8;                                      // both operands carried the factor 16
+            if (out_i32) {
+                *reinterpret_cast<v4i *>(static_cast<int32_t *>(Yv) + (int64_t)om * ldy + on) = sum;
+            } else {
+                union { __half h[4]; uint2 u; } o;
+                o.h[0] = __float2half_rn((float)sum[0] * fx * fw.x);
+                o.h[1] = __float2half_rn((float)sum[1] * fx * fw.y);
+                o.h[2] = __float2half_rn((float)sum[2] * fx * fw.z);
+                o.h[3] = __float2half_rn((float)sum[3] * fx * fw.w);
+                *reinterpret_cast<uint2 *>(static_cast<__half *>(Yv) + (int64_t)om * ldy + on) = o.u;
+            }
         }
-        __syncthreads();                                    // red[] is cleared again by the next pass
+        __syncthreads();                                    // red[] is written again by the next pass
     }
 }
 
@@ -439,8 +448,13 @@ template <int SPW, int UPW>
 hipError_t launch_stream(const uint8_t *Xq, const float *xs, const uint8_t *Wq, const float *ws, int64_t M, int64_t N,
                          int64_t K, void *Y, int64_t ldy, int out_i32, int wgx, hipStream_t st)
 {
-    hipLaunchKernelGGL((gemm_decode_stream_kernel<SPW, UPW>), dim3(8 * wgx), dim3(1024), 0, st, Xq, xs, Wq, ws, (int)M,
-                       (int)N, (int)K, Y, ldy, out_i32);
+    auto kern = gemm_decode_stream_kernel<SPW, UPW>;
+    constexpr int lds = 16 * ((UPW + 1) / 2) * 64 * 16;               // the waves' accumulators
+    if (lds > 32 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, dim3(8 * wgx), dim3(1024), lds, st, Xq, xs, Wq, ws, (int)M, (int)N, (int)K, Y, ldy, out_i32);
     return hipGetLastError();
 }
 
@@ -479,11 +493,13 @@ hipError_t launch_gemm_decode(const uint8_t *Xq, const float *xs, const uint8_t 
         if (M <= 1) return launch_dot<1, 4, 1>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
         return launch_dot<2, 4, 2>(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
     }
-    // The streaming kernel wins wherever a wave can keep its whole share of K in registers (K <= 8192), except
-    // with few tokens and so many channels that a workgroup per 16 channels fills the chip several times over
-    // (4096 -> 14336: 7.0 against 7.9 us for M <= 8; at 16 tokens 8.0 against 8.7 us the other way round).
+    // The streaming kernel wins where every one of its 16 waves has a slab of K (K >= 4096) and a wave can keep
+    // its whole share of K in registers (K <= 8192), except with few tokens and so many channels that a workgroup
+    // per 16 channels fills the chip several times over (4096 -> 14336: 6.7 against 7.7 us for M <= 8; at 16
+    // tokens 8.2 against 7.9 us the other way round).  Shorter rows leave waves idle (1024 -> 14336 at 16 tokens:
+    // 6.0 against 4.5 us).
     const bool few_tokens_many_channels = M <= 8 && nslab <= 16 && N >= 8192;
-    if (force == 3 || (force == 0 && nslab <= 32 && !few_tokens_many_channels))
+    if (force == 3 || (force == 0 && nslab >= 16 && nslab <= 32 && !few_tokens_many_channels))
         return launch_stream_any(Xq, xs, Wq, ws, M, N, K, Y, ldy, out_i32, st);
 
     const unsigned blocks = (unsigned)(N / 16);
