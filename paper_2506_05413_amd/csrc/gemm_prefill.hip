@@ -68,8 +68,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_w4a4_kernel(
     const float *__restrict__ ws, int M, int N, int K, void *__restrict__ Yv, int64_t ldy, int out_i32,
     int tiles_m, int tiles_n, int xcd_m)
 {
-    constexpr int STAGES = 2;
-    constexpr int NWAVE = WGM * WGN;
+    constexpr int NWAVE = WGM * WGN;                 // (two ring stages of LDS)
     constexpr int WM = BM / WGM, WN = BN / WGN;      // wave tile
     constexpr int FM = WM / 32, FN = WN / 32;        // 32 x 32 MFMA tiles per wave
     constexpr int REGIONS = (BM + BN) / 8;           // 1 KB DMA regions (8 rows x 128 B) per stage
