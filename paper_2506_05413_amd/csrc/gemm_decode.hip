@@ -450,10 +450,9 @@ hipError_t launch_stream(const uint8_t *Xq, const float *xs, const uint8_t *Wq, 
 {
     auto kern = gemm_decode_stream_kernel<SPW, UPW>;
     constexpr int lds = 16 * ((UPW + 1) / 2) * 64 * 16;               // the waves' accumulators
-    if (lds > 32 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-    }
+    // with the 36 KB of static staging buffers the workgroup needs up to 100 KB of LDS
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(8 * wgx), dim3(1024), lds, st, Xq, xs, Wq, ws, (int)M, (int)N, (int)K, Y, ldy, out_i32);
     return hipGetLastError();
 }
