@@ -330,12 +330,29 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
     }
 }
 
-template <int K, bool F6 = false>
+template <int K, bool F6 = false, int NT_FORCE = 0>
 hipError_t launch_one(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip,
                       float post_scale, uint8_t *Q, float *scale_out, hipStream_t st)
 {
     constexpr int groups = K / 16;
-    constexpr int NT = groups >= 256 ? 256 : (groups >= 128 ? 128 : 64);
+    constexpr int NT = NT_FORCE ? NT_FORCE : (groups >= 256 ? 256 : (groups >= 128 ? 128 : 64));
+    // Long rows: more threads per row where they pay (measured, one row / 2048 rows, 256 threads against the
+    // choice below).  K = 8192: 5.6 -> 4.1 us / 19.2 -> 16.3 us; 16384: 9.0 -> 6.0 / 46.6 -> 34.4; 28672 (one
+    // workgroup per CU whatever its size): 23.5 -> 9.7 / 257 -> 87; 32768: 24.9 -> 19.9 / 276 -> 222.  K = 14336
+    // and 7168 only while every row still has a CU to itself (14336: 8.0 -> 6.9 us for one row, 9.7 -> 8.2 for 256,
+    // but 42 -> 57 us for 2048: in its Paley pass only 256 threads have work, and two small workgroups per CU
+    // overlap better than one large one).
+    if constexpr (NT_FORCE == 0) {
+        if constexpr (K == 8192) return launch_one<K, F6, 512>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
+        if constexpr (K == 16384 || K == 28672 || K == 32768)
+            return launch_one<K, F6, 1024>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
+        if constexpr (K == 14336) {
+            if (rows <= 256) return launch_one<K, F6, 512>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
+        }
+        if constexpr (K == 7168) {
+            if (rows <= 512) return launch_one<K, F6, 512>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
+        }
+    }
     constexpr size_t lds = sizeof(float) * padded_len(K);
     auto kern = fwht_quant_kernel<K, NT, F6>;
     if (lds > 48 * 1024) {

@@ -57,6 +57,16 @@ def test_every_supported_order(gpu, K):
     compare(gpu, X, inv_s, 0.9, what="K=%d" % K)
 
 
+@pytest.mark.parametrize("K,M", [(7168, 3), (7168, 520), (14336, 200), (14336, 300), (8192, 70), (16384, 40), (28672, 20), (32768, 20)])
+def test_long_rows_both_workgroup_sizes(gpu, K, M):
+    """Long rows run with 256, 512 or 1024 threads per row, for K = 7168 and 14336 depending on the row count
+    (512 / 256 rows is where the launcher switches): every choice against the oracle."""
+    rng = np.random.default_rng(K + M)
+    X = wl.to_f16_sat(rng.standard_normal((M, K)).astype(np.float32) * (1 + 200 * (rng.random(K) < 0.002)))
+    inv_s = np.exp(rng.standard_normal(K) * 0.5).astype(np.float32)
+    compare(gpu, X, inv_s, 0.9, what="K=%d M=%d" % (K, M))
+
+
 @pytest.mark.parametrize("K", [64, 512, 4096, 448, 14336])
 def test_unit_vectors_reproduce_rows_of_H(gpu, K):
     """X = c * e_k with clip = 1: y = c * H[k], so every code is exactly 7 * H[k][j] and Delta = c / 7.
