@@ -368,12 +368,23 @@ hipError_t launch_one(const void *X, int64_t rows, int64_t ldx, const float *pre
 }
 
 // silu(gate) * x in front of the plain kernel (no head mask, no clip search)
-template <int K, bool F6 = false>
+template <int K, bool F6 = false, int NT_FORCE = 0>
 hipError_t launch_one_gated(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip, float post_scale,
                             uint8_t *Q, float *scale_out, const __half *gate, int64_t ldg, hipStream_t st)
 {
     constexpr int groups = K / 16;
-    constexpr int NT = groups >= 256 ? 256 : (groups >= 128 ? 128 : 64);
+    constexpr int NT = NT_FORCE ? NT_FORCE : (groups >= 256 ? 256 : (groups >= 128 ? 128 : 64));
+    if constexpr (NT_FORCE == 0) {                          // threads per row as in launch_one
+        if constexpr (K == 8192) return launch_one_gated<K, F6, 512>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, gate, ldg, st);
+        if constexpr (K == 16384 || K == 28672)
+            return launch_one_gated<K, F6, 1024>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, gate, ldg, st);
+        if constexpr (K == 14336) {
+            if (rows <= 256) return launch_one_gated<K, F6, 512>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, gate, ldg, st);
+        }
+        if constexpr (K == 7168) {
+            if (rows <= 512) return launch_one_gated<K, F6, 512>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, gate, ldg, st);
+        }
+    }
     constexpr size_t lds = sizeof(float) * padded_len(K);
     auto kern = fwht_quant_kernel<K, NT, F6, true>;
     if (lds > 48 * 1024) {
