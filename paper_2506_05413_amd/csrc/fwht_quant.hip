@@ -339,14 +339,15 @@ hipError_t launch_one(const void *X, int64_t rows, int64_t ldx, const float *pre
     // Long rows: more threads per row where they pay (measured, one row / 2048 rows, 256 threads against the
     // choice below).  K = 8192: 5.6 -> 4.1 us / 19.2 -> 16.3 us; 16384: 9.0 -> 6.0 / 46.6 -> 34.4; 28672 (one
     // workgroup per CU whatever its size): 23.5 -> 9.7 / 257 -> 87; 32768: 24.9 -> 19.9 / 276 -> 222.  K = 14336
-    // and 7168 only while every row still has a CU to itself (14336: 8.0 -> 6.9 us for one row, 9.7 -> 8.2 for 256,
-    // but 42 -> 57 us for 2048: in its Paley pass only 256 threads have work, and two small workgroups per CU
-    // overlap better than one large one).
+    // and 7168 only while every row still has a CU to itself (14336: 8.0 -> 6.1 us for one row with 1024 threads,
+    // 9.7 -> 7.9 us for 256 rows with 512, but 42 -> 57 us for 2048 rows: two small workgroups per CU overlap
+    // better than one large one).
     if constexpr (NT_FORCE == 0) {
         if constexpr (K == 8192) return launch_one<K, F6, 512>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
         if constexpr (K == 16384 || K == 28672 || K == 32768)
             return launch_one<K, F6, 1024>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
         if constexpr (K == 14336) {
+            if (rows <= 64) return launch_one<K, F6, 1024>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
             if (rows <= 256) return launch_one<K, F6, 512>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
         }
         if constexpr (K == 7168) {

@@ -336,7 +336,8 @@ __device__ __forceinline__ float rotate_loaded_row_absmax(const RowLoad<K, NT> &
         // K = 16 cannot occur (K >= 64); kept for completeness of the template
     }
     // a single leftover bit of the power-of-two part is folded into the Paley pass (56 values per group)
-    constexpr bool MERGE = KRON && ((LOGP - 4) % 4 == 1);
+    // (with more than 256 threads per row the merged pass would leave most of them idle: 28 values per thread then)
+    constexpr bool MERGE = KRON && ((LOGP - 4) % 4 == 1) && NT <= 256;
     lds_passes<K, NT, 4, MERGE ? LOGP - 1 : LOGP, !KRON>(row, t, amax);
 
     // ---- Paley factor: 28 values at stride P2 per group ---------------------------------
