@@ -380,6 +380,7 @@ hipError_t launch_one_gated(const void *X, int64_t rows, int64_t ldx, const floa
         if constexpr (K == 16384 || K == 28672)
             return launch_one_gated<K, F6, 1024>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, gate, ldg, st);
         if constexpr (K == 14336) {
+            if (rows <= 64) return launch_one_gated<K, F6, 1024>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, gate, ldg, st);
             if (rows <= 256) return launch_one_gated<K, F6, 512>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, gate, ldg, st);
         }
         if constexpr (K == 7168) {
