@@ -40,7 +40,7 @@ def test_swiglu_orders(gpu, K):
     compare_swiglu(gpu, G, U, None, 1.0, "K=%d no inv_s" % K)
 
 
-@pytest.mark.parametrize("K,M", [(14336, 300), (7168, 600), (7168, 4), (8192, 5), (16384, 3), (28672, 2), (2048, 9), (1024, 3)])
+@pytest.mark.parametrize("K,M", [(14336, 300), (14336, 100), (14336, 3), (7168, 600), (7168, 4), (8192, 5), (16384, 3), (28672, 2), (2048, 9), (1024, 3)])
 def test_swiglu_thread_counts(gpu, K, M):
     """The gated prologue on the plain row kernel, with every number of threads per row its launcher picks
     (K = 14336 above 256 rows and K = 7168 above 512 rows: 256 threads; fewer rows, and the longer rows: 512 or 1024)."""
