@@ -144,8 +144,9 @@ def main():
 
     # ---------------- timed region: exactly `steps` steps -------------------------------
     # HIP events bracket the dominant kernel (the N = 14336 GEMM), on the stream it runs on,
-    # on every third step (an event pair costs the stream a microsecond or two; 3 is coprime with the 8 input sets)
-    EV_EVERY = 3
+    # on every eleventh step (an event pair costs the stream a microsecond or two, which is inside the timed region;
+    # 11 is coprime with the 8 input sets, so the samples walk over all of them)
+    EV_EVERY = 11
     gemm_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
                for _ in range((args.steps + EV_EVERY - 1) // EV_EVERY)]
     torch.cuda.synchronize()
