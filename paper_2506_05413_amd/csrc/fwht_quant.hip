@@ -140,15 +140,12 @@ __global__ __launch_bounds__(NT) void fwht_quant_ex_kernel(const __half *__restr
     if constexpr (KRON) {
         for (int g = t; g < P2; g += NT) {
             float v[28], o[28];
-            float S = 0.f;
+            float *col = row + pad(g);
 #pragma unroll
-            for (int i = 0; i < 28; ++i) {
-                v[i] = row[pad(g + i * P2)];
-                S += v[i];
-            }
-            h28_apply(v, o, S, std::make_integer_sequence<int, 28>{});
+            for (int i = 0; i < 28; ++i) v[i] = col[strided<P2>(g, i)];
+            h28_program(v, o);
 #pragma unroll
-            for (int j = 0; j < 28; ++j) row[pad(g + j * P2)] = o[j];
+            for (int j = 0; j < 28; ++j) col[strided<P2>(g, j)] = o[j];
         }
         __syncthreads();
     }

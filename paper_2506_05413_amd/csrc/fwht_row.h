@@ -5,6 +5,7 @@
 #pragma once
 
 #include "sr_common.h"
+#include "h28_program.h"
 
 #include <hip/hip_fp16.h>
 #include <utility>
@@ -48,40 +49,21 @@ constexpr int h28_sign(int i, int j)
     if (i == j) return 1;
     return gf27_is_square(gf27_sub(i - 1, j - 1)) ? 1 : -1;
 }
-// bit i set  <=>  H28[i][j] == -1
-constexpr uint32_t h28_neg_mask(int j)
+// The product itself is the generated straight-line program of h28_program.h (242 additions with shared partial
+// sums; "row sum minus twice the negative terms" took 419).  It must reproduce the matrix built above: checked
+// here on the 28 unit vectors, in integers, at compile time.
+constexpr bool h28_program_matches()
 {
-    uint32_t m = 0;
-    for (int i = 0; i < 28; ++i)
-        if (h28_sign(i, j) < 0) m |= 1u << i;
-    return m;
-}
-constexpr int popc(uint32_t v) { int c = 0; for (; v; v &= v - 1) ++c; return c; }
-
-template <int J>
-__device__ __forceinline__ float h28_col(const float (&v)[28], float S)
-{
-    constexpr uint32_t neg = h28_neg_mask(J);
-    if constexpr (popc(neg) <= 14) {
-        float n = 0.f;
-#pragma unroll
-        for (int i = 0; i < 28; ++i)
-            if ((neg >> i) & 1u) n += v[i];
-        return fmaf(-2.f, n, S);
-    } else {
-        float p = 0.f;
-#pragma unroll
-        for (int i = 0; i < 28; ++i)
-            if (!((neg >> i) & 1u)) p += v[i];
-        return fmaf(2.f, p, -S);
+    for (int i = 0; i < 28; ++i) {
+        int e[28] = {}, o[28] = {};
+        e[i] = 1;
+        h28_program(e, o);
+        for (int j = 0; j < 28; ++j)
+            if (o[j] != h28_sign(i, j)) return false;
     }
+    return true;
 }
-template <int... J>
-__device__ __forceinline__ void h28_apply(const float (&v)[28], float (&o)[28], float S,
-                                          std::integer_sequence<int, J...>)
-{
-    ((o[J] = h28_col<J>(v, S)), ...);
-}
+static_assert(h28_program_matches(), "h28_program.h does not compute the Paley matrix of this file");
 
 // ---- radix-2 butterflies on 2^B register values -----------------------------------
 template <int B>
@@ -102,6 +84,14 @@ __device__ __forceinline__ void butterflies(float (&v)[1 << B])
 
 __device__ __forceinline__ int pad(int i) { return i + ((i >> 6) << 2); }
 constexpr int padded_len(int K) { return K + (K >> 6) * 4; }
+// pad(g + i * P) - pad(g): a compile-time constant where P is a multiple of 64 (one base register and immediate
+// offsets for a column of values P apart; written out, the compiler spends four integer instructions per access)
+template <int P>
+__device__ __forceinline__ int strided(int g, int i)
+{
+    if constexpr (P % 64 == 0) return i * (P + P / 16);
+    else return pad(g + i * P) - pad(g);
+}
 
 constexpr int ilog2(int64_t v) { int l = 0; while ((int64_t(1) << (l + 1)) <= v) ++l; return l; }
 
@@ -345,25 +335,23 @@ __device__ __forceinline__ float rotate_loaded_row_absmax(const RowLoad<K, NT> &
         constexpr int HALF = P2 / 2;
         for (int g = t; g < HALF; g += NT) {
             float a[28], b[28], o[28];
-            float Sa = 0.f, Sb = 0.f;
+            float *lo_p = row + pad(g), *hi_p = row + pad(g + HALF);
 #pragma unroll
             for (int i = 0; i < 28; ++i) {
-                const float lo = row[pad(g + i * P2)], hi = row[pad(g + HALF + i * P2)];
+                const float lo = lo_p[strided<P2>(g, i)], hi = hi_p[strided<P2>(g + HALF, i)];
                 a[i] = lo + hi;
                 b[i] = lo - hi;
-                Sa += a[i];
-                Sb += b[i];
             }
-            h28_apply(a, o, Sa, std::make_integer_sequence<int, 28>{});
+            h28_program(a, o);
 #pragma unroll
             for (int j = 0; j < 28; ++j) {
-                row[pad(g + j * P2)] = o[j];
+                lo_p[strided<P2>(g, j)] = o[j];
                 amax = fmaxf(amax, fabsf(o[j]));
             }
-            h28_apply(b, o, Sb, std::make_integer_sequence<int, 28>{});
+            h28_program(b, o);
 #pragma unroll
             for (int j = 0; j < 28; ++j) {
-                row[pad(g + HALF + j * P2)] = o[j];
+                hi_p[strided<P2>(g + HALF, j)] = o[j];
                 amax = fmaxf(amax, fabsf(o[j]));
             }
         }
@@ -371,16 +359,13 @@ __device__ __forceinline__ float rotate_loaded_row_absmax(const RowLoad<K, NT> &
     } else if constexpr (KRON) {
         for (int g = t; g < P2; g += NT) {
             float v[28], o[28];
-            float S = 0.f;
+            float *col = row + pad(g);
 #pragma unroll
-            for (int i = 0; i < 28; ++i) {
-                v[i] = row[pad(g + i * P2)];
-                S += v[i];
-            }
-            h28_apply(v, o, S, std::make_integer_sequence<int, 28>{});
+            for (int i = 0; i < 28; ++i) v[i] = col[strided<P2>(g, i)];
+            h28_program(v, o);
 #pragma unroll
             for (int j = 0; j < 28; ++j) {
-                row[pad(g + j * P2)] = o[j];
+                col[strided<P2>(g, j)] = o[j];
                 amax = fmaxf(amax, fabsf(o[j]));
             }
         }
