@@ -266,3 +266,30 @@ def test_f6_calls_reject_bad_arguments():
     assert gemm(xs=None) == sr.SR_ERR_NULL
     assert gemm(ldy=68) == sr.SR_ERR_ALIGN
     assert gemm(W6=A + 1) == sr.SR_ERR_ALIGN
+
+
+def test_generated_h28_program_is_the_oracles_paley_matrix():
+    """The kernels multiply by H28 with a generated list of additions (csrc/h28_program.h).  Read as
+    text and evaluated in integers on the 28 unit vectors, it must give the oracle's Paley matrix
+    (paper: online Hadamard of the down-projection input, 14336 = 28 * 512), entry by entry."""
+    import numpy as np
+    from oracle import smoothrot_oracle as orc
+
+    text = open(os.path.join(ROOT, "paper_2506_05413_amd", "csrc", "h28_program.h")).read()
+    shared = re.findall(r"const T (w\d+) = (\S+) ([+-]) (\S+);", text)
+    outs = re.findall(r"o\[(\d+)\] = (.+);", text)
+    assert len(outs) == 28 and sorted(int(j) for j, _ in outs) == list(range(28))
+
+    H = np.zeros((28, 28), dtype=np.int64)
+    n_ops = len(shared)
+    for i in range(28):
+        val = {"v[%d]" % k: int(k == i) for k in range(28)}
+        for name, a, op, b in shared:
+            val[name] = val[a] + val[b] if op == "+" else val[a] - val[b]
+        for j, expr in outs:
+            terms = re.findall(r"([+-]?)\s*(v\[\d+\]|w\d+)", expr)
+            H[i, int(j)] = sum(-val[t] if sg == "-" else val[t] for sg, t in terms)
+            if i == 0:
+                n_ops += len(terms) - 1
+    assert np.array_equal(H, orc.paley28())
+    assert n_ops < 28 * 14                     # fewer additions than "row sum minus twice the negative terms"
