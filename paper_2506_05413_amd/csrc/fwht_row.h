@@ -287,22 +287,28 @@ __device__ __forceinline__ float rotate_loaded_row_absmax(const RowLoad<K, NT> &
     for (int i = 0; i < RowLoad<K, NT>::NG; ++i) {
         const int g = t + i * NT;
         if (g < K / 16) {
-            union { uint4 u[2]; __half h[16]; } raw;
+            typedef _Float16 half2v __attribute__((ext_vector_type(2)));   // element access selects the half in the instruction
+            union { uint4 u[2]; half2v h[8]; } raw;
             raw.u[0] = ld.u[i][0];
             raw.u[1] = ld.u[i][1];
             float v[16];
-#pragma unroll
-            for (int e = 0; e < 16; ++e) v[e] = __half2float(raw.h[e]);
             if constexpr (GATE) {
-                union { uint4 u[2]; __half h[16]; } graw;
+                union { uint4 u[2]; half2v h[8]; } graw;
                 graw.u[0] = ld.gu[i][0];
                 graw.u[1] = ld.gu[i][1];
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const float gv = __half2float(graw.h[e]);
-                    // silu(g) = g / (1 + exp(-g)); exp(-g) = inf for very negative g gives g * 0 = -0
-                    v[e] *= gv * __builtin_amdgcn_rcpf(1.f + __expf(-gv));
+                    // silu(g) = g / (1 + exp(-g)); exp(-g) = inf for very negative g gives g * 0 = 0.
+                    // Each product of a half with a float is written as an FMA with a zero addend: that form
+                    // compiles to one mixed-precision FMA reading the half in place, where a plain product
+                    // costs a conversion (and a shift for the upper half of a dword) on top.
+                    const _Float16 gh = graw.h[e >> 1][e & 1];
+                    const float sig = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(__builtin_fmaf((float)gh, -1.44269504088896341f, 0.f)));
+                    v[e] = __builtin_fmaf((float)raw.h[e >> 1][e & 1], __builtin_fmaf((float)gh, sig, 0.f), 0.f);
                 }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) v[e] = (float)raw.h[e >> 1][e & 1];
             }
             if (pre) {
 #pragma unroll
