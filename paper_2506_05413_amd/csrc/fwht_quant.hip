@@ -256,22 +256,46 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
     const __half *x = X + m * ldx;
 
     // ---- phase 1 --------------------------------------------------------------------------
+    // every load of the row first (the scheduling barrier keeps the compiler from sinking each load to its use,
+    // which serialised the memory round trips), then the arithmetic, chunk by chunk as the data arrives
+    uint4 rx[8];
+    float4 rs[8][2];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        rx[j] = *reinterpret_cast<const uint4 *>(x + 512 * j + 8 * lane);
+        if (HAS_PRE) {
+            rs[j][0] = *reinterpret_cast<const float4 *>(pre + 512 * j + 8 * lane);
+            rs[j][1] = *reinterpret_cast<const float4 *>(pre + 512 * j + 8 * lane + 4);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
     float v[64];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        union { uint4 u; __half h[8]; } raw;
-        raw.u = *reinterpret_cast<const uint4 *>(x + 512 * j + 8 * lane);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[8 * j + e] = __half2float(raw.h[e]);
+        union { uint4 u; half2v h[4]; } raw;
+        raw.u = rx[j];
+        float f[8];
         if (HAS_PRE) {
-            const float4 s0 = *reinterpret_cast<const float4 *>(pre + 512 * j + 8 * lane);
-            const float4 s1 = *reinterpret_cast<const float4 *>(pre + 512 * j + 8 * lane + 4);
-            v[8 * j + 0] *= s0.x; v[8 * j + 1] *= s0.y; v[8 * j + 2] *= s0.z; v[8 * j + 3] *= s0.w;
-            v[8 * j + 4] *= s1.x; v[8 * j + 5] *= s1.y; v[8 * j + 6] *= s1.z; v[8 * j + 7] *= s1.w;
+            const float4 s0 = rs[j][0], s1 = rs[j][1];
+            f[0] = s0.x; f[1] = s0.y; f[2] = s0.z; f[3] = s0.w;
+            f[4] = s1.x; f[5] = s1.y; f[6] = s1.z; f[7] = s1.w;
+        }
+        if constexpr (MASKED) {                         // index bit 0 may be unselected: values as they are
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                v[8 * j + e] = (float)raw.h[e >> 1][e & 1];
+                if (HAS_PRE) v[8 * j + e] *= f[e];
+            }
+        } else {                                        // conversion, factor and index bit 0 in one go
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (HAS_PRE) pair_level(raw.h[e], f[2 * e], f[2 * e + 1], v[8 * j + 2 * e], v[8 * j + 2 * e + 1]);
+                else pair_level(raw.h[e], v[8 * j + 2 * e], v[8 * j + 2 * e + 1]);
+            }
         }
     }
     if constexpr (MASKED) butterflies_masked<6>(v, (had_mask & 7u) | (((had_mask >> 9) & 7u) << 3));   // register bits = index bits 0,1,2,9,10,11
-    else butterflies<6>(v);
+    else butterflies_from<6, 2>(v);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         float *d = buf + 520 * j + 8 * lane;             // element 512 j + 8 l + e lives at 520 j + 8 l + e

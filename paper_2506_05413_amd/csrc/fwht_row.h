@@ -82,6 +82,45 @@ __device__ __forceinline__ void butterflies(float (&v)[1 << B])
     }
 }
 
+// the same, index bit 0 (.., log2 H0 - 1) already done
+template <int B, int H0>
+__device__ __forceinline__ void butterflies_from(float (&v)[1 << B])
+{
+#pragma unroll
+    for (int h = H0; h < (1 << B); h <<= 1) {
+#pragma unroll
+        for (int i = 0; i < (1 << B); ++i) {
+            if (!(i & h)) {
+                float a = v[i], b = v[i | h];
+                v[i] = a + b;
+                v[i | h] = a - b;
+            }
+        }
+    }
+}
+
+// ---- first butterfly level straight from a dword of two halves ------------------------------
+// A product of a half with a float written as an FMA compiles to one mixed-precision FMA that reads the half
+// in place (lower or upper half of the dword selected in the instruction); a plain conversion or product
+// costs an instruction more per value.  For a pair (a, b) with factors (fa, fb):
+//     b' = b fb,   a fa + b',   a fa - b'          three instructions for two values
+// and without factors a * 1 + b, a * 1 - b (exact) with the 1 kept from the optimiser in a scalar register,
+// which would otherwise turn the FMA back into conversions and an addition: two instructions.
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void pair_level(half2v h, float fa, float fb, float &sum, float &dif)
+{
+    const float b = __builtin_fmaf((float)h[1], fb, 0.f);
+    sum = __builtin_fmaf((float)h[0], fa, b);
+    dif = __builtin_fmaf((float)h[0], fa, -b);
+}
+__device__ __forceinline__ void pair_level(half2v h, float &sum, float &dif)
+{
+    float one;
+    asm("s_mov_b32 %0, 1.0" : "=s"(one));
+    sum = __builtin_fmaf((float)h[0], one, (float)h[1]);
+    dif = __builtin_fmaf((float)h[0], one, -(float)h[1]);
+}
+
 __device__ __forceinline__ int pad(int i) { return i + ((i >> 6) << 2); }
 constexpr int padded_len(int K) { return K + (K >> 6) * 4; }
 // pad(g + i * P) - pad(g): a compile-time constant where P is a multiple of 64 (one base register and immediate
@@ -287,37 +326,39 @@ __device__ __forceinline__ float rotate_loaded_row_absmax(const RowLoad<K, NT> &
     for (int i = 0; i < RowLoad<K, NT>::NG; ++i) {
         const int g = t + i * NT;
         if (g < K / 16) {
-            typedef _Float16 half2v __attribute__((ext_vector_type(2)));   // element access selects the half in the instruction
             union { uint4 u[2]; half2v h[8]; } raw;
             raw.u[0] = ld.u[i][0];
             raw.u[1] = ld.u[i][1];
             float v[16];
+            float f[16];                                       // per-element factor: silu(gate) and / or 1 / s
             if constexpr (GATE) {
                 union { uint4 u[2]; half2v h[8]; } graw;
                 graw.u[0] = ld.gu[i][0];
                 graw.u[1] = ld.gu[i][1];
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    // silu(g) = g / (1 + exp(-g)); exp(-g) = inf for very negative g gives g * 0 = 0.
-                    // Each product of a half with a float is written as an FMA with a zero addend: that form
-                    // compiles to one mixed-precision FMA reading the half in place, where a plain product
-                    // costs a conversion (and a shift for the upper half of a dword) on top.
+                    // silu(g) = g / (1 + exp(-g)); exp(-g) = inf for very negative g gives g * 0 = 0
                     const _Float16 gh = graw.h[e >> 1][e & 1];
                     const float sig = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(__builtin_fmaf((float)gh, -1.44269504088896341f, 0.f)));
-                    v[e] = __builtin_fmaf((float)raw.h[e >> 1][e & 1], __builtin_fmaf((float)gh, sig, 0.f), 0.f);
+                    f[e] = __builtin_fmaf((float)gh, sig, 0.f);
                 }
+            }
+            if (GATE || pre) {
+                if (pre) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 sc = ld.p[i][q];
+                        if constexpr (GATE) { f[4 * q] *= sc.x; f[4 * q + 1] *= sc.y; f[4 * q + 2] *= sc.z; f[4 * q + 3] *= sc.w; }
+                        else { f[4 * q] = sc.x; f[4 * q + 1] = sc.y; f[4 * q + 2] = sc.z; f[4 * q + 3] = sc.w; }
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pair_level(raw.h[e], f[2 * e], f[2 * e + 1], v[2 * e], v[2 * e + 1]);
             } else {
 #pragma unroll
-                for (int e = 0; e < 16; ++e) v[e] = (float)raw.h[e >> 1][e & 1];
+                for (int e = 0; e < 8; ++e) pair_level(raw.h[e], v[2 * e], v[2 * e + 1]);
             }
-            if (pre) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 s = ld.p[i][q];
-                    v[4 * q + 0] *= s.x; v[4 * q + 1] *= s.y; v[4 * q + 2] *= s.z; v[4 * q + 3] *= s.w;
-                }
-            }
-            butterflies<4>(v);
+            butterflies_from<4, 2>(v);
             float *dst = row + pad(16 * g);
 #pragma unroll
             for (int q = 0; q < 4; ++q)
