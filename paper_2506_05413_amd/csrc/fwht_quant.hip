@@ -22,8 +22,11 @@ namespace sr {
 namespace {
 
 // F6: Q receives f6 tiles (operands of the FP6-MFMA GEMM) instead of packed nibbles; K % 128 == 0 then.
-template <int K, int NT, bool F6, bool GATE = false>
-__global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict__ X, int64_t ldx, int64_t rows,
+// STREAM: the grid is smaller than the number of rows; a workgroup walks over rows w, w + gridDim.x, .. and
+// fetches its next row while it rotates the current one (gridDim.x % 64 == 0 for F6, so that the row mapping
+// below stays what it is for a grid of one workgroup per row).
+template <int K, int NT, bool F6, bool GATE = false, bool STREAM = false>
+__global__ __launch_bounds__(NT, STREAM ? 2 * NT / 256 : 1) void fwht_quant_kernel(const __half *__restrict__ X, int64_t ldx, int64_t rows,
                                                         const float *__restrict__ pre, float clip,
                                                         float post_scale, uint8_t *__restrict__ Q,
                                                         float *__restrict__ scale_out,
@@ -33,36 +36,76 @@ __global__ __launch_bounds__(NT) void fwht_quant_kernel(const __half *__restrict
     __shared__ float red[NT / 64];
 
     const int t = threadIdx.x;
-    int64_t m = blockIdx.x;
-    if constexpr (F6) {
-        // The eight rows of a tile block (768 contiguous bytes per 128 codes) should be written from ONE XCD at
-        // about the same time, so that its L2 assembles whole lines: workgroups are dealt round-robin to the 8
-        // XCDs, so workgroup w = 8 a + x (XCD x) takes row r = a % 8 of row block 8 (a / 8) + x.
-        const int64_t w = blockIdx.x, x = w & 7, a = w >> 3;
-        m = 64 * (a >> 3) + 8 * x + (a & 7);
-        if (m >= rows) return;                           // the grid is rounded up to a multiple of 64
-    }
-    const float amax = rotate_row_absmax<K, NT, GATE>(X + m * ldx, pre, row, red, t, GATE ? gate + m * ldg : nullptr);
+    // F6: the eight rows of a tile block (768 contiguous bytes per 128 codes) should be written from ONE XCD at
+    // about the same time, so that its L2 assembles whole lines: workgroups are dealt round-robin to the 8
+    // XCDs, so (virtual) workgroup w = 8 a + x (XCD x) takes row r = a % 8 of row block 8 (a / 8) + x.
+    auto row_of = [](int64_t w) -> int64_t {
+        if constexpr (F6) {
+            const int64_t x = w & 7, a = w >> 3;
+            return 64 * (a >> 3) + 8 * x + (a & 7);
+        } else {
+            return w;
+        }
+    };
+    const int64_t total = F6 ? (rows + 63) / 64 * 64 : rows;      // virtual workgroups; F6: some map past the last row
+    auto quantise = [&](int64_t m, float amax) {
+        // Delta = clip * absmax / 7 (1 for an all-zero row), Eq. (1) with the signed range
+        const float delta = (amax == 0.f) ? 1.f : (clip * amax) / 7.f;
+        const float inv_delta = 1.f / delta;
+        if (t == 0) scale_out[m] = (amax == 0.f) ? 1.f : delta * post_scale;
 
-    // Delta = clip * absmax / 7 (1 for an all-zero row), Eq. (1) with the signed range
-    const float delta = (amax == 0.f) ? 1.f : (clip * amax) / 7.f;
-    const float inv_delta = 1.f / delta;
-    if (t == 0) scale_out[m] = (amax == 0.f) ? 1.f : delta * post_scale;
+        if constexpr (F6) {
+            // ---- 32 contiguous values -> one 24-byte piece of a tile (the padding of 4 floats per 64 keeps the
+            // 16-byte reads of 16 neighbouring threads on distinct banks) -----------------------------------------
+            const int64_t row_blocks = (rows + 7) >> 3;
+            for (int p = t; p < K / 32; p += NT) quant_store_f6_piece(row + pad(32 * p), inv_delta, Q, row_blocks, m, p);
+        } else {
+            // ---- quantise 8 contiguous values -> one packed dword ---------------------------------------------
+            uint32_t *q = reinterpret_cast<uint32_t *>(Q + m * (int64_t)(K / 2));
+            for (int c = t; c < K / 8; c += NT) {
+                const float *src = row + pad(8 * c);
+                const float4 a = *reinterpret_cast<const float4 *>(src);
+                const float4 b = *reinterpret_cast<const float4 *>(src + 4);
+                const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+                q[c] = quant_pack8(v, inv_delta);
+            }
+        }
+    };
 
-    if constexpr (F6) {
-        // ---- 32 contiguous values -> one 24-byte piece of a tile (the padding of 4 floats per 64 keeps the
-        // 16-byte reads of 16 neighbouring threads on distinct banks) -----------------------------------------
-        const int64_t row_blocks = (rows + 7) >> 3;
-        for (int p = t; p < K / 32; p += NT) quant_store_f6_piece(row + pad(32 * p), inv_delta, Q, row_blocks, m, p);
+    if constexpr (!STREAM) {
+        const int64_t m = row_of(blockIdx.x);
+        if (m >= rows) return;                           // F6: the grid is rounded up to a multiple of 64
+        const float amax = rotate_row_absmax<K, NT, GATE>(X + m * ldx, pre, row, red, t, GATE ? gate + m * ldg : nullptr);
+        quantise(m, amax);
     } else {
-        // ---- quantise 8 contiguous values -> one packed dword ---------------------------------------------
-        uint32_t *q = reinterpret_cast<uint32_t *>(Q + m * (int64_t)(K / 2));
-        for (int c = t; c < K / 8; c += NT) {
-            const float *src = row + pad(8 * c);
-            const float4 a = *reinterpret_cast<const float4 *>(src);
-            const float4 b = *reinterpret_cast<const float4 *>(src + 4);
-            const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-            q[c] = quant_pack8(v, inv_delta);
+        // (not with a gate row: twice the registers in flight; measured 15 - 25 % slower than one row per
+        // workgroup, also with the prefetch moved behind the Paley pass)
+        static_assert(!GATE, "the walking variant takes no gate row");
+        const int64_t step = gridDim.x;
+        int64_t w = blockIdx.x;
+        while (w < total && row_of(w) >= rows) w += step;
+        if (w >= total) return;
+        RowLoad<K, NT> ld;
+        {
+            const int64_t m = row_of(w);
+            row_load<K, NT, false, GATE>(X + m * ldx, pre, t, ld);
+        }
+        for (;;) {
+            const int64_t m = row_of(w);
+            int64_t wn = w + step;
+            while (wn < total && row_of(wn) >= rows) wn += step;
+            const bool more = wn < total;                // uniform over the workgroup
+            // the next row is requested as soon as this one has left the registers; the smoothing factors,
+            // which come from L2, only after the register-hungry passes
+            const int64_t mn = more ? row_of(wn) : m;
+            const float amax = rotate_loaded_row_absmax<K, NT, GATE>(ld, pre, row, red, t, [&]() {
+                if (more) row_load<K, NT, false, GATE, 1>(X + mn * ldx, pre, t, ld);
+            });
+            if (more) row_load<K, NT, false, GATE, 2>(X + mn * ldx, pre, t, ld);
+            quantise(m, amax);
+            if (!more) break;
+            w = wn;
+            __syncthreads();                             // the row buffer is rewritten by the next first pass
         }
     }
 }
@@ -351,6 +394,34 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
     }
 }
 
+// One workgroup per row -- or, for K = 14336 with 256 threads, no gate row and at least two rounds of rows, as many
+// workgroups as the chip holds at once (the fp32 row in LDS allows two per CU), each walking over rows and
+// fetching its next row while it works on the current one (2048 rows: 36.2 -> 34.4 us, 16384: 264 -> 243 us).
+template <int K, int NT, bool F6, bool GATE>
+hipError_t launch_row_kernel(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip, float post_scale,
+                             uint8_t *Q, float *scale_out, const __half *gate, int64_t ldg, hipStream_t st)
+{
+    constexpr size_t lds = sizeof(float) * padded_len(K);
+    const int64_t total = F6 ? (rows + 63) / 64 * 64 : rows;
+    int64_t grid = total;
+    bool stream = false;
+    if constexpr (K == 14336 && NT == 256 && !GATE) {
+        const int64_t resident = (int64_t)compute_units() * (int64_t)(160 * 1024 / lds) / 64 * 64;
+        stream = resident >= 64 && total >= 2 * resident;
+        if (const char *env = getenv("SMOOTHROT_FWHT_STREAM")) stream = resident >= 64 && atoi(env) != 0;   // tuning aid
+        if (stream) grid = resident < total ? resident : total;
+    }
+    auto kern = stream ? fwht_quant_kernel<K, NT, F6, GATE, (K == 14336 && NT == 256 && !GATE)> : fwht_quant_kernel<K, NT, F6, GATE, false>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, st,
+                       static_cast<const __half *>(X), ldx, rows, pre, clip, post_scale, Q, scale_out, gate, ldg);
+    return hipGetLastError();
+}
+
 template <int K, bool F6 = false, int NT_FORCE = 0>
 hipError_t launch_one(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip,
                       float post_scale, uint8_t *Q, float *scale_out, hipStream_t st)
@@ -375,18 +446,7 @@ hipError_t launch_one(const void *X, int64_t rows, int64_t ldx, const float *pre
             if (rows <= 512) return launch_one<K, F6, 512>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
         }
     }
-    constexpr size_t lds = sizeof(float) * padded_len(K);
-    auto kern = fwht_quant_kernel<K, NT, F6>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
-    const unsigned grid = F6 ? (unsigned)((rows + 63) / 64 * 64) : (unsigned)rows;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st,
-                       static_cast<const __half *>(X), ldx, rows, pre, clip, post_scale, Q, scale_out,
-                       static_cast<const __half *>(nullptr), (int64_t)0);
-    return hipGetLastError();
+    return launch_row_kernel<K, NT, F6, false>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, nullptr, 0, st);
 }
 
 // silu(gate) * x in front of the plain kernel (no head mask, no clip search)
@@ -408,17 +468,7 @@ hipError_t launch_one_gated(const void *X, int64_t rows, int64_t ldx, const floa
             if (rows <= 512) return launch_one_gated<K, F6, 512>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, gate, ldg, st);
         }
     }
-    constexpr size_t lds = sizeof(float) * padded_len(K);
-    auto kern = fwht_quant_kernel<K, NT, F6, true>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
-    const unsigned grid = F6 ? (unsigned)((rows + 63) / 64 * 64) : (unsigned)rows;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st,
-                       static_cast<const __half *>(X), ldx, rows, pre, clip, post_scale, Q, scale_out, gate, ldg);
-    return hipGetLastError();
+    return launch_row_kernel<K, NT, F6, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, gate, ldg, st);
 }
 
 template <int K, bool F6 = false>

@@ -287,7 +287,8 @@ struct RowLoad {
 
 // ALWAYS: threads beyond the row load group 0 instead of nothing, so that the loads sit in straight-line code
 // (for a caller that issues further loads behind these and wants the compiler to count them in its waits).
-template <int K, int NT, bool ALWAYS = false, bool GATE = false>
+// PARTS: 1 = the row (and its gate row), 2 = the values of `pre`, 3 = both
+template <int K, int NT, bool ALWAYS = false, bool GATE = false, int PARTS = 3>
 __device__ __forceinline__ void row_load(const __half *__restrict__ x, const float *__restrict__ pre, const int t,
                                          RowLoad<K, NT> &ld, const __half *__restrict__ gate = nullptr)
 {
@@ -296,15 +297,19 @@ __device__ __forceinline__ void row_load(const __half *__restrict__ x, const flo
         int g = t + i * NT;
         if (ALWAYS) g = g < K / 16 ? g : 0;
         if (g < K / 16) {
-            ld.u[i][0] = *reinterpret_cast<const uint4 *>(x + 16 * g);
-            ld.u[i][1] = *reinterpret_cast<const uint4 *>(x + 16 * g + 8);
-            if constexpr (GATE) {
-                ld.gu[i][0] = *reinterpret_cast<const uint4 *>(gate + 16 * g);
-                ld.gu[i][1] = *reinterpret_cast<const uint4 *>(gate + 16 * g + 8);
+            if constexpr (PARTS & 1) {
+                ld.u[i][0] = *reinterpret_cast<const uint4 *>(x + 16 * g);
+                ld.u[i][1] = *reinterpret_cast<const uint4 *>(x + 16 * g + 8);
+                if constexpr (GATE) {
+                    ld.gu[i][0] = *reinterpret_cast<const uint4 *>(gate + 16 * g);
+                    ld.gu[i][1] = *reinterpret_cast<const uint4 *>(gate + 16 * g + 8);
+                }
             }
-            if (pre) {
+            if constexpr (PARTS & 2) {
+                if (pre) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) ld.p[i][q] = *reinterpret_cast<const float4 *>(pre + 16 * g + 4 * q);
+                    for (int q = 0; q < 4; ++q) ld.p[i][q] = *reinterpret_cast<const float4 *>(pre + 16 * g + 4 * q);
+                }
             }
         }
     }
@@ -312,9 +317,13 @@ __device__ __forceinline__ void row_load(const __half *__restrict__ x, const flo
 
 // GATE: x = silu(gate) * x in fp32 before the smoothing factors (the down-projection input of a gated FFN,
 // paper Fig. 2: sigma(gate) (.) up, then 1/s, Hadamard, quantiser).
-template <int K, int NT, bool GATE = false>
+struct NoHook { __device__ __forceinline__ void operator()() const {} };
+
+// after_pass1: called once the loaded values have been consumed (a caller that walks over several rows issues the
+// loads of its next row there, into the same RowLoad, so that they travel during the rest of this row's work).
+template <int K, int NT, bool GATE = false, typename Hook = NoHook>
 __device__ __forceinline__ float rotate_loaded_row_absmax(const RowLoad<K, NT> &ld, const float *__restrict__ pre,
-                                                          float *row, float *red, const int t)
+                                                          float *row, float *red, const int t, Hook after_pass1 = Hook{})
 {
     constexpr bool KRON = !is_pow2(K);
     constexpr int P2 = KRON ? K / 28 : K;       // power-of-two factor
@@ -365,6 +374,7 @@ __device__ __forceinline__ float rotate_loaded_row_absmax(const RowLoad<K, NT> &
                 *reinterpret_cast<float4 *>(dst + 4 * q) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
         }
     }
+    after_pass1();
     __syncthreads();
 
     // ---- remaining power-of-two bits ---------------------------------------------------

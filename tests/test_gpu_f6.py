@@ -198,6 +198,41 @@ def test_quantiser_tiles_wave_kernel(gpu, M, smooth):
         assert codes.min() >= -8 and codes.max() <= 7
 
 
+@pytest.mark.parametrize("M", [700, 1100])
+def test_row_kernel_walking_over_rows(gpu, monkeypatch, M):
+    """K = 14336 with many rows: as many workgroups as the chip holds, each walking over several rows and
+    fetching its next row while it works (forced here at a row count that leaves workgroups with one, two or
+    three rows and a ragged last tile block).  Same arithmetic as one workgroup per row: every output must
+    equal that launch's bit for bit, and the oracle's under the boundary rule."""
+    K = 14336
+    X = wl.gauss_acts(31 + M, M, K, 3, 300.0)
+    inv_s = np.random.default_rng(M).uniform(0.5, 2.0, K).astype(np.float32)
+    Xd, inv = torch.from_numpy(X).cuda(), torch.from_numpy(inv_s).cuda()
+
+    def run_all():
+        outs = []
+        for pre in (inv, None):
+            outs += list(gpu.sr_fwht_quant_act_f6(Xd, pre, 0.9))
+            outs += list(gpu.sr_fwht_quant_act(Xd, pre, 0.9))
+        torch.cuda.synchronize()
+        return [t.cpu().numpy() for t in outs]
+
+    monkeypatch.setenv("SMOOTHROT_FWHT_STREAM", "0")
+    one = run_all()
+    monkeypatch.setenv("SMOOTHROT_FWHT_STREAM", "1")
+    walk = run_all()
+    for a, b in zip(one, walk):
+        assert np.array_equal(a, b)
+    ref = o.fwht_quant_act(X, inv_s, 0.9)
+    check_scales(walk[1], ref["x_scale"])
+    check_codes(o.f6_codes(o.f6_tiles_unpack(walk[0], M, K)), ref["codes"], ref["t"])
+    check_codes(o.unpack_int4(walk[2]), ref["codes"], ref["t"])
+    ref = o.fwht_quant_act(X, None, 0.9)
+    check_scales(walk[5], ref["x_scale"])
+    check_codes(o.f6_codes(o.f6_tiles_unpack(walk[4], M, K)), ref["codes"], ref["t"])
+    check_codes(o.unpack_int4(walk[6]), ref["codes"], ref["t"])
+
+
 @pytest.mark.parametrize("M,K", [(5, 896), (24, 14336), (9, 4096)])
 def test_gated_prologue_tiles(gpu, M, K):
     """silu(gate) * up fused in front of the rotation, tile output: codes under the boundary rule against the
