@@ -135,10 +135,34 @@ __device__ __forceinline__ int strided(int g, int i)
 constexpr int ilog2(int64_t v) { int l = 0; while ((int64_t(1) << (l + 1)) <= v) ++l; return l; }
 
 // In-LDS pass over index bits [LO, LO+B).
+// Where a thread has at least ~3.4 groups of 2^B values to do, it takes four groups that are neighbours in the low
+// index bits at once: 16-byte LDS accesses instead of 4-byte ones (a quarter of the LDS instructions, four
+// independent butterfly sets in flight; measured inside the K = 14336 kernel: this pass 1.8 -> 1.0 us of a
+// workgroup's 7 us).  Lanes then read 4 q + 272 b floats apart (q = 0..3, b = block of 256): every bank once.
 template <int K, int NT, int LO, int B, bool TRACK>
 __device__ __forceinline__ void lds_pass(float *row, int t, float &amax)
 {
     constexpr int E = 1 << B;
+    if constexpr (LO >= 2 && ((K >> B) * 5 >= NT * 17) && (K >> B) % 4 == 0) {
+        for (int g = t; g < (K >> B) / 4; g += NT) {
+            const int g_low = g & ((1 << (LO - 2)) - 1);
+            const int base = ((g >> (LO - 2)) << (LO + B)) | (g_low << 2);
+            float4 q[E];
+#pragma unroll
+            for (int e = 0; e < E; ++e) q[e] = *reinterpret_cast<const float4 *>(row + pad(base + (e << LO)));
+            float v[4][E];
+#pragma unroll
+            for (int e = 0; e < E; ++e) { v[0][e] = q[e].x; v[1][e] = q[e].y; v[2][e] = q[e].z; v[3][e] = q[e].w; }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) butterflies<B>(v[c]);
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                *reinterpret_cast<float4 *>(row + pad(base + (e << LO))) = make_float4(v[0][e], v[1][e], v[2][e], v[3][e]);
+                if (TRACK) amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v[0][e]), fabsf(v[1][e]))), fmaxf(fabsf(v[2][e]), fabsf(v[3][e])));
+            }
+        }
+        return;
+    }
     for (int g = t; g < (K >> B); g += NT) {
         const int g_low = g & ((1 << LO) - 1);
         const int base = ((g >> LO) << (LO + B)) | g_low;
