@@ -103,6 +103,15 @@ def main():
         extra["calib_absmax"] = {"GB/s": round(M * K * 2 / t / 1e9, 1), "us": round(t * 1e6, 2),
                                  "frac_hbm": round(M * K * 2 / t / 1e9 / PEAK_HBM_GBS, 4),
                                  "workload": "fp16 [2048,4096] chunks, 16 distinct (268 MB)"}
+        # the same kernel on the calibration batch of config 5 (16384 tokens in one call): eight buffers of
+        # 134 MB (the chunks above in eight different orders: 1 GB, well beyond the Infinity Cache)
+        big = [torch.cat([calib[(h + 2 * j) % 16] for j in range(8)]) for h in range(8)]
+        for _ in range(2):
+            t = graph_time(lambda i: sr.sr_calib_absmax(big[i % 8], scratch), 16)
+        extra["calib_absmax_T16384"] = {"GB/s": round(8 * M * K * 2 / t / 1e9, 1), "us": round(t * 1e6, 2),
+                                        "frac_hbm": round(8 * M * K * 2 / t / 1e9 / PEAK_HBM_GBS, 4),
+                                        "workload": "fp16 [16384,4096] per call, 8 distinct (1.07 GB)"}
+        del big
 
     Xs = [torch.from_numpy(wl.cfg2_X(seed=1 + 10 * s)).to(dev) for s in range(SETS)]
     Wq, Ws, W6, inv_s = {}, {}, {}, None

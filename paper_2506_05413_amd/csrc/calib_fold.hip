@@ -26,40 +26,42 @@ __device__ __forceinline__ float half_bits_to_float(unsigned short b)
 
 // Column-wise max |x| over a slab of rows.  |fp16| bit patterns of finite values order
 // like unsigned integers, so the running maximum is kept as packed u16 and is exact.
-// Block = 8 column groups (8 columns each: one 128-byte line per row) x 32 row lanes.  Narrow,
-// tall blocks keep the number of atomics per channel small: the atomics on the K shared
+// Block = CG column groups (8 columns each: CG * 16 contiguous bytes per row) x 256 / CG row lanes.
+// Narrow, tall blocks keep the number of atomics per channel small: the atomics on the K shared
 // addresses, not the reads, were what bounded a wide-block version.
+template <int CG>
 __global__ __launch_bounds__(256) void calib_absmax_kernel(const __half *__restrict__ X, int64_t T, int K,
                                                             int64_t ldx, float *__restrict__ absmax,
                                                             int64_t rows_per_block)
 {
-    __shared__ us8 part[32][8];
-    const int tx = threadIdx.x & 7, ty = threadIdx.x >> 3;
-    const int col = (blockIdx.x * 8 + tx) * 8;
+    constexpr int RL = 256 / CG;                         // row lanes
+    __shared__ us8 part[RL][CG];
+    const int tx = threadIdx.x % CG, ty = threadIdx.x / CG;
+    const int col = (blockIdx.x * CG + tx) * 8;
     const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
     const int64_t r1 = (r0 + rows_per_block < T) ? r0 + rows_per_block : T;
     us8 acc = {0, 0, 0, 0, 0, 0, 0, 0};
     if (col < K) {
         const __half *p = X + col;
         int64_t r = r0 + ty;
-        for (; r + 224 < r1; r += 256) {                 // 8 loads in flight
+        for (; r + RL * 7 < r1; r += RL * 8) {           // 8 loads in flight
             uint4 v[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const uint4 *>(p + (r + 32 * u) * ldx);
+            for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const uint4 *>(p + (r + RL * u) * ldx);
 #pragma unroll
             for (int u = 0; u < 8; ++u) acc = __builtin_elementwise_max(acc, abs_bits(v[u]));
         }
-        for (; r < r1; r += 32)
+        for (; r < r1; r += RL)
             acc = __builtin_elementwise_max(acc, abs_bits(*reinterpret_cast<const uint4 *>(p + r * ldx)));
     }
     part[ty][tx] = acc;
     __syncthreads();
-    for (int s = 16; s >= 1; s >>= 1) {
+    for (int s = RL / 2; s >= 1; s >>= 1) {
         if (ty < s) part[ty][tx] = __builtin_elementwise_max(part[ty][tx], part[ty + s][tx]);
         __syncthreads();
     }
-    if (threadIdx.x < 64) {                              // one channel per thread
-        const int c = (blockIdx.x * 8) * 8 + threadIdx.x;
+    if (threadIdx.x < CG * 8) {                          // one channel per thread
+        const int c = (blockIdx.x * CG) * 8 + threadIdx.x;
         if (c < K) {
             const float f = half_bits_to_float(part[0][threadIdx.x >> 3][threadIdx.x & 7]);
             // non-negative floats order like their bit patterns
@@ -129,19 +131,30 @@ __global__ __launch_bounds__(256) void transpose_f16_kernel(const unsigned short
 
 }  // namespace
 
+template <int CG>
+hipError_t launch_calib(const void *X, int64_t T, int64_t K, int64_t ldx, float *absmax_io, hipStream_t st, int64_t wgs)
+{
+    constexpr int RL = 256 / CG;
+    const unsigned gx = (unsigned)((K + CG * 8 - 1) / (CG * 8));
+    // about `wgs` workgroups, at least one row per row lane each
+    int64_t gy = wgs / gx > 0 ? wgs / gx : 1;
+    if (gy > (T + RL - 1) / RL) gy = (T + RL - 1) / RL;
+    int64_t rpb = (T + gy - 1) / gy;
+    rpb = (rpb + RL - 1) / RL * RL;
+    gy = (T + rpb - 1) / rpb;
+    hipLaunchKernelGGL(calib_absmax_kernel<CG>, dim3(gx, (unsigned)gy), dim3(256), 0, st,
+                       static_cast<const __half *>(X), T, (int)K, ldx, absmax_io, rpb);
+    return hipGetLastError();
+}
+
+// Measured on K = 4096 (TB/s; strips of 128 bytes per row and 1024 workgroups against strips of 256 bytes and
+// 2048 workgroups): T = 2048 2.95 / 2.89 (one short round: the narrower strip ends with fewer atomics),
+// T = 16384 4.73 / 5.66, T = 65536 5.10 / 5.64.
 hipError_t launch_calib_absmax(const void *X, int64_t T, int64_t K, int64_t ldx, float *absmax_io,
                                hipStream_t st)
 {
-    const unsigned gx = (unsigned)((K + 63) / 64);
-    // about 1024 workgroups, at least 32 rows each
-    int64_t gy = 1024 / gx > 0 ? 1024 / gx : 1;
-    if (gy > (T + 31) / 32) gy = (T + 31) / 32;
-    int64_t rpb = (T + gy - 1) / gy;
-    rpb = (rpb + 31) / 32 * 32;
-    gy = (T + rpb - 1) / rpb;
-    hipLaunchKernelGGL(calib_absmax_kernel, dim3(gx, (unsigned)gy), dim3(256), 0, st,
-                       static_cast<const __half *>(X), T, (int)K, ldx, absmax_io, rpb);
-    return hipGetLastError();
+    if (T >= 8192) return launch_calib<16>(X, T, K, ldx, absmax_io, st, 2048);
+    return launch_calib<8>(X, T, K, ldx, absmax_io, st, 1024);
 }
 
 hipError_t launch_row_absmax(const void *W, int64_t K, int64_t N, int64_t ldw, float *w_rowmax, hipStream_t st)
