@@ -367,7 +367,18 @@ def main():
         extra["cfg5_layer_M16384"] = {"ms": round(t * 1e3, 3), "TOPS": round(ops5 / t / 1e12, 1),
                                       "frac_int8_mfma_peak": round(ops5 / t / 1e12 / PEAK_INT8_TOPS, 4),
                                       "workload": "7 linears (q,k,v,o,gate,up,down) + 4 rotate/quantise passes, 16384 tokens, f6 path"}
-        del X5, X5d, Xq5, Xq5d, W5, Y5, X65, X65d, W65
+        # the rotation + quantiser passes of that layer on their own (three distinct inputs of 134 MB for K = 4096;
+        # the 470 MB input of the down-projection is larger than the Infinity Cache by itself)
+        X5s = [X5, torch.randn_like(X5), torch.randn_like(X5)]
+        t = graph_time(lambda i: sr.sr_fwht_quant_act_f6(X5s[i % 3], inv_s, CLIP, X65, xs5), 6)
+        b = M5 * K * 2.75 + 4 * M5
+        extra["fwht_quant_f6_K4096_M16384"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
+                                               "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+        t = graph_time(lambda i: sr.sr_fwht_quant_act_f6(X5d, None, CLIP, X65d, xs5), 4)
+        b = M5 * K3 * 2.75 + 4 * M5
+        extra["fwht_quant_f6_K14336_M16384"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
+                                                "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+        del X5, X5s, X5d, Xq5, Xq5d, W5, Y5, X65, X65d, W65
 
     # ---------------- CPU baseline: the oracle on a bounded sample ------------------------
     cpu = None
