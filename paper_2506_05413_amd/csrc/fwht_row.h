@@ -49,7 +49,7 @@ constexpr int h28_sign(int i, int j)
     if (i == j) return 1;
     return gf27_is_square(gf27_sub(i - 1, j - 1)) ? 1 : -1;
 }
-// The product itself is the generated straight-line program of h28_program.h (242 additions with shared partial
+// The product itself is the generated straight-line program of h28_program.h (235 additions with shared partial
 // sums; "row sum minus twice the negative terms" took 419).  It must reproduce the matrix built above: checked
 // here on the 28 unit vectors, in integers, at compile time.
 constexpr bool h28_program_matches()
