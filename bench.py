@@ -114,7 +114,7 @@ def main():
         del big
 
     Xs = [torch.from_numpy(wl.cfg2_X(seed=1 + 10 * s)).to(dev) for s in range(SETS)]
-    Wq, Ws, W6, inv_s = {}, {}, {}, None
+    Wq, Ws, W6, inv_s_of = {}, {}, {}, {}
     for N in NS:
         W = torch.from_numpy(wl.cfg2_W(N)).to(dev)
         ws_bytes = sr.sr_fold_workspace_bytes(K, N)
@@ -133,8 +133,9 @@ def main():
             t = graph_time(lambda i: sr.sr_pack_f6_tiles(Wq[N][i % SETS], t6), 16)
             extra["pack_f6_tiles_N%d" % N] = {"us": round(t * 1e6, 1), "GB/s": round((K * N * 1.25) / t / 1e9, 1)}
             del t6
-        inv_s = outs[2]
+        inv_s_of[N] = outs[2]                    # every linear has its own smoothing factors
         del W, work
+    inv_s = inv_s_of[NS[-1]]                     # (the side measurements below use one of them)
 
     Xq = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
     X6 = torch.zeros(sr.sr_f6_tiles_bytes(M, K), dtype=torch.uint8, device=dev)
@@ -144,7 +145,7 @@ def main():
     def step(i):
         s = i % SETS
         for N in NS:
-            sr.sr_fwht_quant_act_f6(Xs[s], inv_s, CLIP, X6, xs)
+            sr.sr_fwht_quant_act_f6(Xs[s], inv_s_of[N], CLIP, X6, xs)
             sr.sr_w4a4_gemm_f6(X6, xs, W6[N][s], Ws[N][s], M, N, K, sr.SR_F16, Y[N])
 
     for i in range(args.warmup):
@@ -162,9 +163,9 @@ def main():
     t0 = time.perf_counter()
     for i in range(args.steps):
         s = i % SETS
-        sr.sr_fwht_quant_act_f6(Xs[s], inv_s, CLIP, X6, xs)
+        sr.sr_fwht_quant_act_f6(Xs[s], inv_s_of[4096], CLIP, X6, xs)
         sr.sr_w4a4_gemm_f6(X6, xs, W6[4096][s], Ws[4096][s], M, 4096, K, sr.SR_F16, Y[4096])
-        sr.sr_fwht_quant_act_f6(Xs[s], inv_s, CLIP, X6, xs)
+        sr.sr_fwht_quant_act_f6(Xs[s], inv_s_of[14336], CLIP, X6, xs)
         if i % EV_EVERY == 0:
             gemm_ev[i // EV_EVERY][0].record()
         sr.sr_w4a4_gemm_f6(X6, xs, W6[14336][s], Ws[14336][s], M, 14336, K, sr.SR_F16, Y[14336])
@@ -386,13 +387,13 @@ def main():
         from oracle import smoothrot_oracle as o
         rows = M
         Xh = Xs[0][:rows].cpu().numpy()
-        inv_h = inv_s.cpu().numpy()
+        inv_h = {N: inv_s_of[N].cpu().numpy() for N in NS}
         cws = {N: o.unpack_int4(Wq[N][0].cpu().numpy()) for N in NS}
         wsh = {N: Ws[N][0].cpu().numpy() for N in NS}
         o.gemm_i32_c(np.zeros((1, 64), np.int8), np.zeros((1, 64), np.int8))     # load the C library
         t0 = time.perf_counter()
         for N in NS:
-            act = o.fwht_quant_act(Xh, inv_h, CLIP)
+            act = o.fwht_quant_act(Xh, inv_h[N], CLIP)
             acc = o.gemm_i32_c(act["codes"], cws[N])
             o.dequant_out(acc, act["x_scale"], wsh[N])
         tc = time.perf_counter() - t0
