@@ -293,3 +293,18 @@ def test_generated_h28_program_is_the_oracles_paley_matrix():
                 n_ops += len(terms) - 1
     assert np.array_equal(H, orc.paley28())
     assert n_ops < 28 * 14                     # fewer additions than "row sum minus twice the negative terms"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Nothing here spans GPUs: bench.py --gpus N with N > 1 (or under a multi-rank launcher) must say so and
+    exit with an error before it touches a device."""
+    import subprocess
+    import sys
+
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in (r.stdout + r.stderr)
+    env = dict(os.environ, WORLD_SIZE="2")
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True, timeout=120,
+                       env=env)
+    assert r.returncode != 0 and "ONE GPU" in (r.stdout + r.stderr)
