@@ -308,3 +308,23 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True, timeout=120,
                        env=env)
     assert r.returncode != 0 and "ONE GPU" in (r.stdout + r.stderr)
+
+
+def test_binding_fails_loudly_without_the_library():
+    """There is no fallback path: with the shared library out of reach the first call raises, and neither the
+    package nor the binding imports anything of the oracle."""
+    import subprocess
+    import sys
+
+    code = (
+        "import sys; sys.path.insert(0, %r)\n"
+        "import paper_2506_05413_amd as sr, paper_2506_05413_amd.binding as b\n"
+        "assert not any(m == 'oracle' or m.startswith('oracle.') for m in sys.modules)\n"
+        "b.LIB_PATH = b.LIB_PATH + '.absent'\n"
+        "try:\n"
+        "    sr.sr_hadamard_supported(4096)\n"
+        "except ImportError as e:\n"
+        "    assert 'no fallback' in str(e); print('RAISED')\n"
+    ) % ROOT
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and "RAISED" in r.stdout, r.stderr
