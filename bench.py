@@ -206,7 +206,11 @@ def main():
         extra["fwht_quant_f6_K4096"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
                                         "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
         for N in NS:
-            t = graph_time(lambda i: sr.sr_w4a4_gemm_f6(X6, xs, W6[N][i % SETS], Ws[N][i % SETS], M, N, K, sr.SR_F16, Y[N]), 64)
+            # weights of at least 300 MB in rotation (beyond the Infinity Cache): 24 copies for N = 4096
+            reps = max(1, -(-300_000_000 // (SETS * W6[N][0].numel())))
+            w6r = [w for w in W6[N]] + [w.clone() for _ in range(reps - 1) for w in W6[N]]
+            t = graph_time(lambda i: sr.sr_w4a4_gemm_f6(X6, xs, w6r[i % len(w6r)], Ws[N][i % SETS], M, N, K, sr.SR_F16, Y[N]), 72)
+            del w6r
             extra["gemm_f6_N%d" % N] = {"us": round(t * 1e6, 2), "TOPS": round(2.0 * M * N * K / t / 1e12, 1),
                                         "frac_int8_mfma_peak": round(2.0 * M * N * K / t / 1e12 / PEAK_INT8_TOPS, 4),
                                         "frac_fp6_mfma_peak": round(2.0 * M * N * K / t / 1e12 / PEAK_FP6_TOPS, 4)}
@@ -243,13 +247,14 @@ def main():
         # down-projection shape (config 3): K = 14336 = 28 * 512 -> N = 4096; rotation-only fold (s = 1)
         K3, N3 = 14336, 4096
         X3 = [torch.from_numpy(wl.cfg3_X(seed=2 + 10 * s)).to(dev) for s in range(4)]
+        X3 += [torch.roll(x, 1, 0) for x in X3[:2]]              # 6 x 58.7 MB = 352 MB: beyond the Infinity Cache
         W3 = torch.from_numpy(wl.cfg3_W()).to(dev)
         Wq3, ws3, _ = sr.sr_fold_smooth_rotate_quant(W3, None, ALPHA, 1.0)
         del W3
         Xq3 = torch.empty((M, K3 // 2), dtype=torch.uint8, device=dev)
         xs3 = torch.empty(M, dtype=torch.float32, device=dev)
         Y3 = torch.empty((M, N3), dtype=torch.float16, device=dev)
-        t = graph_time(lambda i: sr.sr_fwht_quant_act(X3[i % 4], None, CLIP, Xq3, xs3), 32)
+        t = graph_time(lambda i: sr.sr_fwht_quant_act(X3[i % 6], None, CLIP, Xq3, xs3), 30)
         b = M * K3 * 2.5 + M * 4
         extra["fwht_quant_K14336"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
                                       "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
@@ -258,7 +263,7 @@ def main():
                                            "frac_int8_mfma_peak": round(2.0 * M * N3 * K3 / t / 1e12 / PEAK_INT8_TOPS, 4)}
         X63 = torch.zeros(sr.sr_f6_tiles_bytes(M, K3), dtype=torch.uint8, device=dev)
         W63 = sr.sr_pack_f6_tiles(Wq3)
-        t = graph_time(lambda i: sr.sr_fwht_quant_act_f6(X3[i % 4], None, CLIP, X63, xs3), 32)
+        t = graph_time(lambda i: sr.sr_fwht_quant_act_f6(X3[i % 6], None, CLIP, X63, xs3), 30)
         b = M * K3 * 2.75 + M * 4
         extra["fwht_quant_f6_K14336"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
                                          "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
