@@ -277,6 +277,24 @@ SR_API int sr_fwht_quant_act_f6(const void *X_f16, int64_t M, int64_t K, int64_t
                          const float *inv_s, float clip,
                          uint8_t *X6, float *x_scale, void *stream);
 
+/*
+ * sr_fwht_quant_act_f6 that, on the side, warms the memory-side cache (the 256 MB Infinity Cache in front of HBM)
+ * for the call that follows: the launch reads one word of every 128-byte line of
+ * [next_operand, next_operand + next_bytes) -- typically the f6-tile weights of the sr_w4a4_gemm_f6 that consumes
+ * X6 -- so that the GEMM streams them from the cache instead of HBM (M = 2048, K = 4096: 2.5 us of 26 for
+ * N = 4096, 4 us of 67 for N = 14336).  The outputs are exactly those of sr_fwht_quant_act_f6; the words read are
+ * never used.  (The paper's deployment runs the online Hadamard + quantiser directly in front of each
+ * projection; this pairs the two calls.)
+ *   next_operand   device memory, readable for next_bytes bytes, 16-byte aligned; NULL with next_bytes = 0
+ *                  gives sr_fwht_quant_act_f6
+ *   next_bytes     the last next_bytes % 128 bytes are not touched
+ * A hint: honoured where the launch has the memory bandwidth to spare (K = 4096 with more than 1024 rows),
+ * ignored otherwise.  Errors as sr_fwht_quant_act_f6, plus SR_ERR_NULL / SR_ERR_ALIGN for the hint.
+ */
+SR_API int sr_fwht_quant_act_f6_warm(const void *X_f16, int64_t M, int64_t K, int64_t ldx,
+                              const float *inv_s, float clip, uint8_t *X6, float *x_scale,
+                              const void *next_operand, size_t next_bytes, void *stream);
+
 /* sr_swiglu_fwht_quant_act writing f6 tiles (the down-projection input of a gated FFN on the fast path);
  * arguments as there, X6 / K as in sr_fwht_quant_act_f6. */
 SR_API int sr_swiglu_fwht_quant_act_f6(const void *G_f16, const void *U_f16, int64_t M, int64_t K,

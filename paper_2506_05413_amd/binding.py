@@ -39,6 +39,7 @@ _SIGNATURES = {
     "sr_f6_tiles_bytes": (_sz, [_i64, _i64]),
     "sr_pack_f6_tiles": (_int, [_vp, _i64, _i64, _vp, _vp]),
     "sr_fwht_quant_act_f6": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _vp]),
+    "sr_fwht_quant_act_f6_warm": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _vp, _sz, _vp]),
     "sr_swiglu_fwht_quant_act_f6": (_int, [_vp, _vp, _i64, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _vp]),
     "sr_w4a4_gemm_f6": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _int, _vp, _sz, _vp]),
     "sr_w4a4_linear_decode": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _vp]),
@@ -273,14 +274,23 @@ def sr_w4a4_gemm_f6(X6, x_scale, W6, w_scale, M: int, N: int, K: int, out_dtype:
     return Y
 
 
-def sr_fwht_quant_act_f6(X, inv_s, clip: float = 0.9, X6=None, x_scale=None):
-    """X fp16 [M, K] -> (X6 uint8 [sr_f6_tiles_bytes(M, K)] f6 tiles of the codes, x_scale fp32 [M])."""
+def sr_fwht_quant_act_f6(X, inv_s, clip: float = 0.9, X6=None, x_scale=None, warm=None):
+    """X fp16 [M, K] -> (X6 uint8 [sr_f6_tiles_bytes(M, K)] f6 tiles of the codes, x_scale fp32 [M]).
+    warm: a contiguous device tensor (the weights of the GEMM that follows) to be pulled into the memory-side
+    cache on the side (sr_fwht_quant_act_f6_warm)."""
     _dev(X, torch.float16, "X")
     M, K = X.shape
     if X6 is None:
         X6 = torch.zeros(max(sr_f6_tiles_bytes(M, K), 16), dtype=torch.uint8, device=X.device)
     x_scale = torch.empty(M, dtype=torch.float32, device=X.device) if x_scale is None else x_scale
     ldx = X.stride(0) if M > 1 else K
+    if warm is not None:
+        if not (warm.is_cuda and warm.is_contiguous()):
+            raise ValueError("warm must be a contiguous device tensor")
+        _check(raw().sr_fwht_quant_act_f6_warm(_ptr(X), M, K, ldx, _ptr(inv_s), clip, _ptr(X6), _ptr(x_scale),
+                                               _ptr(warm), warm.numel() * warm.element_size(), _stream()),
+               "sr_fwht_quant_act_f6_warm")
+        return X6, x_scale
     _check(raw().sr_fwht_quant_act_f6(_ptr(X), M, K, ldx, _ptr(inv_s), clip, _ptr(X6), _ptr(x_scale), _stream()),
            "sr_fwht_quant_act_f6")
     return X6, x_scale

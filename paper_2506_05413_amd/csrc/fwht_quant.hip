@@ -282,7 +282,8 @@ template <bool HAS_PRE, bool F6, bool MASKED = false>
 __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__restrict__ X, int64_t ldx, int64_t rows,
                                                             const float *__restrict__ pre, float clip, float post_scale,
                                                             uint8_t *__restrict__ Q, float *__restrict__ scale_out,
-                                                            uint32_t had_mask)
+                                                            uint32_t had_mask, const uint32_t *__restrict__ warm,
+                                                            int64_t warm_lines)
 {
     constexpr int K = 4096, ROWF = F6 ? K + 576 : K + 64;   // floats per wave-private row incl. padding
     extern __shared__ float smem_rows[];
@@ -339,6 +340,14 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
     }
     if constexpr (MASKED) butterflies_masked<6>(v, (had_mask & 7u) | (((had_mask >> 9) & 7u) << 3));   // register bits = index bits 0,1,2,9,10,11
     else butterflies_from<6, 2>(v);
+    // Warming the memory-side cache for the kernel that follows (its weights): the waves of the launch share the
+    // 128-byte lines of [warm, warm + 128 warm_lines) and read one word of each -- with ordinary loads, so that the
+    // lines are allocated -- now that the row's own loads have returned; the words are never looked at.
+    uint32_t warm_acc = 0;
+    if (warm) {
+        const int64_t gw = (int64_t)blockIdx.x * 4 + wave, nw = (int64_t)gridDim.x * 4;
+        for (int64_t l = gw * 64 + lane; l < warm_lines; l += nw * 64) warm_acc ^= warm[l * 32];
+    }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         float *d = buf + 520 * j + 8 * lane;             // element 512 j + 8 l + e lives at 520 j + 8 l + e
@@ -392,6 +401,7 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
             q[64 * j + lane] = quant_pack8(y, inv_delta);
         }
     }
+    asm volatile("" ::"v"(warm_acc));                    // keeps the warming loads; they returned long ago
 }
 
 // One workgroup per row -- or, for K = 14336 with 256 threads, no gate row and at least two rounds of rows, as many
@@ -498,7 +508,8 @@ constexpr int64_t kWaveKernelMinRows = 1024;   // measured: 3.3 - 4.8 us against
 
 template <bool HAS_PRE, bool F6, bool MASKED = false>
 hipError_t launch_wave4096(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip, float post_scale,
-                           uint8_t *Q, float *scale_out, hipStream_t st, uint32_t had_mask = 0xFFFFFFFFu)
+                           uint8_t *Q, float *scale_out, hipStream_t st, uint32_t had_mask = 0xFFFFFFFFu,
+                           const void *warm = nullptr, size_t warm_bytes = 0)
 {
     constexpr size_t lds = 4 * (4096 + (F6 ? 576 : 64)) * sizeof(float);
     const unsigned blocks = F6 ? (unsigned)((rows + 63) / 64 * 16) : (unsigned)((rows + 3) / 4);
@@ -506,20 +517,23 @@ hipError_t launch_wave4096(const void *X, int64_t rows, int64_t ldx, const float
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, static_cast<const __half *>(X), ldx, rows, pre, clip,
-                       post_scale, Q, scale_out, had_mask);
+                       post_scale, Q, scale_out, had_mask, warm_bytes >= 128 ? static_cast<const uint32_t *>(warm) : nullptr,
+                       (int64_t)(warm_bytes / 128));
     return hipGetLastError();
 }
 
 hipError_t launch_fwht_quant(const void *X, int64_t rows, int64_t K, int64_t ldx, const float *pre,
-                             float clip, float post_scale, uint8_t *Q, float *scale_out, hipStream_t st, bool f6)
+                             float clip, float post_scale, uint8_t *Q, float *scale_out, hipStream_t st, bool f6,
+                             const void *warm, size_t warm_bytes)
 {
     int pick = 0;
     if (const char *env = getenv("SMOOTHROT_FWHT4096")) pick = atoi(env);
     if (K == 4096 && (pick == 1 || (pick == 0 && rows > kWaveKernelMinRows))) {
-        if (pre) return f6 ? launch_wave4096<true, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st)
-                           : launch_wave4096<true, false>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
-        return f6 ? launch_wave4096<false, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st)
-                  : launch_wave4096<false, false>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
+        constexpr uint32_t all = 0xFFFFFFFFu;
+        if (pre) return f6 ? launch_wave4096<true, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, all, warm, warm_bytes)
+                           : launch_wave4096<true, false>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, all, warm, warm_bytes);
+        return f6 ? launch_wave4096<false, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, all, warm, warm_bytes)
+                  : launch_wave4096<false, false>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, all, warm, warm_bytes);
     }
     if (f6) {
 #define SR_CASE(KK) case KK: return launch_one<KK, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);

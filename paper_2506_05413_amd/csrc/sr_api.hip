@@ -157,17 +157,25 @@ int sr_fwht_quant_act(const void *X_f16, int64_t M, int64_t K, int64_t ldx, cons
                                      static_cast<hipStream_t>(stream)));
 }
 
-int sr_fwht_quant_act_f6(const void *X_f16, int64_t M, int64_t K, int64_t ldx, const float *inv_s, float clip,
-                         uint8_t *X6, float *x_scale, void *stream)
+int sr_fwht_quant_act_f6_warm(const void *X_f16, int64_t M, int64_t K, int64_t ldx, const float *inv_s, float clip,
+                              uint8_t *X6, float *x_scale, const void *next_operand, size_t next_bytes, void *stream)
 {
     if (M < 0 || K <= 0 || ldx < K) return SR_ERR_SHAPE;
     if (!sr::hadamard_supported(K) || K % 128 != 0) return SR_ERR_UNSUPPORTED_K;
     if (!(clip > 0.f && clip <= 1.f)) return SR_ERR_ARG;
+    if (next_bytes && !next_operand) return SR_ERR_NULL;
+    if (next_bytes && !aligned16(next_operand)) return SR_ERR_ALIGN;
     if (M == 0) return SR_OK;
     if (!X_f16 || !X6 || !x_scale) return SR_ERR_NULL;
     if (ldx % 8 != 0 || !aligned16(X_f16) || !aligned16(X6) || (inv_s && !aligned16(inv_s))) return SR_ERR_ALIGN;
     return dev(sr::launch_fwht_quant(X_f16, M, K, ldx, inv_s, clip, 1.0f, X6, x_scale,
-                                     static_cast<hipStream_t>(stream), true));
+                                     static_cast<hipStream_t>(stream), true, next_operand, next_bytes));
+}
+
+int sr_fwht_quant_act_f6(const void *X_f16, int64_t M, int64_t K, int64_t ldx, const float *inv_s, float clip,
+                         uint8_t *X6, float *x_scale, void *stream)
+{
+    return sr_fwht_quant_act_f6_warm(X_f16, M, K, ldx, inv_s, clip, X6, x_scale, nullptr, 0, stream);
 }
 
 int sr_swiglu_fwht_quant_act(const void *G_f16, const void *U_f16, int64_t M, int64_t K, int64_t ldg, int64_t ldu,

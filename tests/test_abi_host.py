@@ -23,7 +23,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = declared_symbols()
-    assert len(names) == 18 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
+    assert len(names) == 19 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
     lib = ctypes.CDLL(sr.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -328,3 +328,18 @@ def test_binding_fails_loudly_without_the_library():
     ) % ROOT
     r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
     assert r.returncode == 0 and "RAISED" in r.stdout, r.stderr
+
+
+def test_cache_warming_quantiser_rejects_bad_hints():
+    raw = sr.raw()
+
+    def call(X=A, M=32, K=4096, ldx=4096, inv=A, clip=0.9, X6=A, xs=A, nxt=A, nbytes=4096):
+        return raw.sr_fwht_quant_act_f6_warm(X, M, K, ldx, inv, clip, X6, xs, nxt, nbytes, None)
+    assert call(nxt=None) == sr.SR_ERR_NULL
+    assert call(nxt=A + 4) == sr.SR_ERR_ALIGN
+    assert call(K=192) == sr.SR_ERR_UNSUPPORTED_K
+    assert call(clip=0.0) == sr.SR_ERR_ARG
+    assert call(ldx=100) == sr.SR_ERR_SHAPE
+    assert call(X=None) == sr.SR_ERR_NULL
+    assert call(M=0) == sr.SR_OK
+    assert call(M=0, nxt=None, nbytes=0) == sr.SR_OK

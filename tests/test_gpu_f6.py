@@ -198,6 +198,33 @@ def test_quantiser_tiles_wave_kernel(gpu, M, smooth):
         assert codes.min() >= -8 and codes.max() <= 7
 
 
+@pytest.mark.parametrize("M,K", [(1100, 4096), (2048, 4096), (40, 4096), (64, 14336)])
+def test_cache_warming_changes_nothing(gpu, M, K):
+    """sr_fwht_quant_act_f6_warm reads, on the side, the lines of the operand that the next call will stream
+    (here a weight matrix in f6 tiles; also a region shorter than one line and one with a ragged tail): tiles
+    and scales must be exactly those of sr_fwht_quant_act_f6, the operand untouched, and the GEMM on it as
+    before -- for the kernel that honours the hint (K = 4096, more than 1024 rows) and for those that ignore it."""
+    X = wl.gauss_acts(41 + M, M, K, 4, 250.0)
+    inv_s = np.random.default_rng(M).uniform(0.25, 4.0, K).astype(np.float32)
+    Xd, inv = torch.from_numpy(X).cuda(), torch.from_numpy(inv_s).cuda()
+    N = 272
+    cw = wl.random_codes(7 + K, N, K)
+    W6 = tiles(gpu, cw)
+    W6_before = W6.clone()
+    X6a, xsa = gpu.sr_fwht_quant_act_f6(Xd, inv, 0.9)
+    for region in (W6, W6[:100], W6[: 128 * 37 + 52], W6[:0]):
+        X6b, xsb = gpu.sr_fwht_quant_act_f6(Xd, inv, 0.9, warm=region if region.numel() else None)
+        torch.cuda.synchronize()
+        assert torch.equal(X6a, X6b) and torch.equal(xsa, xsb)
+    assert torch.equal(W6, W6_before)
+    ws = torch.full((N,), 1e-3, device="cuda")
+    Ya = gpu.sr_w4a4_gemm_f6(X6a, xsa, W6, ws, M, N, K, gpu.SR_I32)
+    X6b, xsb = gpu.sr_fwht_quant_act_f6(Xd, inv, 0.9, warm=W6)
+    Yb = gpu.sr_w4a4_gemm_f6(X6b, xsb, W6, ws, M, N, K, gpu.SR_I32)
+    torch.cuda.synchronize()
+    assert torch.equal(Ya, Yb)
+
+
 @pytest.mark.parametrize("M", [700, 1100])
 def test_row_kernel_walking_over_rows(gpu, monkeypatch, M):
     """K = 14336 with many rows: as many workgroups as the chip holds, each walking over several rows and
