@@ -288,8 +288,9 @@ SR_API int sr_fwht_quant_act_f6(const void *X_f16, int64_t M, int64_t K, int64_t
  *   next_operand   device memory, readable for next_bytes bytes, 16-byte aligned; NULL with next_bytes = 0
  *                  gives sr_fwht_quant_act_f6
  *   next_bytes     the last next_bytes % 128 bytes are not touched
- * A hint: honoured where the launch has the memory bandwidth to spare (K = 4096 with more than 1024 rows),
- * ignored otherwise.  Errors as sr_fwht_quant_act_f6, plus SR_ERR_NULL / SR_ERR_ALIGN for the hint.
+ * A hint: honoured where the launch is large enough to move megabytes on the side (K = 4096 with more than 1024
+ * rows; K = 14336 and the other orders served by the default workgroup-per-row launch from 256 rows on), ignored
+ * otherwise.  Errors as sr_fwht_quant_act_f6, plus SR_ERR_NULL / SR_ERR_ALIGN for the hint.
  */
 SR_API int sr_fwht_quant_act_f6_warm(const void *X_f16, int64_t M, int64_t K, int64_t ldx,
                               const float *inv_s, float clip, uint8_t *X6, float *x_scale,

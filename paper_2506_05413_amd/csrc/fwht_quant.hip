@@ -30,12 +30,22 @@ __global__ __launch_bounds__(NT, STREAM ? 2 * NT / 256 : 1) void fwht_quant_kern
                                                         const float *__restrict__ pre, float clip,
                                                         float post_scale, uint8_t *__restrict__ Q,
                                                         float *__restrict__ scale_out,
-                                                        const __half *__restrict__ gate, int64_t ldg)
+                                                        const __half *__restrict__ gate, int64_t ldg,
+                                                        const uint32_t *__restrict__ warm, int64_t warm_lines)
 {
     extern __shared__ float row[];
     __shared__ float red[NT / 64];
 
     const int t = threadIdx.x;
+    // warming the memory-side cache for the kernel that follows (see fwht4096_wave_kernel): the threads of the
+    // launch share the lines and read one word of each once the workgroup's first row has left its load registers
+    uint32_t warm_acc = 0;
+    auto warm_lines_now = [&]() {
+        if (warm) {
+            const int64_t gt = (int64_t)blockIdx.x * NT + t, nt = (int64_t)gridDim.x * NT;
+            for (int64_t l = gt; l < warm_lines; l += nt) warm_acc ^= warm[l * 32];
+        }
+    };
     // F6: the eight rows of a tile block (768 contiguous bytes per 128 codes) should be written from ONE XCD at
     // about the same time, so that its L2 assembles whole lines: workgroups are dealt round-robin to the 8
     // XCDs, so (virtual) workgroup w = 8 a + x (XCD x) takes row r = a % 8 of row block 8 (a / 8) + x.
@@ -75,7 +85,9 @@ __global__ __launch_bounds__(NT, STREAM ? 2 * NT / 256 : 1) void fwht_quant_kern
     if constexpr (!STREAM) {
         const int64_t m = row_of(blockIdx.x);
         if (m >= rows) return;                           // F6: the grid is rounded up to a multiple of 64
-        const float amax = rotate_row_absmax<K, NT, GATE>(X + m * ldx, pre, row, red, t, GATE ? gate + m * ldg : nullptr);
+        RowLoad<K, NT> ld;
+        row_load<K, NT, false, GATE>(X + m * ldx, pre, t, ld, GATE ? gate + m * ldg : nullptr);
+        const float amax = rotate_loaded_row_absmax<K, NT, GATE>(ld, pre, row, red, t, warm_lines_now);
         quantise(m, amax);
     } else {
         // (not with a gate row: twice the registers in flight; measured 15 - 25 % slower than one row per
@@ -90,6 +102,7 @@ __global__ __launch_bounds__(NT, STREAM ? 2 * NT / 256 : 1) void fwht_quant_kern
             const int64_t m = row_of(w);
             row_load<K, NT, false, GATE>(X + m * ldx, pre, t, ld);
         }
+        bool first = true;
         for (;;) {
             const int64_t m = row_of(w);
             int64_t wn = w + step;
@@ -100,7 +113,9 @@ __global__ __launch_bounds__(NT, STREAM ? 2 * NT / 256 : 1) void fwht_quant_kern
             const int64_t mn = more ? row_of(wn) : m;
             const float amax = rotate_loaded_row_absmax<K, NT, GATE>(ld, pre, row, red, t, [&]() {
                 if (more) row_load<K, NT, false, GATE, 1>(X + mn * ldx, pre, t, ld);
+                if (first) warm_lines_now();
             });
+            first = false;
             if (more) row_load<K, NT, false, GATE, 2>(X + mn * ldx, pre, t, ld);
             quantise(m, amax);
             if (!more) break;
@@ -108,6 +123,7 @@ __global__ __launch_bounds__(NT, STREAM ? 2 * NT / 256 : 1) void fwht_quant_kern
             __syncthreads();                             // the row buffer is rewritten by the next first pass
         }
     }
+    asm volatile("" ::"v"(warm_acc));                    // keeps the warming loads; they returned long ago
 }
 
 // ------------------------------------------------------------------------------------------
@@ -409,7 +425,8 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
 // fetching its next row while it works on the current one (2048 rows: 36.2 -> 34.4 us, 16384: 264 -> 243 us).
 template <int K, int NT, bool F6, bool GATE>
 hipError_t launch_row_kernel(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip, float post_scale,
-                             uint8_t *Q, float *scale_out, const __half *gate, int64_t ldg, hipStream_t st)
+                             uint8_t *Q, float *scale_out, const __half *gate, int64_t ldg, hipStream_t st,
+                             const void *warm = nullptr, size_t warm_bytes = 0)
 {
     constexpr size_t lds = sizeof(float) * padded_len(K);
     const int64_t total = F6 ? (rows + 63) / 64 * 64 : rows;
@@ -427,14 +444,18 @@ hipError_t launch_row_kernel(const void *X, int64_t rows, int64_t ldx, const flo
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
+    // the hint is honoured from 256 workgroups on (a launch of a few rows cannot move megabytes on the side)
+    const bool warms = warm && warm_bytes >= 128 && grid >= 256;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, st,
-                       static_cast<const __half *>(X), ldx, rows, pre, clip, post_scale, Q, scale_out, gate, ldg);
+                       static_cast<const __half *>(X), ldx, rows, pre, clip, post_scale, Q, scale_out, gate, ldg,
+                       warms ? static_cast<const uint32_t *>(warm) : nullptr, (int64_t)(warm_bytes / 128));
     return hipGetLastError();
 }
 
 template <int K, bool F6 = false, int NT_FORCE = 0>
 hipError_t launch_one(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip,
-                      float post_scale, uint8_t *Q, float *scale_out, hipStream_t st)
+                      float post_scale, uint8_t *Q, float *scale_out, hipStream_t st,
+                      const void *warm = nullptr, size_t warm_bytes = 0)
 {
     constexpr int groups = K / 16;
     constexpr int NT = NT_FORCE ? NT_FORCE : (groups >= 256 ? 256 : (groups >= 128 ? 128 : 64));
@@ -456,7 +477,7 @@ hipError_t launch_one(const void *X, int64_t rows, int64_t ldx, const float *pre
             if (rows <= 512) return launch_one<K, F6, 512>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
         }
     }
-    return launch_row_kernel<K, NT, F6, false>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, nullptr, 0, st);
+    return launch_row_kernel<K, NT, F6, false>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, nullptr, 0, st, warm, warm_bytes);
 }
 
 // silu(gate) * x in front of the plain kernel (no head mask, no clip search)
@@ -536,7 +557,7 @@ hipError_t launch_fwht_quant(const void *X, int64_t rows, int64_t K, int64_t ldx
                   : launch_wave4096<false, false>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, all, warm, warm_bytes);
     }
     if (f6) {
-#define SR_CASE(KK) case KK: return launch_one<KK, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st);
+#define SR_CASE(KK) case KK: return launch_one<KK, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, warm, warm_bytes);
         switch (K) {                                    // K % 128 == 0
             SR_CASE(128) SR_CASE(256) SR_CASE(512) SR_CASE(1024) SR_CASE(2048)
             SR_CASE(4096) SR_CASE(8192) SR_CASE(16384) SR_CASE(32768)

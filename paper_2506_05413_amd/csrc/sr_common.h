@@ -79,7 +79,8 @@ inline int compute_units()
 // y = (x * pre) H per row, per-row symmetric INT4, scale_out = delta * post_scale.
 // f6: Q receives f6 tiles (see gemm_f6.hip; K % 128 == 0) instead of canonical packed nibbles.
 // warm: device memory (4-byte aligned) whose 128-byte lines the launch reads on the side, so that the kernel
-// that follows finds them in the memory-side cache; honoured by the K = 4096 wave-per-row kernel, ignored elsewhere.
+// that follows finds them in the memory-side cache; honoured by the K = 4096 wave-per-row kernel and by the default
+// workgroup-per-row launches of at least 256 workgroups, ignored elsewhere.
 hipError_t launch_fwht_quant(const void *X_f16, int64_t rows, int64_t K, int64_t ldx,
                              const float *pre, float clip, float post_scale,
                              uint8_t *Q, float *scale_out, hipStream_t st, bool f6 = false,

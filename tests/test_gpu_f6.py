@@ -198,12 +198,13 @@ def test_quantiser_tiles_wave_kernel(gpu, M, smooth):
         assert codes.min() >= -8 and codes.max() <= 7
 
 
-@pytest.mark.parametrize("M,K", [(1100, 4096), (2048, 4096), (40, 4096), (64, 14336)])
+@pytest.mark.parametrize("M,K", [(1100, 4096), (2048, 4096), (40, 4096), (64, 14336), (300, 14336), (1100, 14336), (600, 7168)])
 def test_cache_warming_changes_nothing(gpu, M, K):
     """sr_fwht_quant_act_f6_warm reads, on the side, the lines of the operand that the next call will stream
     (here a weight matrix in f6 tiles; also a region shorter than one line and one with a ragged tail): tiles
     and scales must be exactly those of sr_fwht_quant_act_f6, the operand untouched, and the GEMM on it as
-    before -- for the kernel that honours the hint (K = 4096, more than 1024 rows) and for those that ignore it."""
+    before -- for the kernels that honour the hint (the wave-per-row kernel, the workgroup-per-row kernel from
+    256 rows on, also where its workgroups walk over rows) and for the launches that ignore it."""
     X = wl.gauss_acts(41 + M, M, K, 4, 250.0)
     inv_s = np.random.default_rng(M).uniform(0.25, 4.0, K).astype(np.float32)
     Xd, inv = torch.from_numpy(X).cuda(), torch.from_numpy(inv_s).cuda()
