@@ -196,6 +196,20 @@ def main():
 
     # ---------------- per-kernel side measurements (same buffers, event-timed) ------------
     if not args.no_extra:
+        # the same step with the plain quantiser call (no cache warming), for comparison
+        def step_plain(i):
+            s = i % SETS
+            for N in NS:
+                sr.sr_fwht_quant_act_f6(Xs[s], inv_s_of[N], CLIP, X6, xs)
+                sr.sr_w4a4_gemm_f6(X6, xs, W6[N][s], Ws[N][s], M, N, K, sr.SR_F16, Y[N])
+        for i in range(10):
+            step_plain(i)
+        torch.cuda.synchronize()
+        tq = time.perf_counter()
+        for i in range(100):
+            step_plain(i)
+        torch.cuda.synchronize()
+        extra["step_without_cache_warming_ms"] = round((time.perf_counter() - tq) * 1e3 / 100, 4)
         # 20 distinct inputs (336 MB) for the rotation kernels on their own: 8 would stay in the Infinity Cache
         Xq_in = Xs + [torch.roll(x, 1 + j, 0) for j in range(2) for x in Xs][:12]
         t = graph_time(lambda i: sr.sr_fwht_quant_act(Xq_in[i % 20], inv_s, CLIP, Xq, xs), 60)
@@ -268,11 +282,20 @@ def main():
         b = M * K3 * 2.75 + M * 4
         extra["fwht_quant_f6_K14336"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
                                          "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
-        t = graph_time(lambda i: sr.sr_w4a4_gemm_f6(X63, xs3, W63, ws3, M, N3, K3, sr.SR_F16, Y3), 32)
+        W63s = [W63] + [W63.clone() for _ in range(7)]           # 8 x 44 MB: beyond the Infinity Cache
+        t = graph_time(lambda i: sr.sr_w4a4_gemm_f6(X63, xs3, W63s[i % 8], ws3, M, N3, K3, sr.SR_F16, Y3), 32)
         extra["gemm_f6_K14336_N4096"] = {"us": round(t * 1e6, 2), "TOPS": round(2.0 * M * N3 * K3 / t / 1e12, 1),
                                          "frac_int8_mfma_peak": round(2.0 * M * N3 * K3 / t / 1e12 / PEAK_INT8_TOPS, 4),
                                          "frac_fp6_mfma_peak": round(2.0 * M * N3 * K3 / t / 1e12 / PEAK_FP6_TOPS, 4)}
-        del X63, W63
+        # the pair as a layer runs it: rotation + quantiser, then the GEMM -- without and with the quantiser launch
+        # warming the memory-side cache with the GEMM's weights
+        def pair3(i, warm):
+            sr.sr_fwht_quant_act_f6(X3[i % 6], None, CLIP, X63, xs3, warm=W63s[i % 8] if warm else None)
+            sr.sr_w4a4_gemm_f6(X63, xs3, W63s[i % 8], ws3, M, N3, K3, sr.SR_F16, Y3)
+        tp = graph_time(lambda i: pair3(i, False), 24) * 1e6
+        tw = graph_time(lambda i: pair3(i, True), 24) * 1e6
+        extra["pair_K14336_N4096"] = {"quantiser_plus_gemm_us": round(tp, 2), "with_cache_warming_us": round(tw, 2)}
+        del X63, W63, W63s
         copies = [Wq3.clone() for _ in range(20)]
         for Md in (1, 4, 16):
             xq_d, xs_d = sr.sr_fwht_quant_act(X3[0][:Md].contiguous(), None, CLIP)
