@@ -14,7 +14,9 @@
  * Conventions that hold for every call
  * ------------------------------------
  *  - Every data pointer is DEVICE memory owned by the caller.  The library never
- *    allocates, frees or keeps a pointer, has no global state and is re-entrant.
+ *    allocates, frees or keeps a pointer and is re-entrant.  Its only process-wide
+ *    state: the tuning knobs of sr_tune_set (all "auto" unless a caller sets one) and a
+ *    cached compute-unit count per device.  No environment variable is read.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *    only enqueue work and return; they never synchronise.
  *  - Arguments are validated on the host before anything is launched.  On error a
@@ -65,6 +67,28 @@ enum { SR_F16 = 0, SR_I32 = 1 };
 
 /* Static, NUL-terminated description of a status (never NULL). */
 SR_API const char *sr_status_str(int status);
+
+/*
+ * Tuning knobs: process-wide overrides of the dispatch heuristics, for tests (every kernel on every
+ * shape) and tuning runs (variants compared inside one process).  Results never depend on a knob --
+ * only which kernel, tile or grid computes them.  SR_TUNE_AUTO restores the measured choice.  A knob
+ * is read once per launch with a relaxed atomic load; setting one while another thread launches is
+ * safe but that launch may see either value.
+ *   SR_TUNE_GEMM_TILE      tile configuration of the prefill GEMMs by number (unknown numbers: auto)
+ *   SR_TUNE_GEMM_GRID      persistent workgroups of the prefill GEMMs (rounded down to a multiple of 8)
+ *   SR_TUNE_GEMM_XCDM      split of the tile grid over the 8 XCDs in m: 0 (none), 1, 2, 4, 8
+ *   SR_TUNE_DECODE_KERNEL  M <= 16 GEMM: 1 dot product (M <= 2), 2 MFMA per 16 channels, 3 streaming MFMA
+ *   SR_TUNE_FWHT4096       K = 4096 rotation: 1 wave per row, 2 workgroup per row
+ *   SR_TUNE_FWHT_STREAM    K = 14336 rotation: 1 workgroups walk over rows, 0 one workgroup per row
+ *   SR_TUNE_GEMM_SPLITK    sr_w4a4_gemm_f6: 1 = one K range per tile, 2 = two K halves per tile
+ *                          (partial sums through the workspace); ignored where the workspace is missing
+ * sr_tune_set returns SR_ERR_ARG for an unknown knob; sr_tune_get returns SR_TUNE_AUTO for one.
+ */
+enum { SR_TUNE_GEMM_TILE = 0, SR_TUNE_GEMM_GRID = 1, SR_TUNE_GEMM_XCDM = 2, SR_TUNE_DECODE_KERNEL = 3,
+       SR_TUNE_FWHT4096 = 4, SR_TUNE_FWHT_STREAM = 5, SR_TUNE_GEMM_SPLITK = 6 };
+#define SR_TUNE_AUTO INT64_MIN
+SR_API int sr_tune_set(int knob, int64_t value);
+SR_API int64_t sr_tune_get(int knob);
 
 /* 1 if a Hadamard matrix of order K is implemented (see "Supported shapes"), else 0. */
 SR_API int sr_hadamard_supported(int64_t K);

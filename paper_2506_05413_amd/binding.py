@@ -15,6 +15,9 @@ import torch
 SR_OK, SR_ERR_NULL, SR_ERR_SHAPE, SR_ERR_UNSUPPORTED_K = 0, 1, 2, 3
 SR_ERR_ALIGN, SR_ERR_ARG, SR_ERR_WORKSPACE, SR_ERR_DEVICE = 4, 5, 6, 7
 SR_F16, SR_I32 = 0, 1
+SR_TUNE_GEMM_TILE, SR_TUNE_GEMM_GRID, SR_TUNE_GEMM_XCDM, SR_TUNE_DECODE_KERNEL = 0, 1, 2, 3
+SR_TUNE_FWHT4096, SR_TUNE_FWHT_STREAM, SR_TUNE_GEMM_SPLITK = 4, 5, 6
+SR_TUNE_AUTO = -(1 << 63)
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libsmoothrot.so")
@@ -25,6 +28,8 @@ _vp, _i64, _f32, _sz, _int = _c.c_void_p, _c.c_int64, _c.c_float, _c.c_size_t, _
 _SIGNATURES = {
     "sr_status_str": (_c.c_char_p, [_int]),
     "sr_hadamard_supported": (_int, [_i64]),
+    "sr_tune_set": (_int, [_int, _i64]),
+    "sr_tune_get": (_i64, [_int]),
     "sr_fold_workspace_bytes": (_sz, [_i64, _i64]),
     "sr_gemm_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "sr_calib_absmax": (_int, [_vp, _i64, _i64, _i64, _vp, _vp]),
@@ -98,6 +103,15 @@ def sr_status_str(status: int) -> str:
 
 def sr_hadamard_supported(K: int) -> bool:
     return bool(raw().sr_hadamard_supported(K))
+
+
+def sr_tune_set(knob: int, value: int = SR_TUNE_AUTO) -> None:
+    """Process-wide override of a dispatch heuristic (tests and tuning); SR_TUNE_AUTO restores the default."""
+    _check(raw().sr_tune_set(knob, value), "sr_tune_set")
+
+
+def sr_tune_get(knob: int) -> int:
+    return int(raw().sr_tune_get(knob))
 
 
 def sr_fold_workspace_bytes(K: int, N: int) -> int:
@@ -294,6 +308,12 @@ def sr_fwht_quant_act_f6(X, inv_s, clip: float = 0.9, X6=None, x_scale=None, war
     _check(raw().sr_fwht_quant_act_f6(_ptr(X), M, K, ldx, _ptr(inv_s), clip, _ptr(X6), _ptr(x_scale), _stream()),
            "sr_fwht_quant_act_f6")
     return X6, x_scale
+
+
+def sr_fwht_quant_act_f6_warm(X, inv_s, clip: float, next_operand, X6=None, x_scale=None):
+    """sr_fwht_quant_act_f6 that also pulls `next_operand` (a contiguous device tensor, typically the f6-tile
+    weights of the GEMM that follows) into the memory-side cache; same outputs."""
+    return sr_fwht_quant_act_f6(X, inv_s, clip, X6, x_scale, warm=next_operand)
 
 
 def sr_swiglu_fwht_quant_act_f6(G, U, inv_s, clip: float = 0.9, X6=None, x_scale=None):

@@ -16,8 +16,6 @@
 // bank-conflict free for K = 4096.
 #include "fwht_row.h"
 
-#include <stdlib.h>
-
 namespace sr {
 namespace {
 
@@ -420,6 +418,12 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
     asm volatile("" ::"v"(warm_acc));                    // keeps the warming loads; they returned long ago
 }
 
+__global__ __launch_bounds__(256) void fill_f32_kernel(float *__restrict__ dst, int64_t n, float value)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) dst[i] = value;
+}
+
 // One workgroup per row -- or, for K = 14336 with 256 threads, no gate row and at least two rounds of rows, as many
 // workgroups as the chip holds at once (the fp32 row in LDS allows two per CU), each walking over rows and
 // fetching its next row while it works on the current one (2048 rows: 36.2 -> 34.4 us, 16384: 264 -> 243 us).
@@ -435,7 +439,7 @@ hipError_t launch_row_kernel(const void *X, int64_t rows, int64_t ldx, const flo
     if constexpr (K == 14336 && NT == 256 && !GATE) {
         const int64_t resident = (int64_t)compute_units() * (int64_t)(160 * 1024 / lds) / 64 * 64;
         stream = resident >= 64 && total >= 2 * resident;
-        if (const char *env = getenv("SMOOTHROT_FWHT_STREAM")) stream = resident >= 64 && atoi(env) != 0;   // tuning aid
+        if (int64_t f; tuned(kTuneFwhtStream, f)) stream = resident >= 64 && f != 0;
         if (stream) grid = resident < total ? resident : total;
     }
     auto kern = stream ? fwht_quant_kernel<K, NT, F6, GATE, (K == 14336 && NT == 256 && !GATE)> : fwht_quant_kernel<K, NT, F6, GATE, false>;
@@ -548,7 +552,7 @@ hipError_t launch_fwht_quant(const void *X, int64_t rows, int64_t K, int64_t ldx
                              const void *warm, size_t warm_bytes)
 {
     int pick = 0;
-    if (const char *env = getenv("SMOOTHROT_FWHT4096")) pick = atoi(env);
+    if (int64_t f; tuned(kTuneFwht4096, f)) pick = (int)f;
     if (K == 4096 && (pick == 1 || (pick == 0 && rows > kWaveKernelMinRows))) {
         constexpr uint32_t all = 0xFFFFFFFFu;
         if (pre) return f6 ? launch_wave4096<true, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, all, warm, warm_bytes)
@@ -582,6 +586,11 @@ hipError_t launch_fwht_quant_ex(const void *X, int64_t rows, int64_t K, int64_t 
 {
     // head-wise transform of many rows of 4096: the wave-per-row kernel with the unselected butterflies skipped
     if (K == 4096 && !ex.gate && ex.n_grid == 0 && rows > kWaveKernelMinRows) {
+        // no search: the ratio "chosen" for every row is the fixed one (the wave kernel itself does not report it)
+        if (ex.ratio_out) {
+            hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, ex.ratio_out, rows, clip);
+            if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+        }
         if (pre) return f6 ? launch_wave4096<true, true, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, ex.had_mask)
                            : launch_wave4096<true, false, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, ex.had_mask);
         return f6 ? launch_wave4096<false, true, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, ex.had_mask)

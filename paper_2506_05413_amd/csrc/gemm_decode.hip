@@ -480,10 +480,10 @@ hipError_t launch_stream_any(const uint8_t *Xq, const float *xs, const uint8_t *
 hipError_t launch_gemm_decode(const uint8_t *Xq, const float *xs, const uint8_t *Wq, const float *ws,
                               int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_i32, hipStream_t st)
 {
-    // SMOOTHROT_DECODE_KERNEL = 1 (dot, M <= 2 only), 2 (MFMA, workgroup per 16 channels) or 3 (streaming MFMA)
-    // forces a kernel (tuning and test aid); unset = the choice measured below.
+    // the decode-kernel knob = 1 (dot, M <= 2 only), 2 (MFMA, workgroup per 16 channels) or 3 (streaming MFMA)
+    // forces a kernel (tuning and test aid); not set = the choice measured below.
     int force = 0;
-    if (const char *env = getenv("SMOOTHROT_DECODE_KERNEL")) force = atoi(env);
+    if (int64_t f; tuned(kTuneDecodeKernel, f)) force = (int)f;
     const int nslab = (int)((K / 2 + SLAB - 1) / SLAB);
 
     // measured (4096 -> 14336): dot kernel 6.2 / 7.0 us for M = 1 / 2 (one more microsecond per further token),

@@ -45,7 +45,6 @@
 #include "sr_common.h"
 #include "gemm_common.h"
 
-#include <stdlib.h>
 #include <type_traits>
 
 namespace sr {
@@ -181,10 +180,8 @@ __device__ __forceinline__ void f6_tiles(
 #pragma unroll
         for (int r = 0; r < NREG; ++r) {
             __builtin_amdgcn_sched_barrier(0);
-#ifndef F6_NO_READ                                       // (timing aid: the fragment reads compiled out -- results are then wrong)
 #pragma unroll
             for (int q = r * FPRG; q < (r + 1) * FPRG && q < FM + FN; ++q) read_q(nxt, q, rbase, t);
-#endif
             const int mlo = r * NM / NREG, mhi = (r + 1) * NM / NREG;
 #pragma unroll
             for (int m = mlo; m < mhi; ++m) {
@@ -192,10 +189,8 @@ __device__ __forceinline__ void f6_tiles(
                 acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(cur.w[i], cur.x[j], acc[i][j], 2, 2, 0, 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
-#ifndef F6_NO_DMA                                        // (timing aid: no loads in the loop -- results are then wrong)
 #pragma unroll
             for (int idx = dlo + r * DPR; idx < dlo + (r + 1) * DPR && idx < dhi; ++idx) dma_one(idx, dstage, dslot);
-#endif
         }
     };
     constexpr std::integral_constant<int, 0> AFTER{};
@@ -321,12 +316,11 @@ hipError_t launch_f6(const uint8_t *X6, const float *xs, const uint8_t *W6, cons
     }
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
     int xcd_m = choose_xcd_split(tiles_m, tiles_n, BM, BN);
-    if (const char *env = getenv("SMOOTHROT_GEMM_XCDM")) {            // tuning aid: force the split (0 = none)
-        const int f = atoi(env);
-        if (f == 0 || ((f == 1 || f == 2 || f == 4 || f == 8) && tiles_m % f == 0 && tiles_n % (8 / f) == 0)) xcd_m = f;
+    if (int64_t f; tuned(kTuneGemmXcdM, f)) {                         // force the split (0 = none)
+        if (f == 0 || ((f == 1 || f == 2 || f == 4 || f == 8) && tiles_m % f == 0 && tiles_n % (8 / f) == 0)) xcd_m = (int)f;
     }
     int64_t grid = (int64_t)compute_units() * WG_PER_CU;
-    if (const char *env = getenv("SMOOTHROT_GEMM_GRID")) grid = atoll(env) > 0 ? atoll(env) / 8 * 8 : grid;   // tuning aid
+    if (int64_t g; tuned(kTuneGemmGrid, g) && g > 0) grid = g / 8 * 8;
     if (grid < 8) grid = 8;
     const int64_t total = (int64_t)tiles_m * tiles_n;
     if (grid > total) grid = total;
@@ -391,9 +385,9 @@ hipError_t launch_pack_f6(const uint8_t *Q4, int64_t rows, int64_t K, uint8_t *T
 hipError_t launch_gemm_f6(const uint8_t *X6, const float *xs, const uint8_t *W6, const float *ws, int64_t M, int64_t N,
                           int64_t K, void *Y, int64_t ldy, int out_i32, hipStream_t st)
 {
-    // SMOOTHROT_GEMM_TILE selects a tile configuration by number (tuning aid); unset = heuristic.
+    // the tile knob selects a tile configuration by number; not set = heuristic
     int variant = 0;
-    if (const char *env = getenv("SMOOTHROT_GEMM_TILE")) variant = atoi(env);
+    if (int64_t t; tuned(kTuneGemmTile, t)) variant = (int)t;
     switch (variant) {
         case 61: return launch_f6<256, 256, 2, 4, 3, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
         case 63: return launch_f6<256, 128, 2, 2, 2, 2>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);

@@ -329,7 +329,7 @@ hipError_t launch_tile(const uint8_t *Xq, const float *xs, const uint8_t *Wq, co
     const int xcd_m = choose_xcd_split(tiles_m, tiles_n, BM, BN);
     // persistent grid: as many workgroups as the chip holds at once (a multiple of 8, as the XCD map needs)
     int64_t grid = (int64_t)compute_units() * WG_PER_CU;
-    if (const char *env = getenv("SMOOTHROT_GEMM_GRID")) grid = atoll(env) > 0 ? atoll(env) / 8 * 8 : grid;   // tuning aid
+    if (int64_t g; tuned(kTuneGemmGrid, g) && g > 0) grid = g / 8 * 8;
     if (grid < 8) grid = 8;
     const int64_t total = (int64_t)tiles_m * tiles_n;
     if (grid > total) grid = total;
@@ -504,9 +504,9 @@ hipError_t launch_gemm_prefill(const uint8_t *Xq, const float *xs, const uint8_t
                                int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_i32,
                                hipStream_t st)
 {
-    // SMOOTHROT_GEMM_TILE selects a tile configuration by number (tuning aid); unset = heuristic.
+    // the tile knob selects a tile configuration by number; not set = heuristic
     int variant = 0;
-    if (const char *env = getenv("SMOOTHROT_GEMM_TILE")) variant = atoi(env);
+    if (int64_t t; tuned(kTuneGemmTile, t)) variant = (int)t;
     if (K % 256 != 0 || variant == 9) {
         constexpr int BM = 128, BN = 128;
         const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);

@@ -3,6 +3,17 @@
 #include "../../include/smoothrot.h"
 #include "sr_common.h"
 
+#include <atomic>
+
+namespace sr {
+namespace {
+std::atomic<int64_t> g_tune[kTuneCount] = {
+    {kTuneAuto}, {kTuneAuto}, {kTuneAuto}, {kTuneAuto}, {kTuneAuto}, {kTuneAuto}, {kTuneAuto}};
+static_assert(kTuneCount == 7, "one initialiser per knob");
+}
+int64_t tune(int knob) { return g_tune[knob].load(std::memory_order_relaxed); }
+}  // namespace sr
+
 namespace {
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -42,6 +53,19 @@ const char *sr_status_str(int status)
 }
 
 int sr_hadamard_supported(int64_t K) { return sr::hadamard_supported(K) ? 1 : 0; }
+
+int sr_tune_set(int knob, int64_t value)
+{
+    if (knob < 0 || knob >= sr::kTuneCount) return SR_ERR_ARG;
+    sr::g_tune[knob].store(value, std::memory_order_relaxed);
+    return SR_OK;
+}
+
+int64_t sr_tune_get(int knob)
+{
+    if (knob < 0 || knob >= sr::kTuneCount) return SR_TUNE_AUTO;
+    return sr::tune(knob);
+}
 
 size_t sr_fold_workspace_bytes(int64_t K, int64_t N)
 {

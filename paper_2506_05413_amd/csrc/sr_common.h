@@ -59,6 +59,16 @@ __device__ __forceinline__ float max_of_wave(float v)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+// ---- tuning knobs (host) ---------------------------------------------------------------
+// Process-wide overrides of the dispatch heuristics, set through sr_tune_set (include/smoothrot.h): the tests
+// use them to run every kernel on every shape, tuning runs to compare variants inside one process.  A knob that
+// is not set (kTuneAuto) leaves the measured choice in place.  Relaxed atomics: a launch reads each knob once.
+enum { kTuneGemmTile = 0, kTuneGemmGrid, kTuneGemmXcdM, kTuneDecodeKernel, kTuneFwht4096, kTuneFwhtStream,
+       kTuneGemmSplitK, kTuneCount };
+constexpr int64_t kTuneAuto = INT64_MIN;
+int64_t tune(int knob);                                  // sr_api.hip
+inline bool tuned(int knob, int64_t &v) { v = tune(knob); return v != kTuneAuto; }
+
 // ---- device properties (host) ---------------------------------------------------------
 // compute units of the current device (asked once per process and device)
 inline int compute_units()

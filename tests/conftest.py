@@ -20,3 +20,13 @@ def gpu():
         pytest.skip("no GPU in this process")
     import paper_2506_05413_amd as sr
     return sr
+
+
+@pytest.fixture
+def tune(gpu):
+    """tune(knob, value): sets a tuning knob of the library for the duration of one test (all back to auto after)."""
+    def set_knob(knob, value):
+        gpu.sr_tune_set(knob, int(value))
+    yield set_knob
+    for knob in range(7):
+        gpu.sr_tune_set(knob, gpu.SR_TUNE_AUTO)

@@ -23,11 +23,22 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = declared_symbols()
-    assert len(names) == 19 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
+    assert len(names) == 21 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
     lib = ctypes.CDLL(sr.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
     assert set(names) == set(sr.binding._SIGNATURES)
+
+
+def test_tuning_knobs_round_trip_and_reject_unknown_ones():
+    for knob in range(7):
+        assert sr.sr_tune_get(knob) == sr.SR_TUNE_AUTO
+        sr.sr_tune_set(knob, 3)
+        assert sr.sr_tune_get(knob) == 3
+        sr.sr_tune_set(knob, sr.SR_TUNE_AUTO)
+        assert sr.sr_tune_get(knob) == sr.SR_TUNE_AUTO
+    assert sr.raw().sr_tune_set(7, 1) == sr.SR_ERR_ARG and sr.raw().sr_tune_set(-1, 1) == sr.SR_ERR_ARG
+    assert sr.sr_tune_get(99) == sr.SR_TUNE_AUTO
 
 
 def test_status_strings():

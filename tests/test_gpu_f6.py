@@ -76,10 +76,10 @@ def test_seeded_random_shapes(gpu):
 
 
 @pytest.mark.parametrize("tile", ["61", "63", "64", "65", "66"])
-def test_every_tile_configuration(gpu, tile, monkeypatch):
+def test_every_tile_configuration(gpu, tile, tune):
     """The launch heuristic picks one configuration per shape; each of them is checked on a shape with
     ragged edges and more tiles than workgroups can hold at once is covered by the full-size test below."""
-    monkeypatch.setenv("SMOOTHROT_GEMM_TILE", tile)
+    tune(gpu.SR_TUNE_GEMM_TILE, tile)
     M, N, K = 700, 1040, 640
     cx, cw = wl.random_codes(1, M, K), wl.random_codes(2, N, K)
     got = gemm_f6(gpu, cx, cw, ldy=1048)
@@ -227,7 +227,7 @@ def test_cache_warming_changes_nothing(gpu, M, K):
 
 
 @pytest.mark.parametrize("M", [700, 1100])
-def test_row_kernel_walking_over_rows(gpu, monkeypatch, M):
+def test_row_kernel_walking_over_rows(gpu, tune, M):
     """K = 14336 with many rows: as many workgroups as the chip holds, each walking over several rows and
     fetching its next row while it works (forced here at a row count that leaves workgroups with one, two or
     three rows and a ragged last tile block).  Same arithmetic as one workgroup per row: every output must
@@ -245,9 +245,9 @@ def test_row_kernel_walking_over_rows(gpu, monkeypatch, M):
         torch.cuda.synchronize()
         return [t.cpu().numpy() for t in outs]
 
-    monkeypatch.setenv("SMOOTHROT_FWHT_STREAM", "0")
+    tune(gpu.SR_TUNE_FWHT_STREAM, 0)
     one = run_all()
-    monkeypatch.setenv("SMOOTHROT_FWHT_STREAM", "1")
+    tune(gpu.SR_TUNE_FWHT_STREAM, 1)
     walk = run_all()
     for a, b in zip(one, walk):
         assert np.array_equal(a, b)

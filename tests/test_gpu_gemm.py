@@ -122,17 +122,17 @@ def per_kernel(shapes):
 
 
 @pytest.mark.parametrize("kernel,M,N,K", per_kernel(DECODE_SHAPES))
-def test_every_decode_kernel_bit_exact(gpu, monkeypatch, kernel, M, N, K):
+def test_every_decode_kernel_bit_exact(gpu, tune, kernel, M, N, K):
     print("case", kernel, M, N, K, flush=True)
-    monkeypatch.setenv("SMOOTHROT_DECODE_KERNEL", kernel)
+    tune(gpu.SR_TUNE_DECODE_KERNEL, kernel)
     cx, cw = wl.random_codes(7 * M + K, M, K), wl.random_codes(N + 5 * K, N, K)
     got = gpu_gemm(gpu, cx, cw)
     assert np.array_equal(got.astype(np.int64), o.gemm_i32_c(cx, cw))
 
 
 @pytest.mark.parametrize("kernel,M", [(k, M) for (k, M) in per_kernel([(1,), (2,), (16,)])])
-def test_every_decode_kernel_extreme_codes(gpu, monkeypatch, kernel, M):
-    monkeypatch.setenv("SMOOTHROT_DECODE_KERNEL", kernel)
+def test_every_decode_kernel_extreme_codes(gpu, tune, kernel, M):
+    tune(gpu.SR_TUNE_DECODE_KERNEL, kernel)
     K = 131008
     cx = np.full((M, K), -8, np.int8)
     cw = np.full((48, K), -8, np.int8)
@@ -142,8 +142,8 @@ def test_every_decode_kernel_extreme_codes(gpu, monkeypatch, kernel, M):
 
 
 @pytest.mark.parametrize("kernel,M,N,K", per_kernel([(2, 4096, 4096), (4, 14336, 4096), (11, 528, 1088), (16, 4096, 14336)]))
-def test_every_decode_kernel_fp16_and_leading_dimension(gpu, monkeypatch, kernel, M, N, K):
-    monkeypatch.setenv("SMOOTHROT_DECODE_KERNEL", kernel)
+def test_every_decode_kernel_fp16_and_leading_dimension(gpu, tune, kernel, M, N, K):
+    tune(gpu.SR_TUNE_DECODE_KERNEL, kernel)
     rng = np.random.default_rng(M * N + int(kernel))
     cx, cw = wl.random_codes(3, M, K), wl.random_codes(4, N, K)
     xs = np.exp(rng.standard_normal(M) * 0.5).astype(np.float32) * 0.05
@@ -157,7 +157,7 @@ def test_every_decode_kernel_fp16_and_leading_dimension(gpu, monkeypatch, kernel
     assert np.array_equal(gpu_gemm(gpu, cx, cw, ldy=N + 8).astype(np.int64), acc)
 
 
-def test_decode_seeded_random_shapes(gpu, monkeypatch):
+def test_decode_seeded_random_shapes(gpu, tune):
     """Thirty seeded shapes (M up to 16, N a multiple of 16 up to 9600, K a multiple of 64 up to 6144) through
     every decode kernel that takes them and through the dispatcher's own choice: accumulators bit-exact, nothing
     written past N."""
@@ -172,7 +172,7 @@ def test_decode_seeded_random_shapes(gpu, monkeypatch):
             if kernel == "1" and M > 2:
                 continue
             print("case", case, M, N, K, "kernel", kernel, flush=True)
-            monkeypatch.setenv("SMOOTHROT_DECODE_KERNEL", kernel)
+            tune(gpu.SR_TUNE_DECODE_KERNEL, kernel)
             assert np.array_equal(gpu_gemm(gpu, cx, cw, ldy=N + 8).astype(np.int64), want), (M, N, K, kernel)
 
 
