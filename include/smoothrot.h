@@ -267,7 +267,9 @@ SR_API int sr_w4a4_linear_decode(const void *X_f16, int64_t M, int64_t K, int64_
  * accumulation of integers / 64 below 2^24).  The operands are kept in "f6 tiles", a layout the
  * matrix instruction reads without any unpacking:
  *
- *   a code matrix [rows, K] (K % 128 == 0; rows padded with zero codes to a multiple of 8) is
+ *   a code matrix [rows, K] (K % 128 == 0; rows padded to a multiple of 8 -- the padding rows may hold
+ *   anything: sr_pack_f6_tiles writes zero codes there, sr_fwht_quant_act_f6 leaves them unwritten, and
+ *   the GEMM multiplies them but never stores their outputs; every 6-bit pattern is a finite number) is
  *   cut into blocks of 8 rows x 128 codes; block (R, C) is 768 bytes at ((C * rows/8) + R) * 768
  *   (all row blocks of one 128-code chunk are contiguous);
  *   inside it, piece (r, t, g) = codes k = 128 C + 64 t + 32 g + j, j = 0..31, of row 8 R + r,

@@ -8,6 +8,7 @@ import torch
 
 from oracle import smoothrot_oracle as o
 import workloads as wl
+import f6_codec as fc
 from parity import check_codes, check_output, check_scales
 
 pytestmark = pytest.mark.gpu
@@ -79,7 +80,7 @@ def test_layer_group(gpu, group):
         Y6 = gpu.sr_w4a4_gemm_f6(X6, xs6, W6, ws, M, N, K, gpu.SR_F16)
         torch.cuda.synchronize()
         assert np.array_equal(xs6.cpu().numpy(), xs.cpu().numpy())
-        cx6_all = o.f6_codes(o.f6_tiles_unpack(X6.cpu().numpy(), M, K))
+        cx6_all = fc.f6_codes(fc.f6_tiles_unpack(X6.cpu().numpy(), M, K))
         check_codes(cx6_all[ROWS], act["codes"], act["t"], name + " activation codes (f6 path)")
         assert np.count_nonzero(cx6_all != cx_all) <= 1e-5 * cx_all.size
         assert np.array_equal(acc6[ROWS], o.gemm_i32_c(cx6_all[ROWS], cw_all))

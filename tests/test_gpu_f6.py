@@ -10,6 +10,7 @@ import torch
 
 from oracle import smoothrot_oracle as o
 import workloads as wl
+import f6_codec as fc
 from parity import check_codes, check_output, check_scales
 
 pytestmark = pytest.mark.gpu
@@ -24,7 +25,7 @@ def test_pack_matches_the_format_definition(gpu, rows, K):
     print("case", rows, K, flush=True)
     c = wl.random_codes(rows * 3 + K, rows, K)
     got = tiles(gpu, c).cpu().numpy()
-    want = o.f6_tiles_pack(c)
+    want = fc.f6_tiles_pack(c)
     assert got.size >= want.size and np.array_equal(got[:want.size], want)      # padding rows are zero codes here
 
 
@@ -146,7 +147,7 @@ def quant_f6(sr, X, inv_s, clip):
     inv = None if inv_s is None else torch.from_numpy(inv_s).cuda()
     X6, xs = sr.sr_fwht_quant_act_f6(torch.from_numpy(X).cuda(), inv, clip)
     torch.cuda.synchronize()
-    return o.f6_codes(o.f6_tiles_unpack(X6.cpu().numpy(), M, K)), xs.cpu().numpy(), X6
+    return fc.f6_codes(fc.f6_tiles_unpack(X6.cpu().numpy(), M, K)), xs.cpu().numpy(), X6
 
 
 @pytest.mark.parametrize("K", [128, 256, 512, 1024, 2048, 4096, 8192, 896, 1792, 3584, 14336])
@@ -196,6 +197,34 @@ def test_quantiser_tiles_wave_kernel(gpu, M, smooth):
         check_scales(xs, ref["x_scale"])
         check_codes(codes, ref["codes"], ref["t"])
         assert codes.min() >= -8 and codes.max() <= 7
+
+
+@pytest.mark.parametrize("M,K", [(13, 512), (1027, 4096), (33, 14336)])
+def test_padding_rows_of_the_activation_tiles_cannot_leak(gpu, M, K):
+    """The quantiser leaves the rows that pad the last block of 8 unwritten, so the GEMM multiplies whatever the
+    buffer held there.  With the tile buffer pre-filled with 0xFF (the 6-bit pattern 63 = -7.5 in every field, the
+    largest magnitude the format has) both outputs must be exactly what they are on a zero-filled buffer, and
+    nothing beyond row M - 1 of a larger output may be written."""
+    X = wl.gauss_acts(3 + M, M, K, 3, 200.0)
+    inv_s = np.random.default_rng(K + M).uniform(0.25, 4.0, K).astype(np.float32)
+    Xd, inv = torch.from_numpy(X).cuda(), torch.from_numpy(inv_s).cuda()
+    N = 272
+    W6 = tiles(gpu, wl.random_codes(5 + K, N, K))
+    ws = torch.from_numpy(np.random.default_rng(1).uniform(1e-3, 2e-3, N).astype(np.float32)).cuda()
+    outs = []
+    for fill in (0x00, 0xFF):
+        X6 = torch.full((gpu.sr_f6_tiles_bytes(M, K),), fill, dtype=torch.uint8, device="cuda")
+        X6, xs = gpu.sr_fwht_quant_act_f6(Xd, inv, 0.9, X6=X6)
+        acc = torch.full((M + 9, N), -7, dtype=torch.int32, device="cuda")
+        Y = torch.full((M + 9, N), -7.0, dtype=torch.float16, device="cuda")
+        gpu.sr_w4a4_gemm_f6(X6, None, W6, None, M, N, K, gpu.SR_I32, acc[:M])
+        gpu.sr_w4a4_gemm_f6(X6, xs, W6, ws, M, N, K, gpu.SR_F16, Y[:M])
+        torch.cuda.synchronize()
+        assert bool((acc[M:] == -7).all()) and bool((Y[M:] == -7.0).all())
+        assert bool(torch.isfinite(Y[:M]).all())
+        outs.append((acc[:M].clone(), Y[:M].clone(), xs.clone()))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
 
 
 @pytest.mark.parametrize("M,K", [(1100, 4096), (2048, 4096), (40, 4096), (64, 14336), (300, 14336), (1100, 14336), (600, 7168)])
@@ -253,11 +282,11 @@ def test_row_kernel_walking_over_rows(gpu, tune, M):
         assert np.array_equal(a, b)
     ref = o.fwht_quant_act(X, inv_s, 0.9)
     check_scales(walk[1], ref["x_scale"])
-    check_codes(o.f6_codes(o.f6_tiles_unpack(walk[0], M, K)), ref["codes"], ref["t"])
+    check_codes(fc.f6_codes(fc.f6_tiles_unpack(walk[0], M, K)), ref["codes"], ref["t"])
     check_codes(o.unpack_int4(walk[2]), ref["codes"], ref["t"])
     ref = o.fwht_quant_act(X, None, 0.9)
     check_scales(walk[5], ref["x_scale"])
-    check_codes(o.f6_codes(o.f6_tiles_unpack(walk[4], M, K)), ref["codes"], ref["t"])
+    check_codes(fc.f6_codes(fc.f6_tiles_unpack(walk[4], M, K)), ref["codes"], ref["t"])
     check_codes(o.unpack_int4(walk[6]), ref["codes"], ref["t"])
 
 
@@ -271,7 +300,7 @@ def test_gated_prologue_tiles(gpu, M, K):
     X6, xs = gpu.sr_swiglu_fwht_quant_act_f6(Gd, Ud, inv_d, 0.9)
     Xq, xs4 = gpu.sr_swiglu_fwht_quant_act(Gd, Ud, inv_d, 0.9)
     torch.cuda.synchronize()
-    codes = o.f6_codes(o.f6_tiles_unpack(X6.cpu().numpy(), M, K))
+    codes = fc.f6_codes(fc.f6_tiles_unpack(X6.cpu().numpy(), M, K))
     ref = o.fwht_quant_swiglu(G, U, inv_s, 0.9)
     check_scales(xs.cpu().numpy(), ref["x_scale"])
     check_codes(codes, ref["codes"], ref["t"])
@@ -296,9 +325,9 @@ def test_cfg2_layer_through_the_f6_path(gpu):
     acc = gpu.sr_w4a4_gemm_f6(X6, None, W6, None, M, N, K, gpu.SR_I32)
     torch.cuda.synchronize()
     cw = o.unpack_int4(Wq.cpu().numpy())
-    assert np.array_equal(o.f6_codes(o.f6_tiles_unpack(W6.cpu().numpy(), N, K)), cw)
+    assert np.array_equal(fc.f6_codes(fc.f6_tiles_unpack(W6.cpu().numpy(), N, K)), cw)
     ref = o.fwht_quant_act(X, inv_s.cpu().numpy(), 0.9)
-    cx = o.f6_codes(o.f6_tiles_unpack(X6.cpu().numpy(), M, K))
+    cx = fc.f6_codes(fc.f6_tiles_unpack(X6.cpu().numpy(), M, K))
     check_scales(xs.cpu().numpy(), ref["x_scale"])
     check_codes(cx, ref["codes"], ref["t"])
     rows = np.unique(np.r_[0:4, 1000:1003, M - 4:M])

@@ -161,7 +161,7 @@ def test_heads_cfg2_rows_and_fold_identity(gpu):
 def test_fold_ex_reports_the_fixed_ratio_for_many_output_channels(gpu, nh):
     """More than 1024 output channels of K = 4096 without a search run in the wave-per-row kernel, which does not
     report a ratio itself: w_ratio must still come back as the fixed ratio for every channel (a buffer pre-filled
-    with another value shows a missing write), and the full-Hadamard case must equal the plain fold bit for bit."""
+    with another value shows a missing write); codes and scales against the oracle as everywhere."""
     K, N = 4096, 1040
     W = wl.cfg2_W(4096)[:, :N].copy()
     a = np.abs(np.random.default_rng(3).standard_normal(K)).astype(np.float32) * 4 + 0.05
@@ -169,16 +169,12 @@ def test_fold_ex_reports_the_fixed_ratio_for_many_output_channels(gpu, nh):
     Wq, ws, inv_s, ratio = gpu.sr_fold_smooth_rotate_quant_ex(dev(W), dev(a), 0.5, nh, True, 1, 0.95, w_ratio=ratio)
     torch.cuda.synchronize()
     assert np.all(ratio.cpu().numpy() == np.float32(0.95))
-    if nh == 0:
-        Wq0, ws0, inv0 = gpu.sr_fold_smooth_rotate_quant(dev(W), dev(a), 0.5, 0.95)
-        torch.cuda.synchronize()
-        assert torch.equal(Wq, Wq0) and torch.equal(ws, ws0) and torch.equal(inv_s, inv0)
-    else:
-        s = o.smoothing_factors(a.astype(np.float64), W, 0.5)
-        what_t = o.rotate_heads(np.ascontiguousarray((s[:, None] * W.astype(np.float64)).T), nh, True) / nh
-        c_ref, d_ref, t_ref = o.quant_sym_int4(what_t, 0.95)
-        check_scales(ws.cpu().numpy(), d_ref, "heads fold scale")
-        check_codes(o.unpack_int4(Wq.cpu().numpy()), c_ref, t_ref, "heads fold codes")
+    s = o.smoothing_factors(a.astype(np.float64), W, 0.5)
+    sw_t = np.ascontiguousarray((s[:, None] * W.astype(np.float64)).T)
+    what_t = o.rotate(sw_t) / K if nh == 0 else o.rotate_heads(sw_t, nh, True) / nh
+    c_ref, d_ref, t_ref = o.quant_sym_int4(what_t, 0.95)
+    check_scales(ws.cpu().numpy(), d_ref, "fold scale")
+    check_codes(o.unpack_int4(Wq.cpu().numpy()), c_ref, t_ref, "fold codes")
 
 
 # ------------------------------------------------------------------ weight clipping-ratio search
