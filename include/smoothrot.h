@@ -15,8 +15,9 @@
  * ------------------------------------
  *  - Every data pointer is DEVICE memory owned by the caller.  The library never
  *    allocates, frees or keeps a pointer and is re-entrant.  Its only process-wide
- *    state: the tuning knobs of sr_tune_set (all "auto" unless a caller sets one) and a
- *    cached compute-unit count per device.  No environment variable is read.
+ *    state: the tuning knobs of sr_tune_set (all "auto" unless a caller sets one), a
+ *    cached compute-unit count per device, and the device-resident scratch array of
+ *    sr_fold_smooth_rotate_quant_noalloc.  No environment variable is read.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *    only enqueue work and return; they never synchronise.
  *  - Arguments are validated on the host before anything is launched.  On error a
@@ -134,6 +135,26 @@ SR_API int sr_fold_smooth_rotate_quant(const void *W_f16, int64_t K, int64_t N, 
                                 const float *act_absmax, float alpha, float w_clip,
                                 uint8_t *Wq, float *w_scale, float *inv_s,
                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * sr_fold_smooth_rotate_quant for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments
+ * without the workspace, same kernels, same results bit for bit.  The scratch (the fp16 transposed weight
+ * and two fp32 [K] vectors) lives in a device-resident array of sr_noalloc_scratch_bytes() bytes
+ * (32.25 MiB) that every GPU the library runs on holds until the process ends; the call itself allocates
+ * and frees nothing.
+ *   - Shapes whose sr_fold_workspace_bytes(K, N) exceeds that size (K * N > 16 Mi weights, e.g.
+ *     4096 x 14336) return SR_ERR_WORKSPACE; use the call above with a workspace for those.
+ *   - All calls on one GPU share the one array: two calls whose kernels overlap on the same GPU
+ *     (different streams, different threads) race.  Nothing in it has to start at zero -- every word a
+ *     kernel reads was written earlier in the same call -- so consecutive calls need no clearing.
+ *   - The first call on a device asks the runtime for the array's address (no allocation); make that
+ *     call outside a stream capture.
+ */
+SR_API size_t sr_noalloc_scratch_bytes(void);
+SR_API int sr_fold_smooth_rotate_quant_noalloc(const void *W_f16, int64_t K, int64_t N, int64_t ldw,
+                                        const float *act_absmax, float alpha, float w_clip,
+                                        uint8_t *Wq, float *w_scale, float *inv_s, void *stream);
 
 /*
  * Online rotation + per-token quantisation (paper: online Hadamard before the

@@ -34,6 +34,8 @@ _SIGNATURES = {
     "sr_gemm_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "sr_calib_absmax": (_int, [_vp, _i64, _i64, _i64, _vp, _vp]),
     "sr_fold_smooth_rotate_quant": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "sr_noalloc_scratch_bytes": (_sz, []),
+    "sr_fold_smooth_rotate_quant_noalloc": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _f32, _vp, _vp, _vp, _vp]),
     "sr_fwht_quant_act": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _vp]),
     "sr_w4a4_gemm": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _int, _vp, _sz, _vp]),
     "sr_swiglu_fwht_quant_act": (_int, [_vp, _vp, _i64, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _vp]),
@@ -146,6 +148,21 @@ def sr_fold_smooth_rotate_quant(W, act_absmax, alpha: float, w_clip: float = 1.0
                                              _ptr(Wq), _ptr(w_scale), _ptr(inv_s), _ptr(workspace),
                                              workspace.numel(), _stream()),
            "sr_fold_smooth_rotate_quant")
+    return Wq, w_scale, inv_s
+
+
+def sr_noalloc_scratch_bytes() -> int:
+    return int(raw().sr_noalloc_scratch_bytes())
+
+
+def sr_fold_smooth_rotate_quant_noalloc(W, act_absmax, alpha: float, w_clip, Wq, w_scale, inv_s):
+    """sr_fold_smooth_rotate_quant on the library's device-resident scratch: the caller passes every output
+    (nothing is allocated here either); returns (Wq, w_scale, inv_s)."""
+    _dev(W, torch.float16, "W"); _dev(Wq, torch.uint8, "Wq"); _dev(w_scale, torch.float32, "w_scale")
+    K, N = W.shape
+    _check(raw().sr_fold_smooth_rotate_quant_noalloc(_ptr(W), K, N, W.stride(0), _ptr(act_absmax), alpha, w_clip,
+                                                     _ptr(Wq), _ptr(w_scale), _ptr(inv_s), _stream()),
+           "sr_fold_smooth_rotate_quant_noalloc")
     return Wq, w_scale, inv_s
 
 

@@ -14,7 +14,30 @@ static_assert(kTuneCount == 7, "one initialiser per knob");
 int64_t tune(int knob) { return g_tune[knob].load(std::memory_order_relaxed); }
 }  // namespace sr
 
+// ---- device-resident scratch of the entry point that allocates nothing -------------------------------------
+// One array per GPU the library is loaded on, held until the process ends.  In host code the array's name is
+// only a handle: its device address is asked for once per device (with that device current) and kept.
+constexpr size_t kNoallocScratchBytes = (size_t)32 * 1024 * 1024 + 2 * 128 * 1024;   // fold of 16 Mi weights
+static __device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
+
 namespace {
+
+std::atomic<void *> g_scratch_ptr[64];
+
+// device address of `scratch` on the current device (nullptr and *err set if the runtime refuses)
+void *scratch_on_current_device(hipError_t *err)
+{
+    int dev = 0;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= 64) { *err = hipErrorInvalidDevice; return nullptr; }
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess || !p) { if (*err == hipSuccess) *err = hipErrorInvalidSymbol; return nullptr; }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // two racing first calls store the same address
+    return p;
+}
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -156,6 +179,30 @@ int sr_fold_smooth_rotate_quant(const void *W_f16, int64_t K, int64_t N, int64_t
 {
     return fold_impl(W_f16, K, N, ldw, act_absmax, alpha, 0, 0, 1, w_clip, false, Wq, w_scale, inv_s, nullptr,
                      workspace, workspace_bytes, stream);
+}
+
+size_t sr_noalloc_scratch_bytes(void) { return kNoallocScratchBytes; }
+
+int sr_fold_smooth_rotate_quant_noalloc(const void *W_f16, int64_t K, int64_t N, int64_t ldw,
+                                        const float *act_absmax, float alpha, float w_clip,
+                                        uint8_t *Wq, float *w_scale, float *inv_s, void *stream)
+{
+    // size first: a shape beyond the array is refused whatever else is wrong with the call
+    if (K > 0 && N > 0 && N % 16 == 0 && sr::hadamard_supported(K) && fold_ws(K, N).total > kNoallocScratchBytes)
+        return SR_ERR_WORKSPACE;
+    // argument errors must not depend on the device: validate with a stand-in workspace address, launch nothing
+    if (K <= 0 || N <= 0 || N % 16 != 0 || ldw < N) return SR_ERR_SHAPE;
+    if (!sr::hadamard_supported(K)) return SR_ERR_UNSUPPORTED_K;
+    if (!(alpha >= 0.f && alpha <= 1.f) || !(w_clip > 0.f && w_clip <= 1.f)) return SR_ERR_ARG;
+    if (!W_f16 || !Wq || !w_scale) return SR_ERR_NULL;
+    if (ldw % 8 != 0 || !aligned16(W_f16) || !aligned16(Wq) || !aligned16(w_scale) ||
+        (act_absmax && !aligned16(act_absmax)) || (inv_s && !aligned16(inv_s)))
+        return SR_ERR_ALIGN;
+    hipError_t e = hipSuccess;
+    void *ws = scratch_on_current_device(&e);
+    if (!ws) return SR_ERR_DEVICE;
+    return fold_impl(W_f16, K, N, ldw, act_absmax, alpha, 0, 0, 1, w_clip, false, Wq, w_scale, inv_s, nullptr,
+                     ws, kNoallocScratchBytes, stream);
 }
 
 int sr_fold_smooth_rotate_quant_ex(const void *W_f16, int64_t K, int64_t N, int64_t ldw,

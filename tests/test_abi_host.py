@@ -23,7 +23,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = declared_symbols()
-    assert len(names) == 21 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
+    assert len(names) == 23 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
     lib = ctypes.CDLL(sr.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -39,6 +39,18 @@ def test_tuning_knobs_round_trip_and_reject_unknown_ones():
         assert sr.sr_tune_get(knob) == sr.SR_TUNE_AUTO
     assert sr.raw().sr_tune_set(7, 1) == sr.SR_ERR_ARG and sr.raw().sr_tune_set(-1, 1) == sr.SR_ERR_ARG
     assert sr.sr_tune_get(99) == sr.SR_TUNE_AUTO
+
+
+def test_noalloc_fold_checks_size_and_arguments_before_any_device_call():
+    f = sr.raw().sr_fold_smooth_rotate_quant_noalloc
+    assert sr.sr_noalloc_scratch_bytes() >= sr.sr_fold_workspace_bytes(4096, 4096)
+    assert f(A, 4096, 14336, 14336, A, 0.5, 1.0, A, A, A, None) == sr.SR_ERR_WORKSPACE
+    assert f(A, 4096, 4160, 4160, A, 0.5, 1.0, A, A, A, None) == sr.SR_ERR_WORKSPACE
+    assert f(A, 500, 64, 64, A, 0.5, 1.0, A, A, A, None) == sr.SR_ERR_UNSUPPORTED_K
+    assert f(A, 512, 60, 64, A, 0.5, 1.0, A, A, A, None) == sr.SR_ERR_SHAPE
+    assert f(None, 512, 64, 64, A, 0.5, 1.0, A, A, A, None) == sr.SR_ERR_NULL
+    assert f(A, 512, 64, 64, A, 1.5, 1.0, A, A, A, None) == sr.SR_ERR_ARG
+    assert f(A + 4, 512, 64, 64, A, 0.5, 1.0, A, A, A, None) == sr.SR_ERR_ALIGN
 
 
 def test_status_strings():
