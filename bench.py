@@ -32,11 +32,163 @@ if ROOT not in sys.path:
 PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, TOP/s
 PEAK_FP6_TOPS = 10100.0      # MI355X dense fp6 / fp4 MFMA, TFLOP/s (the instruction the fast GEMM issues)
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, GB/s
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "bench_prefill_cfg2_hbm_traffic.json")
+
+
+def measured_traffic(kernel_key):
+    """HBM bytes per launch of a kernel of the timed step, as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    and committed under profiles/ (None if the file or the entry is missing: the counters cannot be read from
+    inside this process)."""
+    try:
+        with open(TRAFFIC_JSON) as f:
+            t = json.load(f)
+        e = t["kernels"][kernel_key]
+        return {"hbm_bytes_per_launch": e["read_bytes"] + e["written_bytes"], "read_bytes": e["read_bytes"],
+                "written_bytes": e["written_bytes"], "algorithmic_bytes": e["algorithmic_bytes"],
+                "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size; "
+                          "profiles/bench_prefill_cfg2_hbm_traffic.json (tree %s)" % t.get("tree", "?")}
+    except (OSError, KeyError, ValueError):
+        return None
 
 M, K = 2048, 4096
 NS = (4096, 14336)
 CLIP, ALPHA = 0.9, 0.5
 SETS = 8                     # distinct (X, Wq) sets rotated through: 8 * (16.8 + 37.7) MB > 256 MB
+
+
+def cfg5_chained(sr, wl, torch, dev, graph_time, ev_time, args):
+    """Config 5: the seven linears of a LLaMA-3.1-8B-shaped decoder layer on 16384 tokens, W4A4 end to end on
+    random-init weights, chained as the paper's Fig. 2 draws the blocks:
+        Xa --rotate+quantise--> [q|k|v] one GEMM, N = 6144                  (folded as ONE weight: shared input, shared s)
+        Xo --rotate+quantise--> o,      N = 4096                            (Xo: stand-in for the attention core's output)
+        Xf --rotate+quantise--> [gate|up] one GEMM, N = 28672               (1/s of the down-projection absorbed into W_up)
+        silu(gate) * up --rotate (H_28 x H_512)+quantise, no factors--> down, K = 14336 -> N = 4096
+    The gate/up outputs ARE the down-projection's input (sr_swiglu_fwht_quant_act_f6 reads them in place).
+    Left out and not timed: RMS-normalisation, residual additions, RoPE, softmax(QK^T)V, KV-cache quantisation --
+    Xa, Xo, Xf are generated RMS-normalised tensors with the outlier channels of config 2.
+    Offline, timed separately: calibration absmax of the four inputs (the down-projection's on the fp16 layer's own
+    silu(gate) * up, as the paper calibrates on the fp16 model) and the four folds that cover the seven weights."""
+    import numpy as np
+    M5, K, KD, NQ, NG = 16384, 4096, 14336, 6144, 28672
+    out = {}
+    Xa, Xo, Xf = (torch.from_numpy(wl.cfg5_X(M5, K, stream=40 + j)).to(dev) for j in range(3))
+    Wd = {n: torch.from_numpy(wl.cfg5_W(n)).to(dev) for n, _, _ in wl.CFG5_LINEARS}
+    # ---- calibration (offline): one absmax pass per distinct input
+    am = {k: torch.zeros(K, dtype=torch.float32, device=dev) for k in ("a", "o", "f")}
+    calib_us = {}
+    for k, X in (("a", Xa), ("o", Xo), ("f", Xf)):
+        sr.sr_calib_absmax(X, am[k])
+        scratch = torch.zeros(K, dtype=torch.float32, device=dev)
+        calib_us[k] = ev_time(lambda i: sr.sr_calib_absmax(X, scratch), 3) * 1e6
+    # the down-projection's input on the fp16 layer (plain fp16 matmuls: calibration runs on the unquantised model)
+    D = torch.empty((M5, KD), dtype=torch.float16, device=dev)
+    for r in range(0, M5, 4096):
+        g = Xf[r:r + 4096] @ Wd["gate"]
+        u = Xf[r:r + 4096] @ Wd["up"]
+        D[r:r + 4096] = (torch.nn.functional.silu(g.float()) * u.float()).to(torch.float16)
+    am_d = torch.zeros(KD, dtype=torch.float32, device=dev)
+    sr.sr_calib_absmax(D, am_d)
+    scratch = torch.zeros(KD, dtype=torch.float32, device=dev)
+    calib_us["down"] = ev_time(lambda i: sr.sr_calib_absmax(D, scratch), 3) * 1e6
+    del D, g, u
+    # ---- folds (offline): down first (its 1/s goes into W_up), then the fused weights
+    def fold(W, a, what):
+        Kw, Nw = W.shape
+        work = torch.empty(sr.sr_fold_workspace_bytes(Kw, Nw), dtype=torch.uint8, device=dev)
+        outs = sr.sr_fold_smooth_rotate_quant(W, a, ALPHA, 1.0, workspace=work)
+        torch.cuda.synchronize()
+        t = ev_time(lambda i: sr.sr_fold_smooth_rotate_quant(W, a, ALPHA, 1.0, *outs, workspace=work), 3)
+        t6 = sr.sr_pack_f6_tiles(outs[0])
+        out.setdefault("offline_us", {})["fold_" + what] = round(t * 1e6, 1)
+        return t6, outs[1], outs[2], outs[0]
+    W6d, wsd, inv_d, Wqd = fold(Wd["down"], am_d, "down_14336x4096")
+    W_up_abs = (Wd["up"].float() * inv_d[None, :]).to(torch.float16)          # Lambda^-1 of the down-projection, absorbed
+    W6q, wsq, inv_q, Wqq = fold(torch.cat([Wd["q"], Wd["k"], Wd["v"]], 1).contiguous(), am["a"], "qkv_4096x6144")
+    W6o, wso, inv_o, Wqo = fold(Wd["o"], am["o"], "o_4096x4096")
+    W6g, wsg, inv_g, Wqg = fold(torch.cat([Wd["gate"], W_up_abs], 1).contiguous(), am["f"], "gateup_4096x28672")
+    del Wd, W_up_abs
+    for k, v in calib_us.items():
+        out["offline_us"]["calib_absmax_" + k] = round(v, 1)
+    # ---- the chained layer (timed)
+    X6 = torch.zeros(sr.sr_f6_tiles_bytes(M5, K), dtype=torch.uint8, device=dev)
+    X6d = torch.zeros(sr.sr_f6_tiles_bytes(M5, KD), dtype=torch.uint8, device=dev)
+    xs = torch.empty(M5, dtype=torch.float32, device=dev)
+    QKV = torch.empty((M5, NQ), dtype=torch.float16, device=dev)
+    O = torch.empty((M5, K), dtype=torch.float16, device=dev)
+    GU = torch.empty((M5, NG), dtype=torch.float16, device=dev)
+    DN = torch.empty((M5, K), dtype=torch.float16, device=dev)
+
+    def layer(i):
+        sr.sr_fwht_quant_act_f6(Xa, inv_q, CLIP, X6, xs, warm=W6q)
+        sr.sr_w4a4_gemm_f6(X6, xs, W6q, wsq, M5, NQ, K, sr.SR_F16, QKV)
+        sr.sr_fwht_quant_act_f6(Xo, inv_o, CLIP, X6, xs, warm=W6o)
+        sr.sr_w4a4_gemm_f6(X6, xs, W6o, wso, M5, K, K, sr.SR_F16, O)
+        sr.sr_fwht_quant_act_f6(Xf, inv_g, CLIP, X6, xs, warm=W6g)
+        sr.sr_w4a4_gemm_f6(X6, xs, W6g, wsg, M5, NG, K, sr.SR_F16, GU)
+        sr.sr_swiglu_fwht_quant_act_f6(GU[:, :KD], GU[:, KD:], None, CLIP, X6d, xs)
+        sr.sr_w4a4_gemm_f6(X6d, xs, W6d, wsd, M5, K, KD, sr.SR_F16, DN)
+    layer(0)
+    torch.cuda.synchronize()
+    t = ev_time(layer, 5)
+    ops5 = sum(2.0 * M5 * kk * nn for _, kk, nn in wl.CFG5_LINEARS)
+    out["cfg5_layer_M16384"] = {
+        "ms": round(t * 1e3, 3), "TOPS": round(ops5 / t / 1e12, 1),
+        "frac_int8_mfma_peak": round(ops5 / t / 1e12 / PEAK_INT8_TOPS, 4),
+        "workload": "chained layer, 16384 tokens, FP6-pipe path: [q|k|v] as one N=6144 GEMM, o, [gate|up] as one N=28672 GEMM "
+                    "(1/s of down absorbed into W_up), silu(gate)*up read in place by the fused K=14336 rotate+quantise, down; "
+                    "4 rotate/quantise launches + 4 GEMMs; left out: RMS-normalise, residual adds, RoPE, attention core, KV quantiser"}
+    # the same chain through the canonical-nibble quantiser and the int8-MFMA GEMM
+    Xq = torch.empty((M5, K // 2), dtype=torch.uint8, device=dev)
+    Xqd = torch.empty((M5, KD // 2), dtype=torch.uint8, device=dev)
+
+    def layer_i8(i):
+        sr.sr_fwht_quant_act(Xa, inv_q, CLIP, Xq, xs)
+        sr.sr_w4a4_gemm(Xq, xs, Wqq, wsq, sr.SR_F16, QKV)
+        sr.sr_fwht_quant_act(Xo, inv_o, CLIP, Xq, xs)
+        sr.sr_w4a4_gemm(Xq, xs, Wqo, wso, sr.SR_F16, O)
+        sr.sr_fwht_quant_act(Xf, inv_g, CLIP, Xq, xs)
+        sr.sr_w4a4_gemm(Xq, xs, Wqg, wsg, sr.SR_F16, GU)
+        sr.sr_swiglu_fwht_quant_act(GU[:, :KD], GU[:, KD:], None, CLIP, Xqd, xs)
+        sr.sr_w4a4_gemm(Xqd, xs, Wqd, wsd, sr.SR_F16, DN)
+    layer_i8(0)
+    torch.cuda.synchronize()
+    t8 = ev_time(layer_i8, 3)
+    out["cfg5_layer_M16384_int8"] = {"ms": round(t8 * 1e3, 3), "TOPS": round(ops5 / t8 / 1e12, 1),
+                                     "frac_int8_mfma_peak": round(ops5 / t8 / 1e12 / PEAK_INT8_TOPS, 4),
+                                     "workload": "the same chain through sr_fwht_quant_act / sr_swiglu_fwht_quant_act and sr_w4a4_gemm"}
+    # the rotation + quantiser launches of the layer on their own
+    t = graph_time(lambda i: sr.sr_fwht_quant_act_f6((Xa, Xo, Xf)[i % 3], inv_g, CLIP, X6, xs), 6)
+    b = M5 * K * 2.75 + 4 * M5
+    out["fwht_quant_f6_K4096_M16384"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
+                                         "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+    t = graph_time(lambda i: sr.sr_swiglu_fwht_quant_act_f6(GU[:, :KD], GU[:, KD:], None, CLIP, X6d, xs), 4)
+    b = M5 * KD * 4.75 + 4 * M5
+    out["swiglu_fwht_quant_f6_K14336_M16384"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
+                                                 "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+    # ---- the oracle on a seeded 256-row subsample of the same chain, extrapolated x 64 (all host cores)
+    if not args.no_cpu_baseline:
+        from oracle import smoothrot_oracle as o
+        rows = np.sort(np.random.default_rng(5).choice(M5, 256, replace=False))
+        ridx = torch.from_numpy(rows).to(dev)
+        h = lambda tns: tns.cpu().numpy()
+        xa, xo, xf = h(Xa[ridx]), h(Xo[ridx]), h(Xf[ridx])
+        cw = {k: o.unpack_int4(h(v)) for k, v in (("q", Wqq), ("o", Wqo), ("g", Wqg), ("d", Wqd))}
+        sc = {k: h(v).astype(np.float64) for k, v in (("q", wsq), ("o", wso), ("g", wsg), ("d", wsd))}
+        iv = {k: h(v).astype(np.float64) for k, v in (("q", inv_q), ("o", inv_o), ("g", inv_g))}
+        o.gemm_i32_c(np.zeros((1, 64), np.int8), np.zeros((1, 64), np.int8))
+        t0 = time.perf_counter()
+        for x, k in ((xa, "q"), (xo, "o")):
+            act = o.fwht_quant_act(x, iv[k], CLIP)
+            o.dequant_out(o.gemm_i32_c(act["codes"], cw[k]), act["x_scale"], sc[k])
+        act = o.fwht_quant_act(xf, iv["g"], CLIP)
+        gu = o.dequant_out(o.gemm_i32_c(act["codes"], cw["g"]), act["x_scale"], sc["g"]).astype(np.float16)
+        act = o.fwht_quant_swiglu(gu[:, :KD], gu[:, KD:], None, CLIP)
+        o.dequant_out(o.gemm_i32_c(act["codes"], cw["d"]), act["x_scale"], sc["d"])
+        tc = time.perf_counter() - t0
+        out["cfg5_layer_M16384"]["cpu_baseline_extrapolated"] = {
+            "value": round(ops5 / (tc * 64) / 1e12, 5), "unit": "TOPS", "cores": o.c_threads(), "kind": "oracle",
+            "sample": "256 seeded rows of 16384 through the whole chain against the full weights: %.1f s, x 64 = %.0f s (extrapolated)" % (tc, tc * 64)}
+    return out
 
 
 def main():
@@ -193,9 +345,54 @@ def main():
                 "achieved": round(gemm_ops / gemm_avg_s / 1e12, 2), "peak": PEAK_FP6_TOPS, "unit": "TFLOP/s",
                 "frac": round(gemm_ops / gemm_avg_s / 1e12 / PEAK_FP6_TOPS, 4),
                 "frac_int8_mfma_peak": round(gemm_ops / gemm_avg_s / 1e12 / PEAK_INT8_TOPS, 4),
-                "traffic": {"hbm_bytes_per_launch": 197.5e6, "algorithmic_bytes": 109.0e6,
-                            "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/"},
+                "traffic": measured_traffic("gemm_f6_N14336"),
                 "avg_launch_us": round(gemm_avg_s * 1e6, 2), "median_launch_us": round(gemm_ms[len(gemm_ms) // 2] * 1e3, 2)}
+
+    # ---------------- measured ceilings (committed measurement kernels of the library) ------
+    # What this machine sustains with nothing else in the way, measured in this process: a bare issue loop of the
+    # matrix instruction the GEMM uses on code-valued operands, a pure read of one packed weight (29.4 MB) over 20
+    # rotating copies, a bare fp32 vector-ALU loop.  Every fraction of a published peak below is also given
+    # against these.
+    ceil = {}
+    if not args.no_extra:
+        CU = torch.cuda.get_device_properties(0).multi_processor_count
+        f6_src = W6[4096][0]
+        # ~60 us launches (the length of the N = 14336 GEMM), back to back in a graph
+        ops = [0.0]
+        def f6_loop(i):
+            ops[0] = sr.sr_ceiling_mfma_f6(f6_src, 170, CU)
+        t = graph_time(f6_loop, 40)
+        ceil["mfma_f6_loop"] = {"us": round(t * 1e6, 2), "PFLOP/s": round(ops[0] / t / 1e15, 3),
+                                "what": "v_mfma_scale_f32_32x32x64_f8f6f4 on 6-bit code fields, 8 waves per CU, 8 accumulator tiles per wave, no loads"}
+        i8_src = Wq[4096][0]
+        def i8_loop(i):
+            ops[0] = sr.sr_ceiling_mfma_i8(i8_src, 170, CU)
+        t = graph_time(i8_loop, 40)
+        ceil["mfma_i8_loop"] = {"us": round(t * 1e6, 2), "POP/s": round(ops[0] / t / 1e15, 3),
+                                "what": "v_mfma_i32_32x32x32_i8 on packed code bytes, same loop"}
+        def valu_loop(i):
+            ops[0] = sr.sr_ceiling_valu_f32(16, 2 * CU)
+        t = graph_time(valu_loop, 60)
+        ceil["valu_f32_loop"] = {"us": round(t * 1e6, 2), "T_wave_instr/s": round(ops[0] / t / 1e12, 3),
+                                 "implied_GHz": round(ops[0] / t * 4 / (4 * CU) / 1e9, 3),
+                                 "what": "fp32 add/sub/mul on 64 lanes, 2 waves per SIMD; 4 cycles per instruction and SIMD"}
+        rd = [Wq[14336][0].clone() for _ in range(20)]                         # 20 x 29.4 MB = 587 MB
+        best = None
+        for grid, block, fl, nt in ((8 * CU, 256, 8, True), (4 * CU, 512, 8, True), (8 * CU, 256, 16, True),
+                                    (16 * CU, 256, 4, True), (8 * CU, 256, 8, False), (28 * CU, 256, 4, True)):
+            t = graph_time(lambda i: sr.sr_ceiling_hbm_read(rd[i % 20], grid, block, fl, nt), 100)
+            if best is None or t < best[0]:
+                best = (t, grid, block, fl, nt)
+        nbytes = rd[0].numel()
+        ceil["hbm_read_29MB"] = {"us": round(best[0] * 1e6, 2), "GB/s": round(nbytes / best[0] / 1e9, 1),
+                                 "frac_hbm": round(nbytes / best[0] / 1e9 / PEAK_HBM_GBS, 4),
+                                 "config": {"workgroups": best[1], "threads": best[2], "loads_in_flight": best[3], "nontemporal": best[4]},
+                                 "what": "pure read of one packed weight [14336, 2048] bytes per launch, 20 rotating copies, best of 6 launch shapes"}
+        del rd
+        extra["ceilings"] = ceil
+        roofline["measured_ceiling"] = {"TFLOP/s": round(ceil["mfma_f6_loop"]["PFLOP/s"] * 1e3, 1),
+                                        "frac": round(roofline["achieved"] / (ceil["mfma_f6_loop"]["PFLOP/s"] * 1e3), 4),
+                                        "what": "bare FP6 MFMA issue loop, this box, this process"}
 
     # ---------------- per-kernel side measurements (same buffers, event-timed) ------------
     if not args.no_extra:
@@ -236,10 +433,12 @@ def main():
             del w6r
             extra["gemm_f6_N%d" % N] = {"us": round(t * 1e6, 2), "TOPS": round(2.0 * M * N * K / t / 1e12, 1),
                                         "frac_int8_mfma_peak": round(2.0 * M * N * K / t / 1e12 / PEAK_INT8_TOPS, 4),
-                                        "frac_fp6_mfma_peak": round(2.0 * M * N * K / t / 1e12 / PEAK_FP6_TOPS, 4)}
+                                        "frac_fp6_mfma_peak": round(2.0 * M * N * K / t / 1e12 / PEAK_FP6_TOPS, 4),
+                                        "frac_measured_f6_loop": round(2.0 * M * N * K / t / 1e15 / ceil["mfma_f6_loop"]["PFLOP/s"], 4)}
             t = graph_time(lambda i: sr.sr_w4a4_gemm(Xq, xs, Wq[N][i % SETS], Ws[N][i % SETS], sr.SR_F16, Y[N]), 64)
             extra["gemm_int8_N%d" % N] = {"us": round(t * 1e6, 2), "TOPS": round(2.0 * M * N * K / t / 1e12, 1),
-                                          "frac_int8_mfma_peak": round(2.0 * M * N * K / t / 1e12 / PEAK_INT8_TOPS, 4)}
+                                          "frac_int8_mfma_peak": round(2.0 * M * N * K / t / 1e12 / PEAK_INT8_TOPS, 4),
+                                          "frac_measured_i8_loop": round(2.0 * M * N * K / t / 1e15 / ceil["mfma_i8_loop"]["POP/s"], 4)}
         # decode: M in {1,4,16}, K=4096 -> N=14336, weights streamed from >512 MB of distinct copies
         copies = [Wq[14336][0].clone() for _ in range(20)]
         wsc = Ws[14336][0]
@@ -250,7 +449,8 @@ def main():
             t = graph_time(lambda i: sr.sr_w4a4_gemm(xq_d, xs_d, copies[i % 20], wsc, sr.SR_F16, Yd), 100)
             b = 14336 * K / 2 + Md * K / 2 + 2 * Md * 14336
             extra["decode_M%d_4096x14336" % Md] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
-                                                    "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+                                                    "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4),
+                                                    "frac_measured_read_29MB": round(b / t / 1e9 / ceil["hbm_read_29MB"]["GB/s"], 4)}
         # one token, whole online path: rotation + quantiser + GEMM as two calls and as the single fused launch
         Xd = Xs[0][:1].contiguous()
         xq_d = torch.empty((1, K // 2), dtype=torch.uint8, device=dev)
@@ -294,7 +494,8 @@ def main():
         t = graph_time(lambda i: sr.sr_w4a4_gemm_f6(X63, xs3, W63s[i % 8], ws3, M, N3, K3, sr.SR_F16, Y3), 32)
         extra["gemm_f6_K14336_N4096"] = {"us": round(t * 1e6, 2), "TOPS": round(2.0 * M * N3 * K3 / t / 1e12, 1),
                                          "frac_int8_mfma_peak": round(2.0 * M * N3 * K3 / t / 1e12 / PEAK_INT8_TOPS, 4),
-                                         "frac_fp6_mfma_peak": round(2.0 * M * N3 * K3 / t / 1e12 / PEAK_FP6_TOPS, 4)}
+                                         "frac_fp6_mfma_peak": round(2.0 * M * N3 * K3 / t / 1e12 / PEAK_FP6_TOPS, 4),
+                                         "frac_measured_f6_loop": round(2.0 * M * N3 * K3 / t / 1e15 / ceil["mfma_f6_loop"]["PFLOP/s"], 4)}
         # the pair as a layer runs it: rotation + quantiser, then the GEMM -- without and with the quantiser launch
         # warming the memory-side cache with the GEMM's weights
         def pair3(i, warm):
@@ -311,7 +512,8 @@ def main():
             t = graph_time(lambda i: sr.sr_w4a4_gemm(xq_d, xs_d, copies[i % 20], ws3, sr.SR_F16, Yd), 100)
             b = N3 * K3 / 2 + Md * K3 / 2 + 2 * Md * N3
             extra["decode_M%d_14336x4096" % Md] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
-                                                    "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+                                                    "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4),
+                                                    "frac_measured_read_29MB": round(b / t / 1e9 / ceil["hbm_read_29MB"]["GB/s"], 4)}
         del copies, X3
         # ---- rows around the core path -----------------------------------------------------------
         # gated-FFN prologue fused into the K = 14336 rotation + quantiser (two fp16 inputs per value)
@@ -353,73 +555,8 @@ def main():
         extra["kv_quant_asym_32768x1024"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
                                              "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
         del KV
-        # ---- config 5: the seven linears of a LLaMA-3.1-8B decoder layer at 8 x 2048 tokens (timing only:
-        # random packed weights; q/k/v share one quantised input, gate/up another) --------------------------
-        M5 = 16384
-        X5 = torch.randn((M5, K), dtype=torch.float16, device=dev)
-        X5d = torch.randn((M5, K3), dtype=torch.float16, device=dev)
-        Xq5 = torch.empty((M5, K // 2), dtype=torch.uint8, device=dev)
-        Xq5d = torch.empty((M5, K3 // 2), dtype=torch.uint8, device=dev)
-        xs5 = torch.empty(M5, dtype=torch.float32, device=dev)
-        W5 = {n: (torch.randint(0, 256, (nn, kk // 2), dtype=torch.uint8, device=dev), torch.rand(nn, device=dev) * 1e-3)
-              for n, kk, nn in wl.CFG5_LINEARS}
-        Y5 = torch.empty((M5, 14336), dtype=torch.float16, device=dev)
-
-        def layer(i):
-            sr.sr_fwht_quant_act(X5, inv_s, CLIP, Xq5, xs5)
-            for n in ("q", "k", "v"):
-                sr.sr_w4a4_gemm(Xq5, xs5, W5[n][0], W5[n][1], sr.SR_F16, Y5[:, :W5[n][0].shape[0]])
-            sr.sr_fwht_quant_act(X5, inv_s, CLIP, Xq5, xs5)
-            sr.sr_w4a4_gemm(Xq5, xs5, W5["o"][0], W5["o"][1], sr.SR_F16, Y5[:, :4096])
-            sr.sr_fwht_quant_act(X5, inv_s, CLIP, Xq5, xs5)
-            for n in ("gate", "up"):
-                sr.sr_w4a4_gemm(Xq5, xs5, W5[n][0], W5[n][1], sr.SR_F16, Y5)
-            sr.sr_fwht_quant_act(X5d, None, CLIP, Xq5d, xs5)
-            sr.sr_w4a4_gemm(Xq5d, xs5, W5["down"][0], W5["down"][1], sr.SR_F16, Y5[:, :4096])
-        layer(0)
-        torch.cuda.synchronize()
-        t = ev_time(layer, 5)
-        ops5 = sum(2.0 * M5 * kk * nn for _, kk, nn in wl.CFG5_LINEARS)
-        extra["cfg5_layer_M16384_int8"] = {"ms": round(t * 1e3, 3), "TOPS": round(ops5 / t / 1e12, 1),
-                                           "frac_int8_mfma_peak": round(ops5 / t / 1e12 / PEAK_INT8_TOPS, 4),
-                                           "workload": "7 linears (q,k,v,o,gate,up,down) + 4 rotate/quantise passes, 16384 tokens"}
-        X65 = torch.zeros(sr.sr_f6_tiles_bytes(M5, K), dtype=torch.uint8, device=dev)
-        X65d = torch.zeros(sr.sr_f6_tiles_bytes(M5, K3), dtype=torch.uint8, device=dev)
-        W65 = {n: sr.sr_pack_f6_tiles(W5[n][0]) for n, _, _ in wl.CFG5_LINEARS}
-        dims = {n: (kk, nn) for n, kk, nn in wl.CFG5_LINEARS}
-
-        def g6(n, X6_, Yv):
-            sr.sr_w4a4_gemm_f6(X6_, xs5, W65[n], W5[n][1], M5, dims[n][1], dims[n][0], sr.SR_F16, Yv)
-
-        def layer6(i):                                       # every quantiser call warms the cache for the GEMM behind it
-            sr.sr_fwht_quant_act_f6(X5, inv_s, CLIP, X65, xs5, warm=W65["q"])
-            for n in ("q", "k", "v"):
-                g6(n, X65, Y5[:, :dims[n][1]])
-            sr.sr_fwht_quant_act_f6(X5, inv_s, CLIP, X65, xs5, warm=W65["o"])
-            g6("o", X65, Y5[:, :4096])
-            sr.sr_fwht_quant_act_f6(X5, inv_s, CLIP, X65, xs5, warm=W65["gate"])
-            for n in ("gate", "up"):
-                g6(n, X65, Y5)
-            sr.sr_fwht_quant_act_f6(X5d, None, CLIP, X65d, xs5, warm=W65["down"])
-            g6("down", X65d, Y5[:, :4096])
-        layer6(0)
-        torch.cuda.synchronize()
-        t = ev_time(layer6, 5)
-        extra["cfg5_layer_M16384"] = {"ms": round(t * 1e3, 3), "TOPS": round(ops5 / t / 1e12, 1),
-                                      "frac_int8_mfma_peak": round(ops5 / t / 1e12 / PEAK_INT8_TOPS, 4),
-                                      "workload": "7 linears (q,k,v,o,gate,up,down) + 4 rotate/quantise passes, 16384 tokens, f6 path"}
-        # the rotation + quantiser passes of that layer on their own (three distinct inputs of 134 MB for K = 4096;
-        # the 470 MB input of the down-projection is larger than the Infinity Cache by itself)
-        X5s = [X5, torch.randn_like(X5), torch.randn_like(X5)]
-        t = graph_time(lambda i: sr.sr_fwht_quant_act_f6(X5s[i % 3], inv_s, CLIP, X65, xs5), 6)
-        b = M5 * K * 2.75 + 4 * M5
-        extra["fwht_quant_f6_K4096_M16384"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
-                                               "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
-        t = graph_time(lambda i: sr.sr_fwht_quant_act_f6(X5d, None, CLIP, X65d, xs5), 4)
-        b = M5 * K3 * 2.75 + 4 * M5
-        extra["fwht_quant_f6_K14336_M16384"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
-                                                "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
-        del X5, X5s, X5d, Xq5, Xq5d, W5, Y5, X65, X65d, W65
+        # ---- config 5: a LLaMA-3.1-8B-shaped decoder layer at 8 x 2048 tokens, chained (see cfg5_chained) ----
+        extra.update(cfg5_chained(sr, wl, torch, dev, graph_time, ev_time, args))
 
     # ---------------- CPU baseline: the oracle on a bounded sample ------------------------
     cpu = None

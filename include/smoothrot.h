@@ -361,6 +361,35 @@ SR_API int sr_w4a4_gemm_f6(const uint8_t *X6, const float *x_scale,
                     void *Y, int64_t ldy, int out_dtype,
                     void *workspace, size_t workspace_bytes, void *stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Measurement kernels (bench.py): what the chip sustains with nothing else in the way.  They compute
+ * nothing of the method; their timings are the "measured ceilings" quoted beside the published peaks.
+ * Each call enqueues ONE launch on `stream` and returns.  `sink` may be NULL (it is written only if a
+ * checksum takes a value it cannot take; it exists so that the work cannot be optimised away).
+ * ------------------------------------------------------------------------------------------ */
+
+/* A pure read stream over [src, src + bytes): `grid` workgroups of `block` threads (a multiple of 64, at
+ * most 1024), every thread keeping `in_flight` (1, 2, 4, 8 or 16) 16-byte loads in flight; nontemporal != 0
+ * uses loads that do not allocate in the caches.  bytes a multiple of 16, src 16-byte aligned.
+ * Algorithmic bytes per launch = bytes. */
+SR_API int sr_ceiling_hbm_read(const void *src, size_t bytes, int grid, int block, int in_flight, int nontemporal,
+                        uint32_t *sink, void *stream);
+
+/* A bare issue loop of the FP6 matrix instruction of sr_w4a4_gemm_f6 (32 x 32 x 64 per instruction): `grid`
+ * workgroups of 8 waves, each wave 8 independent accumulator tiles, `iters` rounds of 8 instructions, operands
+ * taken once from `fields` (at least 9216 bytes of 6-bit patterns, e.g. the first bytes of an f6-tile buffer).
+ * Operations per launch = grid * 8 waves * iters * 8 * 2 * 32 * 32 * 64. */
+SR_API int sr_ceiling_mfma_f6(const void *fields, size_t bytes, int iters, int grid, float *sink, void *stream);
+
+/* The same for the int8 matrix instruction of sr_w4a4_gemm (32 x 32 x 32 per instruction); `operands`: at least
+ * 6144 bytes.  Operations per launch = grid * 8 * iters * 8 * 2 * 32 * 32 * 32. */
+SR_API int sr_ceiling_mfma_i8(const void *operands, size_t bytes, int iters, int grid, int *sink, void *stream);
+
+/* A bare loop of fp32 vector arithmetic in the mix of the rotation kernels' register passes: `grid` workgroups of
+ * 4 waves, per iteration and wave 160 additions / subtractions and 32 multiplications.
+ * Vector instructions per launch = grid * 4 * iters * 192 (each over 64 lanes). */
+SR_API int sr_ceiling_valu_f32(int iters, int grid, float *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -49,6 +49,10 @@ _SIGNATURES = {
     "sr_fwht_quant_act_f6_warm": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _vp, _sz, _vp]),
     "sr_swiglu_fwht_quant_act_f6": (_int, [_vp, _vp, _i64, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _vp]),
     "sr_w4a4_gemm_f6": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _int, _vp, _sz, _vp]),
+    "sr_ceiling_hbm_read": (_int, [_vp, _sz, _int, _int, _int, _int, _vp, _vp]),
+    "sr_ceiling_mfma_f6": (_int, [_vp, _sz, _int, _int, _vp, _vp]),
+    "sr_ceiling_mfma_i8": (_int, [_vp, _sz, _int, _int, _vp, _vp]),
+    "sr_ceiling_valu_f32": (_int, [_int, _int, _vp, _vp]),
     "sr_w4a4_linear_decode": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _vp]),
 }
 
@@ -347,3 +351,29 @@ def sr_swiglu_fwht_quant_act_f6(G, U, inv_s, clip: float = 0.9, X6=None, x_scale
     _check(raw().sr_swiglu_fwht_quant_act_f6(_ptr(G), _ptr(U), M, K, ldg, ldu, _ptr(inv_s), clip, _ptr(X6),
                                              _ptr(x_scale), _stream()), "sr_swiglu_fwht_quant_act_f6")
     return X6, x_scale
+
+
+def sr_ceiling_hbm_read(src, grid: int, block: int = 256, in_flight: int = 8, nontemporal: bool = True):
+    """Measurement kernel: reads every byte of `src` (a contiguous device tensor) once."""
+    _check(raw().sr_ceiling_hbm_read(_ptr(src), src.numel() * src.element_size(), grid, block, in_flight,
+                                     int(bool(nontemporal)), None, _stream()), "sr_ceiling_hbm_read")
+
+
+def sr_ceiling_mfma_f6(fields, iters: int, grid: int):
+    """Measurement kernel: bare FP6 matrix-instruction loop; returns the operations of the launch."""
+    _check(raw().sr_ceiling_mfma_f6(_ptr(fields), fields.numel() * fields.element_size(), iters, grid, None, _stream()),
+           "sr_ceiling_mfma_f6")
+    return grid * 8 * iters * 8 * 2.0 * 32 * 32 * 64
+
+
+def sr_ceiling_mfma_i8(operands, iters: int, grid: int):
+    """Measurement kernel: bare int8 matrix-instruction loop; returns the operations of the launch."""
+    _check(raw().sr_ceiling_mfma_i8(_ptr(operands), operands.numel() * operands.element_size(), iters, grid, None,
+                                    _stream()), "sr_ceiling_mfma_i8")
+    return grid * 8 * iters * 8 * 2.0 * 32 * 32 * 32
+
+
+def sr_ceiling_valu_f32(iters: int, grid: int):
+    """Measurement kernel: bare fp32 vector-ALU loop; returns the wave-level vector instructions of the launch."""
+    _check(raw().sr_ceiling_valu_f32(iters, grid, None, _stream()), "sr_ceiling_valu_f32")
+    return grid * 4 * iters * 192.0

@@ -14,7 +14,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libsmoothrot.so")
 
-SOURCES = ["sr_api.hip", "fwht_quant.hip", "calib_fold.hip", "gemm_prefill.hip", "gemm_f6.hip", "gemm_decode.hip", "kv_quant.hip", "linear_decode.hip"]
+SOURCES = ["sr_api.hip", "fwht_quant.hip", "calib_fold.hip", "gemm_prefill.hip", "gemm_f6.hip", "gemm_decode.hip", "kv_quant.hip", "linear_decode.hip", "ceilings.hip"]
 
 # packed-fp32 instructions are switched off on purpose (device code only)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

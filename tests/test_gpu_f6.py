@@ -111,25 +111,23 @@ def test_fp16_epilogue(gpu, M, N, K):
 
 
 @pytest.mark.parametrize("N", [4096, 14336])
-def test_cfg2_full_size_sampled(gpu, N):
-    """M = 2048, K = 4096 in the launch configuration the benchmark times: sampled rows by the oracle one by
-    one, and two sum identities that cover every output (row sums against cx . colsum(cw), column sums
-    against rowsum(cx) . cw)."""
+def test_cfg2_full_size_every_accumulator(gpu, N):
+    """M = 2048, K = 4096 in the launch configuration the benchmark times: every one of the M x N INT32
+    accumulators against the oracle's triple loop, plus two sum identities (row sums against cx . colsum(cw),
+    column sums against rowsum(cx) . cw) as an independent cross-check of the comparison itself."""
     M, K = 2048, 4096
     cx, cw = wl.random_codes(21, M, K), wl.random_codes(22 + N, N, K)
     got = gemm_f6(gpu, cx, cw).astype(np.int64)
-    rows = np.unique(np.r_[0:4, 255:258, 1023:1026, M - 4:M])
-    assert np.array_equal(got[rows], o.gemm_i32_c(cx[rows], cw))
+    assert np.array_equal(got, o.gemm_i32_c(cx, cw))
     assert np.array_equal(got.sum(axis=1), cx.astype(np.int64) @ cw.astype(np.int64).sum(axis=0))
     assert np.array_equal(got.sum(axis=0), cx.astype(np.int64).sum(axis=0) @ cw.astype(np.int64).T)
 
 
-def test_cfg3_full_size_sampled(gpu):
+def test_cfg3_full_size_every_accumulator(gpu):
     M, N, K = 2048, 4096, 14336
     cx, cw = wl.random_codes(31, M, K), wl.random_codes(32, N, K)
     got = gemm_f6(gpu, cx, cw).astype(np.int64)
-    rows = np.unique(np.r_[0:3, 1024:1026, M - 3:M])
-    assert np.array_equal(got[rows], o.gemm_i32_c(cx[rows], cw))
+    assert np.array_equal(got, o.gemm_i32_c(cx, cw))
     assert np.array_equal(got.sum(axis=1), cx.astype(np.int64) @ cw.astype(np.int64).sum(axis=0))
 
 

@@ -76,25 +76,23 @@ def test_ragged_leading_dimension(gpu):
 
 
 @pytest.mark.parametrize("N", [4096, 14336])
-def test_cfg2_full_size_properties_and_samples(gpu, N):
-    """Full prefill shape in the configuration the benchmark times.  The oracle computes a sample of
-    token rows one by one; every other output is covered by two exact identities that hold at any size:
+def test_cfg2_full_size_every_accumulator(gpu, N):
+    """Full prefill shape in the configuration the benchmark times: every INT32 accumulator against the oracle's
+    triple loop; the two identities that hold at any size stay as a cross-check of the comparison:
     sum_n acc[m][n] = cx[m] . (sum_n cw[n])   and   sum_m acc[m][n] = (sum_m cx[m]) . cw[n]."""
     M, K = 2048, 4096
     cx, cw = wl.random_codes(11, M, K), wl.random_codes(12 + N, N, K)
     got = gpu_gemm(gpu, cx, cw).astype(np.int64)
-    rows = np.r_[0:8, 120:136, 1017:1033, 2040:2048]
-    assert np.array_equal(got[rows], o.gemm_i32_c(cx[rows], cw))
+    assert np.array_equal(got, o.gemm_i32_c(cx, cw))
     assert np.array_equal(got.sum(axis=1), cx.astype(np.int64) @ cw.astype(np.int64).sum(axis=0))
     assert np.array_equal(got.sum(axis=0), cw.astype(np.int64) @ cx.astype(np.int64).sum(axis=0))
 
 
-def test_cfg3_full_size_properties_and_samples(gpu):
+def test_cfg3_full_size_every_accumulator(gpu):
     M, K, N = 2048, 14336, 4096
     cx, cw = wl.random_codes(21, M, K), wl.random_codes(22, N, K)
     got = gpu_gemm(gpu, cx, cw).astype(np.int64)
-    rows = np.r_[0:4, 1000:1008, 2044:2048]
-    assert np.array_equal(got[rows], o.gemm_i32_c(cx[rows], cw))
+    assert np.array_equal(got, o.gemm_i32_c(cx, cw))
     assert np.array_equal(got.sum(axis=1), cx.astype(np.int64) @ cw.astype(np.int64).sum(axis=0))
     assert np.array_equal(got.sum(axis=0), cw.astype(np.int64) @ cx.astype(np.int64).sum(axis=0))
 
