@@ -41,11 +41,27 @@ def _compile(src: str) -> str:
     return obj
 
 
+def _check_asm_loads() -> None:
+    """The staged rotation kernels load rows with inline-assembly loads whose destination registers must not be
+    touched before the matching wait (csrc/check_asm_loads.py): verified on the device assembly of this build."""
+    asm = os.path.join(OBJ, "fwht_quant.s")
+    dev_flags = [f for f in FLAGS if f not in ("-fPIC", "-fvisibility=hidden")]
+    r = subprocess.run([_hipcc(), *dev_flags, "-S", "--cuda-device-only", os.path.join(CSRC, "fwht_quant.hip"), "-o", asm],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc -S failed for fwht_quant.hip:\n" + r.stderr[-2000:])
+    r = subprocess.run([sys.executable, os.path.join(CSRC, "check_asm_loads.py"), asm], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("inline-assembly load check failed:\n" + r.stdout + r.stderr)
+
+
 def build(verbose: bool = True) -> str:
     """Compile every HIP source and link the shared library; returns its path."""
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES) + 1)) as ex:
+        check = ex.submit(_check_asm_loads)
         objs = list(ex.map(_compile, SOURCES))
+        check.result()
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

@@ -15,6 +15,7 @@
 // The LDS row is padded by 4 floats per 64 so that every access pattern above is
 // bank-conflict free for K = 4096.
 #include "fwht_row.h"
+#include "gemm_common.h"      // LDS-DMA load, hand-placed waits, fence-free barrier
 
 namespace sr {
 namespace {
@@ -292,7 +293,12 @@ __global__ __launch_bounds__(NT) void fwht_quant_ex_kernel(const __half *__restr
 // ------------------------------------------------------------------------------------------
 
 // MASKED: head-wise transform -- only the index bits set in had_mask are butterflied (uniform branches).
-template <bool HAS_PRE, bool F6, bool MASKED = false>
+// STAGED (with factors, full transform): the 16 KB of smoothing factors reach the four waves of a workgroup through
+// LDS -- ONE copy per workgroup by LDS-DMA instead of 16 vector loads per wave, a quarter of the traffic on the
+// CU's vector-memory path, which every row load of the launch has to share.  The copies are inline assembly with a
+// hand-counted wait, so that the order (factors, then the row) and the wait (factors have landed while the row is
+// still in flight) are what is written here, not what the compiler's scheduler makes of them.
+template <bool HAS_PRE, bool F6, bool MASKED = false, bool STAGED = false>
 __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__restrict__ X, int64_t ldx, int64_t rows,
                                                             const float *__restrict__ pre, float clip, float post_scale,
                                                             uint8_t *__restrict__ Q, float *__restrict__ scale_out,
@@ -300,8 +306,8 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
                                                             int64_t warm_lines)
 {
     constexpr int K = 4096, ROWF = F6 ? K + 576 : K + 64;   // floats per wave-private row incl. padding
-    extern __shared__ float smem_rows[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    extern __shared__ __attribute__((aligned(16))) float smem_rows[];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     int64_t m = (int64_t)blockIdx.x * 4 + wave;
     if constexpr (F6) {
         // both halves of a tile block (8 rows) from the same XCD: workgroup w = 8 a + x (XCD x) takes half
@@ -309,7 +315,10 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
         const int64_t w = blockIdx.x, x = w & 7, a = w >> 3;
         m = 8 * (8 * (a >> 1) + x) + 4 * (a & 1) + wave;
     }
-    if (m >= rows) return;                               // no barrier below: waves are independent
+    static_assert(!STAGED || (HAS_PRE && !MASKED), "the staged variant is the plain transform with factors");
+    if constexpr (!STAGED) {
+        if (m >= rows) return;                           // no barrier below: waves are independent
+    }
     float *buf = smem_rows + wave * ROWF;
     const __half *x = X + m * ldx;
 
@@ -317,19 +326,69 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
     // every load of the row first (the scheduling barrier keeps the compiler from sinking each load to its use,
     // which serialised the memory round trips), then the arithmetic, chunk by chunk as the data arrives
     uint4 rx[8];
+    u32x4 rxa[8];                                        // STAGED: the row as loaded by inline assembly
     float4 rs[8][2];
+    if constexpr (STAGED) {
+        const bool active = m < rows;                    // a wave past the last row still helps with the factors
+        // wave w copies KB 4 w .. 4 w + 3 of the factors into the staging area, which overlays the row buffers
+        // (nobody writes those before the second barrier).  KB q = half h = q & 1 of the 512 factors j = q >> 1:
+        // lane l fetches the four factors 512 j + 8 l + 4 h .., so that the reads below are contiguous per lane.
+        const uint32_t stage = (uint32_t)(uintptr_t)smem_rows;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        rx[j] = *reinterpret_cast<const uint4 *>(x + 512 * j + 8 * lane);
-        if (HAS_PRE) {
-            rs[j][0] = *reinterpret_cast<const float4 *>(pre + 512 * j + 8 * lane);
-            rs[j][1] = *reinterpret_cast<const float4 *>(pre + 512 * j + 8 * lane + 4);
+        for (int i = 0; i < 4; ++i) {
+            const int q = __builtin_amdgcn_readfirstlane(4 * wave + i);
+            dma16(reinterpret_cast<const uint8_t *>(pre), (uint32_t)((512 * (q >> 1) + 8 * lane + 4 * (q & 1)) * 4),
+                  (uint32_t)__builtin_amdgcn_readfirstlane((int)(stage + q * 1024)));
         }
+        // The row's loads are inline assembly too: ordinary loads from a read-only argument float freely in the
+        // compiler's schedule (it sank them below both barriers, past the wait that counts on them).  The compiler
+        // takes rxa[] for defined where the statement stands; every use goes through the wait statements below.
+        const uint64_t xa = (uint64_t)(uintptr_t)(active ? x : X);          // wave-uniform: into scalar registers
+        const uint32_t xlo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)xa);
+        const uint32_t xhi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(xa >> 32));
+        const __half *xr = reinterpret_cast<const __half *>((uint64_t)xlo | ((uint64_t)xhi << 32));
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(rxa[j]) : "v"((uint32_t)((512 * j + 8 * lane) * 2)), "s"(xr) : "memory");
+        wait_vmcnt<8>();
+        barrier_nofence();                               // all 16 KB of factors are in LDS
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            rs[j][0] = *reinterpret_cast<const float4 *>(reinterpret_cast<const uint8_t *>(smem_rows) + (2 * j) * 1024 + lane * 16);
+            rs[j][1] = *reinterpret_cast<const float4 *>(reinterpret_cast<const uint8_t *>(smem_rows) + (2 * j + 1) * 1024 + lane * 16);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        barrier_nofence();                               // every wave holds its factors: the row buffers are free
+        if (!active) {
+            wait_vmcnt<0>();                             // (its loads read row 0; nothing may be in flight at the end)
+            return;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            rx[j] = *reinterpret_cast<const uint4 *>(x + 512 * j + 8 * lane);
+            if (HAS_PRE) {
+                rs[j][0] = *reinterpret_cast<const float4 *>(pre + 512 * j + 8 * lane);
+                rs[j][1] = *reinterpret_cast<const float4 *>(pre + 512 * j + 8 * lane + 4);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_barrier(0);
     float v[64];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
+        if constexpr (STAGED) {
+            // chunk j has landed once at most 7 - j younger loads are outstanding (loads complete in order)
+            if (j == 0) asm volatile("s_waitcnt vmcnt(7)" : "+v"(rxa[0]));
+            if (j == 1) asm volatile("s_waitcnt vmcnt(6)" : "+v"(rxa[1]));
+            if (j == 2) asm volatile("s_waitcnt vmcnt(5)" : "+v"(rxa[2]));
+            if (j == 3) asm volatile("s_waitcnt vmcnt(4)" : "+v"(rxa[3]));
+            if (j == 4) asm volatile("s_waitcnt vmcnt(3)" : "+v"(rxa[4]));
+            if (j == 5) asm volatile("s_waitcnt vmcnt(2)" : "+v"(rxa[5]));
+            if (j == 6) asm volatile("s_waitcnt vmcnt(1)" : "+v"(rxa[6]));
+            if (j == 7) asm volatile("s_waitcnt vmcnt(0)" : "+v"(rxa[7]));
+            rx[j] = make_uint4(rxa[j][0], rxa[j][1], rxa[j][2], rxa[j][3]);
+        }
         union { uint4 u; half2v h[4]; } raw;
         raw.u = rx[j];
         float f[8];
@@ -351,8 +410,21 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
                 else pair_level(raw.h[e], v[8 * j + 2 * e], v[8 * j + 2 * e + 1]);
             }
         }
+        // (STAGED: keeps the arithmetic of chunk j between the waits for chunks j and j + 1 -- the compiler
+        // otherwise gathers the eight waits in front of all of it)
+        if constexpr (STAGED) {
+            float *vj = v + 8 * j;
+            float blk[8] = {vj[0], vj[1], vj[2], vj[3], vj[4], vj[5], vj[6], vj[7]};
+            butterflies_from<3, 2>(blk);                 // index bits 1, 2 inside the chunk, as soon as it is there
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                vj[e] = blk[e];
+                asm volatile("" : "+v"(vj[e]));          // pins the arithmetic here (it would be sunk to its first use)
+            }
+        }
     }
     if constexpr (MASKED) butterflies_masked<6>(v, (had_mask & 7u) | (((had_mask >> 9) & 7u) << 3));   // register bits = index bits 0,1,2,9,10,11
+    else if constexpr (STAGED) butterflies_from<6, 8>(v);   // bits 1, 2 were done chunk by chunk
     else butterflies_from<6, 2>(v);
     // Warming the memory-side cache for the kernel that follows (its weights): the waves of the launch share the
     // 128-byte lines of [warm, warm + 128 warm_lines) and read one word of each -- with ordinary loads, so that the
@@ -531,14 +603,14 @@ hipError_t launch_one_ex(const void *X, int64_t rows, int64_t ldx, const float *
 // and the workgroup-per-row kernel has the shorter critical path.
 constexpr int64_t kWaveKernelMinRows = 1024;   // measured: 3.3 - 4.8 us against 4.2 - 5.9 us up to 512 rows, equal at 1024
 
-template <bool HAS_PRE, bool F6, bool MASKED = false>
+template <bool HAS_PRE, bool F6, bool MASKED = false, bool STAGED = false>
 hipError_t launch_wave4096(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip, float post_scale,
                            uint8_t *Q, float *scale_out, hipStream_t st, uint32_t had_mask = 0xFFFFFFFFu,
                            const void *warm = nullptr, size_t warm_bytes = 0)
 {
     constexpr size_t lds = 4 * (4096 + (F6 ? 576 : 64)) * sizeof(float);
     const unsigned blocks = F6 ? (unsigned)((rows + 63) / 64 * 16) : (unsigned)((rows + 3) / 4);
-    auto kern = fwht4096_wave_kernel<HAS_PRE, F6, MASKED>;
+    auto kern = fwht4096_wave_kernel<HAS_PRE, F6, MASKED, STAGED>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, static_cast<const __half *>(X), ldx, rows, pre, clip,
@@ -553,8 +625,12 @@ hipError_t launch_fwht_quant(const void *X, int64_t rows, int64_t K, int64_t ldx
 {
     int pick = 0;
     if (int64_t f; tuned(kTuneFwht4096, f)) pick = (int)f;
-    if (K == 4096 && (pick == 1 || (pick == 0 && rows > kWaveKernelMinRows))) {
+    if (K == 4096 && (pick == 1 || pick == 3 || pick == 4 || (pick == 0 && rows > kWaveKernelMinRows))) {
         constexpr uint32_t all = 0xFFFFFFFFu;
+        // factors through LDS (one copy per workgroup) unless the knob asks for per-wave vector loads (4)
+        if (pre && pick != 4 && (reinterpret_cast<uintptr_t>(pre) & 15u) == 0 && ldx * 2 * rows < (int64_t)1 << 40)
+            return f6 ? launch_wave4096<true, true, false, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, all, warm, warm_bytes)
+                      : launch_wave4096<true, false, false, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, all, warm, warm_bytes);
         if (pre) return f6 ? launch_wave4096<true, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, all, warm, warm_bytes)
                            : launch_wave4096<true, false>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, all, warm, warm_bytes);
         return f6 ? launch_wave4096<false, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, all, warm, warm_bytes)
