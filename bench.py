@@ -451,21 +451,26 @@ def main():
             extra["decode_M%d_4096x14336" % Md] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
                                                     "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4),
                                                     "frac_measured_read_29MB": round(b / t / 1e9 / ceil["hbm_read_29MB"]["GB/s"], 4)}
-        # one token, whole online path: rotation + quantiser + GEMM as two calls and as the single fused launch
-        Xd = Xs[0][:1].contiguous()
-        xq_d = torch.empty((1, K // 2), dtype=torch.uint8, device=dev)
-        xs_d = torch.empty(1, dtype=torch.float32, device=dev)
-        Yd = torch.empty((1, 14336), dtype=torch.float16, device=dev)
+        # whole online path of a decode step: rotation + quantiser + GEMM as two calls and as the one call
+        # sr_w4a4_linear_decode (one token, K = 4096: a single launch in which every workgroup rotates the row itself;
+        # otherwise the two kernels back to back inside the call -- no single launch measured faster there)
+        for Md in (1, 4, 16):
+            Xd = Xs[0][:Md].contiguous()
+            xq_d = torch.empty((Md, K // 2), dtype=torch.uint8, device=dev)
+            xs_d = torch.empty(Md, dtype=torch.float32, device=dev)
+            Yd = torch.empty((Md, 14336), dtype=torch.float16, device=dev)
+            wsp = torch.zeros(max(sr.sr_linear_decode_workspace_bytes(Md, K), 256), dtype=torch.uint8, device=dev)
 
-        def two_calls(i):
-            sr.sr_fwht_quant_act(Xd, inv_s, CLIP, xq_d, xs_d)
-            sr.sr_w4a4_gemm(xq_d, xs_d, copies[i % 20], wsc, sr.SR_F16, Yd)
-        t2 = graph_time(two_calls, 100)
-        t1 = graph_time(lambda i: sr.sr_w4a4_linear_decode(Xd, inv_s, copies[i % 20], wsc, CLIP, Yd), 100)
-        b = 14336 * K / 2 + K * 2 + 2 * 14336
-        extra["decode_M1_4096x14336_whole_path"] = {"two_calls_us": round(t2 * 1e6, 2), "one_launch_us": round(t1 * 1e6, 2),
-                                                    "GB/s": round(b / t1 / 1e9, 1),
-                                                    "frac_hbm": round(b / t1 / 1e9 / PEAK_HBM_GBS, 4)}
+            def two_calls(i):
+                sr.sr_fwht_quant_act(Xd, inv_s, CLIP, xq_d, xs_d)
+                sr.sr_w4a4_gemm(xq_d, xs_d, copies[i % 20], wsc, sr.SR_F16, Yd)
+            t2 = graph_time(two_calls, 100)
+            t1 = graph_time(lambda i: sr.sr_w4a4_linear_decode(Xd, inv_s, copies[i % 20], wsc, CLIP, Yd, workspace=wsp), 100)
+            b = 14336 * K / 2 + Md * K * 2 + 2 * Md * 14336
+            extra["decode_M%d_4096x14336_whole_path" % Md] = {
+                "two_calls_us": round(t2 * 1e6, 2), "one_call_us": round(t1 * 1e6, 2), "GB/s": round(b / t1 / 1e9, 1),
+                "frac_hbm": round(b / t1 / 1e9 / PEAK_HBM_GBS, 4),
+                "launches_in_the_one_call": 1 if Md == 1 else 2}
         del copies
         # down-projection shape (config 3): K = 14336 = 28 * 512 -> N = 4096; rotation-only fold (s = 1)
         K3, N3 = 14336, 4096
@@ -514,6 +519,24 @@ def main():
             extra["decode_M%d_14336x4096" % Md] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
                                                     "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4),
                                                     "frac_measured_read_29MB": round(b / t / 1e9 / ceil["hbm_read_29MB"]["GB/s"], 4)}
+        # the down-projection's decode step (K = 14336 = 28 * 512: the place the paper puts the online Hadamard), whole path
+        for Md in (1, 4, 16):
+            Xd = X3[0][:Md].contiguous()
+            xq_d = torch.empty((Md, K3 // 2), dtype=torch.uint8, device=dev)
+            xs_d = torch.empty(Md, dtype=torch.float32, device=dev)
+            Yd = torch.empty((Md, N3), dtype=torch.float16, device=dev)
+            wsp = torch.zeros(sr.sr_linear_decode_workspace_bytes(Md, K3), dtype=torch.uint8, device=dev)
+
+            def two_calls3(i):
+                sr.sr_fwht_quant_act(Xd, None, CLIP, xq_d, xs_d)
+                sr.sr_w4a4_gemm(xq_d, xs_d, copies[i % 20], ws3, sr.SR_F16, Yd)
+            t2 = graph_time(two_calls3, 100)
+            t1 = graph_time(lambda i: sr.sr_w4a4_linear_decode(Xd, None, copies[i % 20], ws3, CLIP, Yd, workspace=wsp), 100)
+            b = N3 * K3 / 2 + Md * K3 * 2 + 2 * Md * N3
+            extra["decode_M%d_14336x4096_whole_path" % Md] = {
+                "two_calls_us": round(t2 * 1e6, 2), "one_call_us": round(t1 * 1e6, 2), "GB/s": round(b / t1 / 1e9, 1),
+                "frac_hbm": round(b / t1 / 1e9 / PEAK_HBM_GBS, 4), "launches_in_the_one_call": 2,
+                "note": "one-launch variants lose here (measured 11.9 - 13.4 us against this pair): the call runs the two kernels"}
         del copies, X3
         # ---- rows around the core path -----------------------------------------------------------
         # gated-FFN prologue fused into the K = 14336 rotation + quantiser (two fp16 inputs per value)

@@ -259,25 +259,34 @@ SR_API int sr_kv_quant_asym(const void *X_f16, int64_t rows, int64_t D, int64_t 
                      uint8_t *Q, float *scale, float *zero, void *stream);
 
 /*
- * The whole online path for ONE token in a single launch (decode step):
+ * The whole online path of a decode step (up to 16 tokens) behind ONE call:
  *     exactly sr_fwht_quant_act(X, inv_s, clip) followed by sr_w4a4_gemm(..., SR_F16)
  * (paper: online Hadamard and per-token INT4 in front of the quantised projection, section
- * "Methodology", Eq. (1)).  Codes and scale are the ones the two calls would produce, up to the
- * rounding-order freedom of the fp32 rotation (a code may sit on the other side of a rounding
- * boundary).  Offered where it beats the two calls: one token, K a power of two up to 8192.
+ * "Methodology", Eq. (1); Fig. 2 puts it in front of the down-projection, K = 14336 for an 8B model).
+ * Codes and scales are the ones the two calls would produce, up to the rounding-order freedom of the
+ * fp32 rotation (a code may sit on the other side of a rounding boundary).
+ * One token with K = 2048 or 4096 runs as a SINGLE launch (rotation, quantiser and GEMM in one kernel, every
+ * workgroup rotating the row while its weights travel): 8.0 us against 9.6 - 10.0 us for 4096 -> 14336.  Every
+ * other shape runs the two kernels back to back inside the call -- measured, no single launch beats that pair
+ * there (see csrc/linear_decode.hip) -- so the call is never slower than the two calls and saves their host side.
  *
- *   X_f16   fp16 [M, K], M = 1 (M = 0 is a no-op; M > 1 is SR_ERR_SHAPE: use the two calls)
- *   K       2048, 4096 or 8192 (SR_ERR_UNSUPPORTED_K otherwise: use the two calls)
+ *   X_f16   fp16 [M, K], 1 <= M <= 16 (M = 0 is a no-op), row stride ldx
+ *   K       2048, 4096, 8192 or 14336 (SR_ERR_UNSUPPORTED_K otherwise: use the two calls)
  *   Wq, w_scale   packed weights [N, K/2] and scales [N] from the fold; N a multiple of 16
  *   Y_f16   out, fp16 [M, N], row stride ldy
  *   Xq_out  out, optional (may be NULL): uint8 [M, K/2], the activation codes that were used
  *   x_scale_out  out, optional (may be NULL): fp32 [M]
+ *   workspace    sr_linear_decode_workspace_bytes(M, K) bytes, 256-byte aligned: the codes and scales between the
+ *                two kernels (may be NULL where that is 0: the single-launch shapes).  Contents need no
+ *                initialisation; calls that share a workspace must not overlap.
  */
+SR_API size_t sr_linear_decode_workspace_bytes(int64_t M, int64_t K);
 SR_API int sr_w4a4_linear_decode(const void *X_f16, int64_t M, int64_t K, int64_t ldx,
                           const float *inv_s, float clip,
                           const uint8_t *Wq, const float *w_scale, int64_t N,
                           void *Y_f16, int64_t ldy,
-                          uint8_t *Xq_out, float *x_scale_out, void *stream);
+                          uint8_t *Xq_out, float *x_scale_out,
+                          void *workspace, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------
  * Fast prefill path: the same INT4 x INT4 product on the FP6 matrix pipe.

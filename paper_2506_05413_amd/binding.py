@@ -17,6 +17,7 @@ SR_ERR_ALIGN, SR_ERR_ARG, SR_ERR_WORKSPACE, SR_ERR_DEVICE = 4, 5, 6, 7
 SR_F16, SR_I32 = 0, 1
 SR_TUNE_GEMM_TILE, SR_TUNE_GEMM_GRID, SR_TUNE_GEMM_XCDM, SR_TUNE_DECODE_KERNEL = 0, 1, 2, 3
 SR_TUNE_FWHT4096, SR_TUNE_FWHT_STREAM, SR_TUNE_GEMM_SPLITK = 4, 5, 6
+SR_TUNE_KNOBS = 7
 SR_TUNE_AUTO = -(1 << 63)
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -53,7 +54,8 @@ _SIGNATURES = {
     "sr_ceiling_mfma_f6": (_int, [_vp, _sz, _int, _int, _vp, _vp]),
     "sr_ceiling_mfma_i8": (_int, [_vp, _sz, _int, _int, _vp, _vp]),
     "sr_ceiling_valu_f32": (_int, [_int, _int, _vp, _vp]),
-    "sr_w4a4_linear_decode": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _vp]),
+    "sr_linear_decode_workspace_bytes": (_sz, [_i64, _i64]),
+    "sr_w4a4_linear_decode": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _sz, _vp]),
 }
 
 _lib = None
@@ -265,8 +267,15 @@ def sr_kv_quant_asym(X, group: int = 128, clip: float = 0.95, Q=None, scale=None
     return Q, scale, zero
 
 
-def sr_w4a4_linear_decode(X, inv_s, Wq, w_scale, clip: float = 0.9, Y=None, Xq_out=None, x_scale_out=None):
-    """X fp16 [1, K], Wq uint8 [N, K/2] -> Y fp16 [1, N] in one launch (rotate, quantise, multiply)."""
+def sr_linear_decode_workspace_bytes(M: int, K: int) -> int:
+    return int(raw().sr_linear_decode_workspace_bytes(M, K))
+
+
+def sr_w4a4_linear_decode(X, inv_s, Wq, w_scale, clip: float = 0.9, Y=None, Xq_out=None, x_scale_out=None,
+                          workspace=None):
+    """X fp16 [M <= 16, K], Wq uint8 [N, K/2] -> Y fp16 [M, N] in one launch (rotate, quantise, multiply).
+    workspace: a uint8 device tensor of sr_linear_decode_workspace_bytes(M, K) bytes (reuse it from call to call);
+    one is made per call if none is given."""
     _dev(X, torch.float16, "X"); _dev(Wq, torch.uint8, "Wq")
     M, K = X.shape
     N = Wq.shape[0]
@@ -275,8 +284,12 @@ def sr_w4a4_linear_decode(X, inv_s, Wq, w_scale, clip: float = 0.9, Y=None, Xq_o
     Y = torch.empty((M, N), dtype=torch.float16, device=X.device) if Y is None else Y
     ldx = X.stride(0) if M > 1 else K
     ldy = Y.stride(0) if M > 1 else N
+    need = sr_linear_decode_workspace_bytes(M, K)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     _check(raw().sr_w4a4_linear_decode(_ptr(X), M, K, ldx, _ptr(inv_s), clip, _ptr(Wq), _ptr(w_scale), N, _ptr(Y),
-                                       ldy, _ptr(Xq_out), _ptr(x_scale_out), _stream()), "sr_w4a4_linear_decode")
+                                       ldy, _ptr(Xq_out), _ptr(x_scale_out), _ptr(workspace),
+                                       0 if workspace is None else workspace.numel(), _stream()), "sr_w4a4_linear_decode")
     return Y
 
 

@@ -1,4 +1,5 @@
-// Whole online path of the W4A4 linear layer for ONE token in ONE launch:
+// Whole online path of the W4A4 linear layer for a decode step behind one entry point; for ONE token and
+// K = 2048 / 4096 in ONE launch:
 //     x^ = quantise((x * inv_s) H),   Y = dequantise(x^ W^)
 // (Paper: online Hadamard + per-token INT4 of the activations in front of the quantised
 // projection, section "Methodology" and Eq. (1); this is the decode step, where a launch and a
@@ -163,6 +164,8 @@ hipError_t launch_ld(const void *X, int64_t M, int64_t ldx, const float *pre, fl
     return hipGetLastError();
 }
 
+constexpr int LD_WS_SCALES = 256, LD_WS_CODES = 512;      // workspace of the two-launch path: scales [16], codes [M][K / 2]
+
 // Row groups of 8 channels per workgroup: every workgroup repeats the rotation, so few large workgroups are
 // cheaper, but the chip should be filled in whole rounds -- the G <= gmax with the least (rounds x G), ties to
 // the larger G (14336 channels on 256 CUs: G = 7 gives exactly 256 workgroups, G = 8 would leave 32 CUs idle).
@@ -181,21 +184,52 @@ inline int pick_g(int64_t N, int gmax)
 
 }  // namespace
 
-bool linear_decode_supported(int64_t K) { return K == 2048 || K == 4096 || K == 8192; }
+bool linear_decode_supported(int64_t K) { return K == 2048 || K == 4096 || K == 8192 || K == 14336; }
+
+// one token and a power-of-two order up to 4096: ONE launch in which every workgroup rotates the row itself
+// (4096 -> 14336: 8.0 against 9.6 - 10.0 us for two launches; 4096 -> 4096: 5.0 against 6.5 us; K = 8192: 11.3 us
+// either way, so it takes the general path)
+static bool redundant_rotation_path(int64_t M, int64_t K) { return M == 1 && (K == 2048 || K == 4096); }
+
+size_t linear_decode_workspace_bytes(int64_t M, int64_t K)
+{
+    if (M < 1 || M > 16 || !linear_decode_supported(K) || redundant_rotation_path(M, K)) return 0;
+    return (size_t)LD_WS_CODES + (size_t)M * (size_t)(K / 2);
+}
 
 hipError_t launch_linear_decode(const void *X, int64_t M, int64_t K, int64_t ldx, const float *pre, float clip,
                                 const uint8_t *Wq, const float *ws, int64_t N, void *Y, int64_t ldy,
-                                uint8_t *Xq_out, float *xs_out, hipStream_t st)
+                                uint8_t *Xq_out, float *xs_out, void *workspace, hipStream_t st)
 {
+    if (redundant_rotation_path(M, K)) {
 #define SR_LD(KK, GG) case GG: return launch_ld<KK, GG>(X, M, ldx, pre, clip, Wq, ws, N, Y, ldy, Xq_out, xs_out, st)
-    switch (K) {
-        case 2048: switch (pick_g(N, 8)) { SR_LD(2048, 1); SR_LD(2048, 2); SR_LD(2048, 3); SR_LD(2048, 4); SR_LD(2048, 5); SR_LD(2048, 6); SR_LD(2048, 7); SR_LD(2048, 8); default: break; } break;
-        case 4096: switch (pick_g(N, 8)) { SR_LD(4096, 1); SR_LD(4096, 2); SR_LD(4096, 3); SR_LD(4096, 4); SR_LD(4096, 5); SR_LD(4096, 6); SR_LD(4096, 7); SR_LD(4096, 8); default: break; } break;
-        case 8192: switch (pick_g(N, 4)) { SR_LD(8192, 1); SR_LD(8192, 2); SR_LD(8192, 3); SR_LD(8192, 4); default: break; } break;
-        default: break;
-    }
-    return hipErrorInvalidValue;
+        switch (K) {
+            case 2048: switch (pick_g(N, 8)) { SR_LD(2048, 1); SR_LD(2048, 2); SR_LD(2048, 3); SR_LD(2048, 4); SR_LD(2048, 5); SR_LD(2048, 6); SR_LD(2048, 7); SR_LD(2048, 8); default: break; } break;
+            case 4096: switch (pick_g(N, 8)) { SR_LD(4096, 1); SR_LD(4096, 2); SR_LD(4096, 3); SR_LD(4096, 4); SR_LD(4096, 5); SR_LD(4096, 6); SR_LD(4096, 7); SR_LD(4096, 8); default: break; } break;
+            default: break;
+        }
+        return hipErrorInvalidValue;
 #undef SR_LD
+    }
+    // Everything else -- several tokens, K = 8192 where the two are level, K = 14336 = 28 * 512 -- runs as two launches
+    // behind the one entry point: the rotation + quantiser of the M rows, then the M <= 16 GEMM; codes and scales go
+    // through the workspace (or straight into the caller's optional outputs).  One-launch variants for these shapes
+    // were built and measured against exactly this pair (4096 -> 14336 / 14336 -> 4096, 20 rotating weight copies):
+    //  - every workgroup rotating the row(s) itself: 13.4 us against 11.9 us at K = 14336, one token (the rotation
+    //    of such a row takes a 512-thread workgroup longer than its weights take to arrive);
+    //  - rows rotated once by M extra workgroups and handed to the others through memory (agent-scope release,
+    //    relaxed polling, coherent loads of the codes): 11.9 - 12.3 us against 11.9 us at K = 14336 for one token,
+    //    13.4 - 15.5 against 12.1 - 12.5 us for 2 - 4 tokens, 12.2 against 10.1 us at K = 4096 for two tokens -- the
+    //    producers' own loads queue behind 29 MB of weight requests (rotation done 7.6 us into the kernel instead
+    //    of 5.2 us), and dot products on packed nibbles for several tokens lose to the matrix-pipe GEMM;
+    //  - the pair with the quantiser launch also pulling the weights into the memory-side cache: 13.5 against
+    //    12.1 us (a GEMM that is bound by HBM gains nothing from reading the weights twice).
+    uint8_t *wsp = static_cast<uint8_t *>(workspace);
+    uint8_t *xq = Xq_out ? Xq_out : wsp + LD_WS_CODES;
+    float *xs = xs_out ? xs_out : reinterpret_cast<float *>(wsp + LD_WS_SCALES);
+    hipError_t e = launch_fwht_quant(X, M, K, ldx, pre, clip, 1.0f, xq, xs, st);
+    if (e != hipSuccess) return e;
+    return launch_gemm_decode(xq, xs, Wq, ws, M, N, K, Y, ldy, 0, st);
 }
 
 }  // namespace sr

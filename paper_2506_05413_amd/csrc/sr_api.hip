@@ -314,21 +314,26 @@ int sr_kv_quant_asym(const void *X_f16, int64_t rows, int64_t D, int64_t ldx, in
                                    static_cast<hipStream_t>(stream)));
 }
 
+size_t sr_linear_decode_workspace_bytes(int64_t M, int64_t K) { return sr::linear_decode_workspace_bytes(M, K); }
+
 int sr_w4a4_linear_decode(const void *X_f16, int64_t M, int64_t K, int64_t ldx, const float *inv_s, float clip,
                           const uint8_t *Wq, const float *w_scale, int64_t N, void *Y_f16, int64_t ldy,
-                          uint8_t *Xq_out, float *x_scale_out, void *stream)
+                          uint8_t *Xq_out, float *x_scale_out, void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (M < 0 || M > 1 || K <= 0 || N <= 0 || N % 16 != 0 || ldx < K || ldy < N) return SR_ERR_SHAPE;
+    if (M < 0 || M > 16 || K <= 0 || N <= 0 || N % 16 != 0 || ldx < K || ldy < N) return SR_ERR_SHAPE;
     if ((double)N * (double)K >= 4294967296.0) return SR_ERR_SHAPE;
     if (!sr::linear_decode_supported(K)) return SR_ERR_UNSUPPORTED_K;
     if (!(clip > 0.f && clip <= 1.f)) return SR_ERR_ARG;
     if (M == 0) return SR_OK;
+    const size_t need = sr::linear_decode_workspace_bytes(M, K);
     if (!X_f16 || !Wq || !w_scale || !Y_f16) return SR_ERR_NULL;
-    if (ldx % 8 != 0 || !aligned16(X_f16) || !aligned16(Wq) || (inv_s && !aligned16(inv_s)) ||
-        (Xq_out && !aligned16(Xq_out)))
+    if (ldx % 8 != 0 || (need && ldy % 8 != 0) || !aligned16(X_f16) || !aligned16(Wq) || !aligned16(Y_f16) ||
+        !aligned16(w_scale) || (inv_s && !aligned16(inv_s)) || (Xq_out && !aligned16(Xq_out)))
         return SR_ERR_ALIGN;
+    if (need && (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)))
+        return SR_ERR_WORKSPACE;
     return dev(sr::launch_linear_decode(X_f16, M, K, ldx, inv_s, clip, Wq, w_scale, N, Y_f16, ldy, Xq_out,
-                                        x_scale_out, static_cast<hipStream_t>(stream)));
+                                        x_scale_out, workspace, static_cast<hipStream_t>(stream)));
 }
 
 int sr_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, const float *w_scale,

@@ -130,11 +130,13 @@ hipError_t launch_transpose_f16(const void *W_f16, int64_t K, int64_t N, int64_t
 hipError_t launch_kv_quant(const void *X_f16, int64_t rows, int64_t D, int64_t ldx, int64_t group, float clip,
                            uint8_t *Q, float *scale, float *zero, hipStream_t st);
 
-// one-launch decode path: rotate + quantise M <= 2 token rows and multiply (see linear_decode.hip)
+// decode step behind one entry point: rotate + quantise up to 16 token rows and multiply (see linear_decode.hip).
+// workspace: linear_decode_workspace_bytes(M, K) bytes (0 = none needed).
 bool linear_decode_supported(int64_t K);
+size_t linear_decode_workspace_bytes(int64_t M, int64_t K);
 hipError_t launch_linear_decode(const void *X_f16, int64_t M, int64_t K, int64_t ldx, const float *pre, float clip,
                                 const uint8_t *Wq, const float *ws, int64_t N, void *Y_f16, int64_t ldy,
-                                uint8_t *Xq_out, float *xs_out, hipStream_t st);
+                                uint8_t *Xq_out, float *xs_out, void *workspace, hipStream_t st);
 
 hipError_t launch_gemm_prefill(const uint8_t *Xq, const float *xs, const uint8_t *Wq, const float *ws,
                                int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_i32,

@@ -28,5 +28,5 @@ def tune(gpu):
     def set_knob(knob, value):
         gpu.sr_tune_set(knob, int(value))
     yield set_knob
-    for knob in range(7):
+    for knob in range(gpu.SR_TUNE_KNOBS):
         gpu.sr_tune_set(knob, gpu.SR_TUNE_AUTO)

@@ -23,7 +23,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = declared_symbols()
-    assert len(names) == 27 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
+    assert len(names) == 28 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
     lib = ctypes.CDLL(sr.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -31,13 +31,13 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_tuning_knobs_round_trip_and_reject_unknown_ones():
-    for knob in range(7):
+    for knob in range(sr.SR_TUNE_KNOBS):
         assert sr.sr_tune_get(knob) == sr.SR_TUNE_AUTO
         sr.sr_tune_set(knob, 3)
         assert sr.sr_tune_get(knob) == 3
         sr.sr_tune_set(knob, sr.SR_TUNE_AUTO)
         assert sr.sr_tune_get(knob) == sr.SR_TUNE_AUTO
-    assert sr.raw().sr_tune_set(7, 1) == sr.SR_ERR_ARG and sr.raw().sr_tune_set(-1, 1) == sr.SR_ERR_ARG
+    assert sr.raw().sr_tune_set(sr.SR_TUNE_KNOBS, 1) == sr.SR_ERR_ARG and sr.raw().sr_tune_set(-1, 1) == sr.SR_ERR_ARG
     assert sr.sr_tune_get(99) == sr.SR_TUNE_AUTO
 
 
@@ -219,18 +219,19 @@ def test_kv_quant_rejects_bad_arguments():
 
 def test_linear_decode_rejects_bad_arguments():
     f = sr.raw().sr_w4a4_linear_decode
-    ok = dict(X=A, M=1, K=4096, ldx=4096, inv=None, clip=0.9, Wq=A, ws=A, N=64, Y=A, ldy=64, xq=None, xs=None, st=None)
+    ok = dict(X=A, M=1, K=4096, ldx=4096, inv=None, clip=0.9, Wq=A, ws=A, N=64, Y=A, ldy=64, xq=None, xs=None,
+              wsp=None, wsb=0, st=None)
     def call(**kw):
         a = dict(ok); a.update(kw)
         return f(a["X"], a["M"], a["K"], a["ldx"], a["inv"], a["clip"], a["Wq"], a["ws"], a["N"], a["Y"], a["ldy"],
-                 a["xq"], a["xs"], a["st"])
-    assert call(M=2) == sr.SR_ERR_SHAPE                         # more than one token: use the two calls
+                 a["xq"], a["xs"], a["wsp"], a["wsb"], a["st"])
+    assert call(M=17) == sr.SR_ERR_SHAPE                        # more than sixteen tokens: use the two calls
     assert call(M=-1) == sr.SR_ERR_SHAPE
     assert call(N=40) == sr.SR_ERR_SHAPE
     assert call(ldx=2048) == sr.SR_ERR_SHAPE
     assert call(ldy=32) == sr.SR_ERR_SHAPE
     assert call(K=512, ldx=512) == sr.SR_ERR_UNSUPPORTED_K      # a valid Hadamard order, but not built for this call
-    assert call(K=14336, ldx=14336) == sr.SR_ERR_UNSUPPORTED_K
+    assert call(K=28672, ldx=28672) == sr.SR_ERR_UNSUPPORTED_K
     assert call(K=4000, ldx=4000) == sr.SR_ERR_UNSUPPORTED_K
     assert call(clip=0.0) == sr.SR_ERR_ARG
     assert call(X=None) == sr.SR_ERR_NULL
@@ -239,6 +240,17 @@ def test_linear_decode_rejects_bad_arguments():
     assert call(X=A + 2) == sr.SR_ERR_ALIGN
     assert call(ldx=4100) == sr.SR_ERR_ALIGN
     assert call(M=0, X=None, Y=None) == sr.SR_OK
+    # beyond one token with K = 2048 / 4096 the call runs two kernels and needs its workspace
+    assert sr.sr_linear_decode_workspace_bytes(1, 4096) == 0 and sr.sr_linear_decode_workspace_bytes(1, 2048) == 0
+    assert sr.sr_linear_decode_workspace_bytes(1, 8192) == 512 + 4096
+    assert sr.sr_linear_decode_workspace_bytes(1, 14336) == 512 + 7168
+    assert sr.sr_linear_decode_workspace_bytes(16, 4096) == 512 + 16 * 2048
+    assert sr.sr_linear_decode_workspace_bytes(17, 4096) == 0 and sr.sr_linear_decode_workspace_bytes(2, 512) == 0
+    assert call(M=2, N=4096, ldy=4096) == sr.SR_ERR_WORKSPACE
+    assert call(M=2, N=4096, ldy=4096, wsp=WS, wsb=100) == sr.SR_ERR_WORKSPACE
+    assert call(M=2, N=4096, ldy=4096, wsp=WS + 16, wsb=1 << 20) == sr.SR_ERR_WORKSPACE
+    assert call(K=14336, ldx=14336) == sr.SR_ERR_WORKSPACE
+    assert call(M=2, N=4096, ldy=4100, wsp=WS, wsb=1 << 20) == sr.SR_ERR_ALIGN
 
 
 def test_f6_calls_reject_bad_arguments():
