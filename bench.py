@@ -389,6 +389,22 @@ def main():
                                  "config": {"workgroups": best[1], "threads": best[2], "loads_in_flight": best[3], "nontemporal": best[4]},
                                  "what": "pure read of one packed weight [14336, 2048] bytes per launch, 20 rotating copies, best of 6 launch shapes"}
         del rd
+        # the traffic of the rotation + quantiser launches without the rotation: a row in, its codes out, same grid and
+        # LDS footprint (K = 4096: 8 rows in flight per CU; K = 14336: 512 workgroups walking over the rows)
+        xin = Xs + [torch.roll(x, 1 + j, 0) for j in range(2) for x in Xs][:12]              # 20 x 16.8 MB
+        outb = torch.empty(M * 3072, dtype=torch.uint8, device=dev)
+        t = graph_time(lambda i: sr.sr_ceiling_row_stream(xin[i % 20], outb, M, 2 * K, 3072, M, 19 * 1024), 60)
+        b = M * (2 * K + 3072)
+        ceil["row_stream_K4096"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1), "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4),
+                                    "what": "2048 rows of 8 KB read, 3 KB written per row (the bytes of sr_fwht_quant_act_f6 at K = 4096), 20 rotating inputs"}
+        del xin, outb
+        x3 = [torch.randint(0, 255, (M * 28672,), dtype=torch.uint8, device=dev) for _ in range(6)]       # 6 x 58.7 MB
+        outb = torch.empty(M * 10752, dtype=torch.uint8, device=dev)
+        t = graph_time(lambda i: sr.sr_ceiling_row_stream(x3[i % 6], outb, M, 28672, 10752, 2 * CU, 61 * 1024), 30)
+        b = M * (28672 + 10752)
+        ceil["row_stream_K14336"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1), "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4),
+                                     "what": "2048 rows of 28 KB read, 10.5 KB written per row (sr_fwht_quant_act_f6 at K = 14336), 6 rotating inputs"}
+        del x3, outb
         extra["ceilings"] = ceil
         roofline["measured_ceiling"] = {"TFLOP/s": round(ceil["mfma_f6_loop"]["PFLOP/s"] * 1e3, 1),
                                         "frac": round(roofline["achieved"] / (ceil["mfma_f6_loop"]["PFLOP/s"] * 1e3), 4),
@@ -424,7 +440,8 @@ def main():
         t = graph_time(lambda i: sr.sr_fwht_quant_act_f6(Xq_in[i % 20], inv_s, CLIP, X6, xs), 60)
         b = M * K * 2.75 + M * 4
         extra["fwht_quant_f6_K4096"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
-                                        "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+                                        "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4),
+                                        "frac_measured_row_stream": round(ceil["row_stream_K4096"]["us"] * 1e-6 / t, 4)}
         for N in NS:
             # weights of at least 300 MB in rotation (beyond the Infinity Cache): 24 copies for N = 4096
             reps = max(1, -(-300_000_000 // (SETS * W6[N][0].numel())))
@@ -494,7 +511,8 @@ def main():
         t = graph_time(lambda i: sr.sr_fwht_quant_act_f6(X3[i % 6], None, CLIP, X63, xs3), 30)
         b = M * K3 * 2.75 + M * 4
         extra["fwht_quant_f6_K14336"] = {"us": round(t * 1e6, 2), "GB/s": round(b / t / 1e9, 1),
-                                         "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4)}
+                                         "frac_hbm": round(b / t / 1e9 / PEAK_HBM_GBS, 4),
+                                         "frac_measured_row_stream": round(ceil["row_stream_K14336"]["us"] * 1e-6 / t, 4)}
         W63s = [W63] + [W63.clone() for _ in range(7)]           # 8 x 44 MB: beyond the Infinity Cache
         t = graph_time(lambda i: sr.sr_w4a4_gemm_f6(X63, xs3, W63s[i % 8], ws3, M, N3, K3, sr.SR_F16, Y3), 32)
         extra["gemm_f6_K14336_N4096"] = {"us": round(t * 1e6, 2), "TOPS": round(2.0 * M * N3 * K3 / t / 1e12, 1),

@@ -384,6 +384,14 @@ SR_API int sr_w4a4_gemm_f6(const uint8_t *X6, const float *x_scale,
 SR_API int sr_ceiling_hbm_read(const void *src, size_t bytes, int grid, int block, int in_flight, int nontemporal,
                         uint32_t *sink, void *stream);
 
+/* The memory traffic of a rotation + quantiser launch without the rotation: workgroup w (256 threads, lds_bytes of
+ * LDS) reads row w of row_bytes from src with all loads issued up front, folds it, and writes out_bytes that depend
+ * on every load to row w of dst; `grid` workgroups walk over `rows` rows.  src holds rows * row_bytes bytes, dst
+ * rows * out_bytes; both 16-byte aligned, sizes multiples of 16.
+ * Algorithmic bytes per launch = rows * (row_bytes + out_bytes). */
+SR_API int sr_ceiling_row_stream(const void *src, void *dst, int64_t rows, int64_t row_bytes, int64_t out_bytes, int grid,
+                          int lds_bytes, void *stream);
+
 /* A bare issue loop of the FP6 matrix instruction of sr_w4a4_gemm_f6 (32 x 32 x 64 per instruction): `grid`
  * workgroups of 8 waves, each wave 8 independent accumulator tiles, `iters` rounds of 8 instructions, operands
  * taken once from `fields` (at least 9216 bytes of 6-bit patterns, e.g. the first bytes of an f6-tile buffer).

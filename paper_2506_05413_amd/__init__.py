@@ -8,5 +8,5 @@ from .binding import (  # noqa: F401
     sr_fwht_quant_act_f6, sr_swiglu_fwht_quant_act_f6, sr_fwht_quant_act_f6_warm, sr_tune_set, sr_tune_get,
     SR_TUNE_AUTO, SR_TUNE_GEMM_TILE, SR_TUNE_GEMM_GRID, SR_TUNE_GEMM_XCDM, SR_TUNE_DECODE_KERNEL, SR_TUNE_FWHT4096,
     SR_TUNE_FWHT_STREAM, SR_TUNE_GEMM_SPLITK, SR_TUNE_KNOBS, sr_linear_decode_workspace_bytes, sr_noalloc_scratch_bytes, sr_fold_smooth_rotate_quant_noalloc,
-    sr_ceiling_hbm_read, sr_ceiling_mfma_f6, sr_ceiling_mfma_i8, sr_ceiling_valu_f32,
+    sr_ceiling_hbm_read, sr_ceiling_row_stream, sr_ceiling_mfma_f6, sr_ceiling_mfma_i8, sr_ceiling_valu_f32,
 )

@@ -51,6 +51,7 @@ _SIGNATURES = {
     "sr_swiglu_fwht_quant_act_f6": (_int, [_vp, _vp, _i64, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _vp]),
     "sr_w4a4_gemm_f6": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _int, _vp, _sz, _vp]),
     "sr_ceiling_hbm_read": (_int, [_vp, _sz, _int, _int, _int, _int, _vp, _vp]),
+    "sr_ceiling_row_stream": (_int, [_vp, _vp, _i64, _i64, _i64, _int, _int, _vp]),
     "sr_ceiling_mfma_f6": (_int, [_vp, _sz, _int, _int, _vp, _vp]),
     "sr_ceiling_mfma_i8": (_int, [_vp, _sz, _int, _int, _vp, _vp]),
     "sr_ceiling_valu_f32": (_int, [_int, _int, _vp, _vp]),
@@ -370,6 +371,15 @@ def sr_ceiling_hbm_read(src, grid: int, block: int = 256, in_flight: int = 8, no
     """Measurement kernel: reads every byte of `src` (a contiguous device tensor) once."""
     _check(raw().sr_ceiling_hbm_read(_ptr(src), src.numel() * src.element_size(), grid, block, in_flight,
                                      int(bool(nontemporal)), None, _stream()), "sr_ceiling_hbm_read")
+
+
+def sr_ceiling_row_stream(src, dst, rows: int, row_bytes: int, out_bytes: int, grid: int, lds_bytes: int = 1024):
+    """Measurement kernel: reads rows * row_bytes from src, writes rows * out_bytes to dst (a row's output depends
+    on all of the row)."""
+    if src.numel() * src.element_size() < rows * row_bytes or dst.numel() * dst.element_size() < rows * out_bytes:
+        raise ValueError("buffers smaller than the rows say")
+    _check(raw().sr_ceiling_row_stream(_ptr(src), _ptr(dst), rows, row_bytes, out_bytes, grid, lds_bytes, _stream()),
+           "sr_ceiling_row_stream")
 
 
 def sr_ceiling_mfma_f6(fields, iters: int, grid: int):

@@ -2,6 +2,7 @@
 // bench.py times them beside the real kernels so that every fraction of a published peak can also be read against
 // a ceiling measured in the same process on the same box.
 //   sr_ceiling_hbm_read   a pure read stream over a buffer (the weight stream of a decode GEMM without the GEMM)
+//   sr_ceiling_row_stream the memory traffic of a rotation + quantiser launch (a row in, its codes out) without the rotation
 //   sr_ceiling_mfma_f6    a bare issue loop of the FP6 matrix instruction the prefill GEMM uses, on code-valued
 //                         operands held in registers (no LDS, no loads, no barriers)
 //   sr_ceiling_mfma_i8    the same for the int8 matrix instruction of the canonical-nibble GEMM
@@ -10,13 +11,13 @@
 #include "sr_common.h"
 
 namespace sr {
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef int v16i __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // Every thread keeps INFLIGHT 16-byte loads in flight; a workgroup reads contiguous runs of NT * 16 bytes and
 // strides by the grid.  The words are folded into one value that is stored only if it equals a constant no
@@ -40,6 +41,44 @@ __global__ __launch_bounds__(1024) void hbm_read_kernel(const u32x4 *__restrict_
         acc ^= v[0] ^ v[1] ^ v[2] ^ v[3];
     }
     if (acc == 0x9E3779B9u && sink) sink[0] = acc;
+}
+
+// The traffic of a rotation + quantiser launch without the rotation: workgroup w of 256 threads reads "row" w of
+// `row_bytes` (16-byte loads, all issued up front, as the rotation kernels do), folds it and writes `out_bytes` of
+// the fold to "row" w of dst -- same grid, same bytes per workgroup, same dependence of every store on every load of
+// the row, no arithmetic to speak of.  lds_bytes of dynamic LDS per workgroup reproduce the occupancy.
+__global__ __launch_bounds__(256) void row_stream_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t rows,
+                                                         int row16, int out16)
+{
+    extern __shared__ uint32_t red_s[];
+    const int t = threadIdx.x;
+    for (int64_t w = blockIdx.x; w < rows; w += gridDim.x) {
+        const u32x4 *s = src + w * row16;
+        u32x4 acc = {0u, 0u, 0u, 0u};
+        u32x4 v[8];
+        for (int i0 = 0; i0 < row16; i0 += 8 * 256) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int i = i0 + k * 256 + t;
+                v[k] = i < row16 ? __builtin_nontemporal_load(s + i) : acc;
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) acc ^= v[k];
+        }
+        // every store depends on every load of the row (as the quantiser's scale does): fold over the workgroup
+        uint32_t f = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) f ^= __shfl_xor(f, off, 64);
+        if ((t & 63) == 0) red_s[t >> 6] = f;
+        __syncthreads();
+        f = red_s[0] ^ red_s[1] ^ red_s[2] ^ red_s[3];
+        __syncthreads();
+        u32x4 *d = dst + w * out16;
+        for (int i = t; i < out16; i += 256) {
+            const u32x4 o = {f, acc[1], acc[2], (uint32_t)i};
+            d[i] = o;
+        }
+    }
 }
 
 // 8 waves per workgroup (two per SIMD, as in the GEMM), 8 independent 32 x 32 accumulators per wave (4 x 2 tiles,
@@ -178,6 +217,26 @@ int sr_ceiling_hbm_read(const void *src, size_t bytes, int grid, int block, int 
         default: return SR_ERR_ARG;
     }
     return e == hipSuccess ? SR_OK : SR_ERR_DEVICE;
+}
+
+int sr_ceiling_row_stream(const void *src, void *dst, int64_t rows, int64_t row_bytes, int64_t out_bytes, int grid,
+                          int lds_bytes, void *stream)
+{
+    if (!src || !dst) return SR_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(dst) & 15u) || row_bytes % 16 != 0 ||
+        out_bytes % 16 != 0)
+        return SR_ERR_ALIGN;
+    if (rows < 1 || row_bytes < 16 || out_bytes < 16 || row_bytes > (1 << 24) || grid < 1 || grid > 65536 || lds_bytes < 64 ||
+        lds_bytes > 160 * 1024)
+        return SR_ERR_ARG;
+    auto kern = sr::row_stream_kernel;
+    if (lds_bytes > 48 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
+        return SR_ERR_DEVICE;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), (size_t)lds_bytes, static_cast<hipStream_t>(stream),
+                       static_cast<const sr::u32x4 *>(src), static_cast<sr::u32x4 *>(dst), rows, (int)(row_bytes / 16),
+                       (int)(out_bytes / 16));
+    return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_DEVICE;
 }
 
 int sr_ceiling_mfma_f6(const void *fields, size_t bytes, int iters, int grid, float *sink, void *stream)

@@ -13,6 +13,9 @@ def test_ceiling_kernels_run_and_leave_their_inputs_alone(gpu):
     for grid, block, fl, nt in ((2048, 256, 8, True), (1024, 512, 8, True), (2048, 256, 16, True), (4096, 256, 4, True),
                                 (2048, 256, 8, False), (7168, 256, 4, True), (1, 64, 1, False), (3, 1024, 2, True)):
         gpu.sr_ceiling_hbm_read(src, grid, block, fl, nt)
+    dst = torch.zeros(700 * 1536, dtype=torch.uint8, device="cuda")
+    gpu.sr_ceiling_row_stream(src[:700 * 4096], dst, 700, 4096, 1536, 512, 70 * 1024)      # rows in, "codes" out
+    gpu.sr_ceiling_row_stream(src[:100 * 28672], dst, 100, 28672, 10752, 37, 1024)
     assert gpu.sr_ceiling_mfma_f6(src, 5, 256) == 256 * 8 * 5 * 8 * 2.0 * 32 * 32 * 64
     assert gpu.sr_ceiling_mfma_i8(src, 5, 256) == 256 * 8 * 5 * 8 * 2.0 * 32 * 32 * 32
     assert gpu.sr_ceiling_valu_f32(4, 512) == 512 * 4 * 4 * 192.0
