@@ -1,5 +1,5 @@
-// Offline helpers: calibration absmax, weight row maxima, smoothing factors and the
-// fp16 transpose that turns the weight fold into a row-wise rotation + quantisation.
+// Offline helpers: calibration absmax, smoothing factors, and the fp16 transpose (which also collects the weight's
+// row maxima) that turns the weight fold into a row-wise rotation + quantisation.
 // (Paper, section "Methodology": s_j = max|X_j|^alpha / max|W_j|^(1-alpha), calibrated
 // offline; Lambda = diag(s) goes into the weights.)
 #include "sr_common.h"
@@ -70,31 +70,6 @@ __global__ __launch_bounds__(256) void calib_absmax_kernel(const __half *__restr
     }
 }
 
-// w_rowmax[j] = max_n |W[j][n]|: one block per input channel j.
-__global__ __launch_bounds__(256) void row_absmax_kernel(const __half *__restrict__ W, int N, int64_t ldw,
-                                                          float *__restrict__ w_rowmax)
-{
-    __shared__ us8 part[256];
-    const __half *p = W + (int64_t)blockIdx.x * ldw;
-    us8 acc = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int c = threadIdx.x * 8; c < N; c += 256 * 8)      // N % 16 == 0: whole 8-groups
-        acc = __builtin_elementwise_max(acc, abs_bits(*reinterpret_cast<const uint4 *>(p + c)));
-    part[threadIdx.x] = acc;
-    __syncthreads();
-    for (int s = 128; s >= 1; s >>= 1) {
-        if ((int)threadIdx.x < s)
-            part[threadIdx.x] = __builtin_elementwise_max(part[threadIdx.x], part[threadIdx.x + s]);
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) {
-        const us8 a = part[0];
-        unsigned short m = 0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) m = a[e] > m ? a[e] : m;
-        w_rowmax[blockIdx.x] = half_bits_to_float(m);
-    }
-}
-
 // s_j = max(a_j, 1e-5)^alpha / max(w_j, 1e-5)^(1 - alpha), in double (K values only).
 __global__ void smooth_factors_kernel(const float *__restrict__ act_absmax, const float *__restrict__ w_rowmax,
                                       int K, double alpha, float *__restrict__ s, float *__restrict__ inv_s)
@@ -111,22 +86,69 @@ __global__ void smooth_factors_kernel(const float *__restrict__ act_absmax, cons
     if (inv_s) inv_s[j] = (float)(1.0 / sj);
 }
 
-// 64 x 64 tile transpose of 16-bit values through LDS.
-__global__ __launch_bounds__(256) void transpose_f16_kernel(const unsigned short *__restrict__ W, int K, int N,
-                                                             int64_t ldw, unsigned short *__restrict__ Wt)
+// Wt[n][k] = W[k][n] in tiles of 64 x 64 through LDS, 16 bytes per lane on both sides, and -- on the way -- the row
+// maxima w_rowmax[k] = max_n |W[k][n]| of the smoothing-factor formula, so that W is read once for both.
+//   load   lane (row r = t / 8, chunk c = t % 8) fetches the eight values W[k0 + r][n0 + 8 c ..]: a wave reads eight
+//          whole 128-byte rows of the tile; their maximum over the eight lanes of a row goes to w_rowmax with ONE
+//          atomic per row and tile (bit patterns of non-negative floats order like unsigned integers; the caller
+//          clears w_rowmax first)
+//   LDS    row pitch 72 values; the 16-byte chunk c of row k sits at chunk position (c + k / 8) % 8, so that the
+//          transposed reads below touch every bank once
+//   store  lane (n = t / 8, chunk kc = t % 8) gathers W[k0 + 8 kc .. + 7][n0 + n] with eight 2-byte reads and writes
+//          16 bytes of row n of Wt: eight lanes fill one 128-byte line
+// K % 64 == 0 for every supported Hadamard order; N % 16 == 0, so a chunk of 8 columns is inside or outside N whole.
+__global__ __launch_bounds__(256) void transpose_absmax_f16_kernel(const unsigned short *__restrict__ W, int K, int N,
+                                                                   int64_t ldw, unsigned short *__restrict__ Wt,
+                                                                   float *__restrict__ w_rowmax)
 {
-    __shared__ unsigned short tile[64][66];
+    constexpr int PITCH = 72;
+    __shared__ __attribute__((aligned(16))) unsigned short tile[64 * PITCH];
     const int k0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int r = ty; r < 64; r += 4) {
-        const int k = k0 + r, n = n0 + tx;
-        tile[r][tx] = (k < K && n < N) ? W[(int64_t)k * ldw + n] : (unsigned short)0;
+    const int t = threadIdx.x;
+    {
+        const int c = t & 7;
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            const int r = (t >> 3) + 32 * pass;
+            const int n = n0 + 8 * c;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (n < N) v = *reinterpret_cast<const uint4 *>(W + (int64_t)(k0 + r) * ldw + n);
+            *reinterpret_cast<uint4 *>(tile + r * PITCH + 8 * ((c + (r >> 3)) & 7)) = v;
+            if (w_rowmax) {
+                const us8 a = abs_bits(v);
+                unsigned short m = 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) m = a[e] > m ? a[e] : m;
+                int mi = (int)m;                          // maximum over the 8 lanes of the row (lanes 8 q .. 8 q + 7)
+                mi = max(mi, lane_perm<0xB1>(mi));
+                mi = max(mi, lane_perm<0x4E>(mi));
+                mi = max(mi, lane_perm<0x141>(mi));
+                if (c == 0 && mi != 0)
+                    atomicMax(reinterpret_cast<unsigned int *>(w_rowmax + k0 + r), __float_as_uint(half_bits_to_float((unsigned short)mi)));
+            }
+        }
     }
     __syncthreads();
-    for (int r = ty; r < 64; r += 4) {
-        const int n = n0 + r, k = k0 + tx;
-        if (n < N && k < K) Wt[(int64_t)n * K + k] = tile[tx][r];
+    {
+        const int kc = t & 7;
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            const int nl = (t >> 3) + 32 * pass;
+            if (n0 + nl < N) {
+                union { uint4 u; unsigned short h[8]; } o;
+                const int pos = 8 * (((nl >> 3) + kc) & 7) + (nl & 7);      // where column nl sits in the rows of chunk kc
+#pragma unroll
+                for (int u = 0; u < 8; ++u) o.h[u] = tile[(8 * kc + u) * PITCH + pos];
+                *reinterpret_cast<uint4 *>(Wt + (int64_t)(n0 + nl) * K + k0 + 8 * kc) = o.u;
+            }
+        }
     }
+}
+
+__global__ __launch_bounds__(256) void zero_f32_kernel(float *__restrict__ p, int n)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0.f;
 }
 
 }  // namespace
@@ -157,13 +179,6 @@ hipError_t launch_calib_absmax(const void *X, int64_t T, int64_t K, int64_t ldx,
     return launch_calib<8>(X, T, K, ldx, absmax_io, st, 1024);
 }
 
-hipError_t launch_row_absmax(const void *W, int64_t K, int64_t N, int64_t ldw, float *w_rowmax, hipStream_t st)
-{
-    hipLaunchKernelGGL(row_absmax_kernel, dim3((unsigned)K), dim3(256), 0, st,
-                       static_cast<const __half *>(W), (int)N, ldw, w_rowmax);
-    return hipGetLastError();
-}
-
 hipError_t launch_smooth_factors(const float *act_absmax, const float *w_rowmax, int64_t K, float alpha,
                                  float *s, float *inv_s, hipStream_t st)
 {
@@ -172,11 +187,16 @@ hipError_t launch_smooth_factors(const float *act_absmax, const float *w_rowmax,
     return hipGetLastError();
 }
 
-hipError_t launch_transpose_f16(const void *W, int64_t K, int64_t N, int64_t ldw, void *Wt, hipStream_t st)
+hipError_t launch_transpose_absmax_f16(const void *W, int64_t K, int64_t N, int64_t ldw, void *Wt, float *w_rowmax,
+                                       hipStream_t st)
 {
-    hipLaunchKernelGGL(transpose_f16_kernel, dim3((unsigned)((N + 63) / 64), (unsigned)((K + 63) / 64)),
-                       dim3(256), 0, st, static_cast<const unsigned short *>(W), (int)K, (int)N, ldw,
-                       static_cast<unsigned short *>(Wt));
+    if (w_rowmax) {                                      // the maxima are collected with atomicMax: start from zero
+        hipLaunchKernelGGL(zero_f32_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, w_rowmax, (int)K);
+        if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(transpose_absmax_f16_kernel, dim3((unsigned)((N + 63) / 64), (unsigned)(K / 64)), dim3(256), 0, st,
+                       static_cast<const unsigned short *>(W), (int)K, (int)N, ldw, static_cast<unsigned short *>(Wt),
+                       w_rowmax);
     return hipGetLastError();
 }
 

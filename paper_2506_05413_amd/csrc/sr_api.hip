@@ -148,10 +148,9 @@ static int fold_impl(const void *W_f16, int64_t K, int64_t N, int64_t ldw, const
     float *s = reinterpret_cast<float *>(base + ws.s);
     float *wmax = reinterpret_cast<float *>(base + ws.wmax);
 
-    hipError_t e = hipSuccess;
-    if (act_absmax) e = sr::launch_row_absmax(W_f16, K, N, ldw, wmax, st);
+    // one pass over W gives the transposed copy and (where the factors need them) the row maxima
+    hipError_t e = sr::launch_transpose_absmax_f16(W_f16, K, N, ldw, Wt, act_absmax ? wmax : nullptr, st);
     if (e == hipSuccess) e = sr::launch_smooth_factors(act_absmax, wmax, K, alpha, s, inv_s, st);
-    if (e == hipSuccess) e = sr::launch_transpose_f16(W_f16, K, N, ldw, Wt, st);
     if (e != hipSuccess) return dev(e);
     // rows of Wt are the columns of W: rotate (s * column) and quantise per output channel;
     // the 1/order of H H^T = order * I goes into the scale only (codes do not depend on it).

@@ -114,17 +114,13 @@ hipError_t launch_fwht_quant_ex(const void *X_f16, int64_t rows, int64_t K, int6
 hipError_t launch_calib_absmax(const void *X_f16, int64_t T, int64_t K, int64_t ldx,
                                float *absmax_io, hipStream_t st);
 
-// w_rowmax[j] = max_n |W[j][n]|
-hipError_t launch_row_absmax(const void *W_f16, int64_t K, int64_t N, int64_t ldw,
-                             float *w_rowmax, hipStream_t st);
-
 // s / inv_s from calibration and weight maxima (act_absmax may be NULL: s = 1)
 hipError_t launch_smooth_factors(const float *act_absmax, const float *w_rowmax, int64_t K,
                                  float alpha, float *s, float *inv_s, hipStream_t st);
 
-// Wt[n][k] = W[k][n] (fp16 bits moved unchanged)
-hipError_t launch_transpose_f16(const void *W_f16, int64_t K, int64_t N, int64_t ldw,
-                                void *Wt_f16, hipStream_t st);
+// Wt[n][k] = W[k][n] (fp16 bits moved unchanged) and, if w_rowmax is not NULL, w_rowmax[j] = max_n |W[j][n]|
+hipError_t launch_transpose_absmax_f16(const void *W_f16, int64_t K, int64_t N, int64_t ldw, void *Wt_f16,
+                                       float *w_rowmax, hipStream_t st);
 
 // asymmetric 4-bit group quantiser (keys / values)
 hipError_t launch_kv_quant(const void *X_f16, int64_t rows, int64_t D, int64_t ldx, int64_t group, float clip,
