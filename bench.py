@@ -371,11 +371,14 @@ def main():
         ceil["mfma_i8_loop"] = {"us": round(t * 1e6, 2), "POP/s": round(ops[0] / t / 1e15, 3),
                                 "what": "v_mfma_i32_32x32x32_i8 on packed code bytes, same loop"}
         def valu_loop(i):
-            ops[0] = sr.sr_ceiling_valu_f32(16, 2 * CU)
-        t = graph_time(valu_loop, 60)
+            ops[0] = sr.sr_ceiling_valu_f32(160, 2 * CU)
+        t = graph_time(valu_loop, 20)
         ceil["valu_f32_loop"] = {"us": round(t * 1e6, 2), "T_wave_instr/s": round(ops[0] / t / 1e12, 3),
-                                 "implied_GHz": round(ops[0] / t * 4 / (4 * CU) / 1e9, 3),
-                                 "what": "fp32 add/sub/mul on 64 lanes, 2 waves per SIMD; 4 cycles per instruction and SIMD"}
+                                 "T_lane_instr/s": round(ops[0] * 64 / t / 1e12, 2),
+                                 "frac_of_78.6_T_lane_instr/s": round(ops[0] * 64 / t / 78.6e12, 3),
+                                 "SIMD_cycles_per_wave_instr_at_2.4GHz": round(2.4e9 * t * 4 * CU / ops[0], 2),
+                                 "what": "fp32 add / sub / mul (no FMA, no packed forms) on 64 lanes, 2 waves per SIMD, 192 instructions per "
+                                         "iteration; peak = 157.3 TFLOP/s FMA-counted = 78.6 T lane instructions/s"}
         rd = [Wq[14336][0].clone() for _ in range(20)]                         # 20 x 29.4 MB = 587 MB
         best = None
         for grid, block, fl, nt in ((8 * CU, 256, 8, True), (4 * CU, 512, 8, True), (8 * CU, 256, 16, True),
