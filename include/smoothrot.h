@@ -81,12 +81,11 @@ SR_API const char *sr_status_str(int status);
  *   SR_TUNE_DECODE_KERNEL  M <= 16 GEMM: 1 dot product (M <= 2), 2 MFMA per 16 channels, 3 streaming MFMA
  *   SR_TUNE_FWHT4096       K = 4096 rotation: 1 wave per row, 2 workgroup per row
  *   SR_TUNE_FWHT_STREAM    K = 14336 rotation: 1 workgroups walk over rows, 0 one workgroup per row
- *   SR_TUNE_GEMM_SPLITK    sr_w4a4_gemm_f6: 1 = one K range per tile, 2 = two K halves per tile
- *                          (partial sums through the workspace); ignored where the workspace is missing
+ *   SR_TUNE_GEMM_WARM      sr_w4a4_gemm_f6_warm: 0 = ignore the hint (the launch of sr_w4a4_gemm_f6)
  * sr_tune_set returns SR_ERR_ARG for an unknown knob; sr_tune_get returns SR_TUNE_AUTO for one.
  */
 enum { SR_TUNE_GEMM_TILE = 0, SR_TUNE_GEMM_GRID = 1, SR_TUNE_GEMM_XCDM = 2, SR_TUNE_DECODE_KERNEL = 3,
-       SR_TUNE_FWHT4096 = 4, SR_TUNE_FWHT_STREAM = 5, SR_TUNE_GEMM_SPLITK = 6 };
+       SR_TUNE_FWHT4096 = 4, SR_TUNE_FWHT_STREAM = 5, SR_TUNE_GEMM_WARM = 6 };
 #define SR_TUNE_AUTO INT64_MIN
 SR_API int sr_tune_set(int knob, int64_t value);
 SR_API int64_t sr_tune_get(int knob);
@@ -369,6 +368,26 @@ SR_API int sr_w4a4_gemm_f6(const uint8_t *X6, const float *x_scale,
                     int64_t M, int64_t N, int64_t K,
                     void *Y, int64_t ldy, int out_dtype,
                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * sr_w4a4_gemm_f6 that, on the side, warms the memory-side cache for the call after it: where the launch has a
+ * wave to spare -- the 256 x 128 tile configuration, which the dispatcher takes for shapes like M = 2048,
+ * N = 4096, K = 4096: such a GEMM is short of L2 delivery and LDS bandwidth, HBM is mostly idle -- an extra wave
+ * per workgroup reads one word of every 128-byte line of [next_operand, next_operand + next_bytes), spread over
+ * the K loop; elsewhere the hint is ignored.  Typical use: the weights of the next linear layer (the paper's
+ * deployment runs the projections of a block one after the other, Fig. 2), which a rotation + quantiser call
+ * in between is too short to fetch without paying for it.  Outputs are exactly those of sr_w4a4_gemm_f6; the
+ * words read are never used.
+ *   next_operand   device memory, readable for next_bytes bytes, 16-byte aligned; NULL with next_bytes = 0
+ *                  gives sr_w4a4_gemm_f6
+ * Errors as sr_w4a4_gemm_f6; SR_ERR_NULL for next_bytes without next_operand, SR_ERR_ALIGN for a misaligned one.
+ */
+SR_API int sr_w4a4_gemm_f6_warm(const uint8_t *X6, const float *x_scale,
+                         const uint8_t *W6, const float *w_scale,
+                         int64_t M, int64_t N, int64_t K,
+                         void *Y, int64_t ldy, int out_dtype,
+                         const void *next_operand, size_t next_bytes,
+                         void *workspace, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------
  * Measurement kernels (bench.py): what the chip sustains with nothing else in the way.  They compute

@@ -16,7 +16,7 @@ SR_OK, SR_ERR_NULL, SR_ERR_SHAPE, SR_ERR_UNSUPPORTED_K = 0, 1, 2, 3
 SR_ERR_ALIGN, SR_ERR_ARG, SR_ERR_WORKSPACE, SR_ERR_DEVICE = 4, 5, 6, 7
 SR_F16, SR_I32 = 0, 1
 SR_TUNE_GEMM_TILE, SR_TUNE_GEMM_GRID, SR_TUNE_GEMM_XCDM, SR_TUNE_DECODE_KERNEL = 0, 1, 2, 3
-SR_TUNE_FWHT4096, SR_TUNE_FWHT_STREAM, SR_TUNE_GEMM_SPLITK = 4, 5, 6
+SR_TUNE_FWHT4096, SR_TUNE_FWHT_STREAM, SR_TUNE_GEMM_WARM = 4, 5, 6
 SR_TUNE_KNOBS = 7
 SR_TUNE_AUTO = -(1 << 63)
 
@@ -50,6 +50,7 @@ _SIGNATURES = {
     "sr_fwht_quant_act_f6_warm": (_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _vp, _sz, _vp]),
     "sr_swiglu_fwht_quant_act_f6": (_int, [_vp, _vp, _i64, _i64, _i64, _i64, _vp, _f32, _vp, _vp, _vp]),
     "sr_w4a4_gemm_f6": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _int, _vp, _sz, _vp]),
+    "sr_w4a4_gemm_f6_warm": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _int, _vp, _sz, _vp, _sz, _vp]),
     "sr_ceiling_hbm_read": (_int, [_vp, _sz, _int, _int, _int, _int, _vp, _vp]),
     "sr_ceiling_row_stream": (_int, [_vp, _vp, _i64, _i64, _i64, _int, _int, _vp]),
     "sr_ceiling_mfma_f6": (_int, [_vp, _sz, _int, _int, _vp, _vp]),
@@ -310,17 +311,31 @@ def sr_pack_f6_tiles(Q4, T6=None):
     return T6
 
 
-def sr_w4a4_gemm_f6(X6, x_scale, W6, w_scale, M: int, N: int, K: int, out_dtype: int = SR_F16, Y=None):
-    """X6, W6 = f6 tiles of the codes [M, K] and [N, K] -> Y [M, N] fp16 (dequantised) or int32 (accumulators)."""
+def sr_w4a4_gemm_f6(X6, x_scale, W6, w_scale, M: int, N: int, K: int, out_dtype: int = SR_F16, Y=None, warm=None):
+    """X6, W6 = f6 tiles of the codes [M, K] and [N, K] -> Y [M, N] fp16 (dequantised) or int32 (accumulators).
+    warm: a contiguous device tensor (the weights of the next linear) to be pulled into the memory-side cache on
+    the side where the launch has a wave to spare (sr_w4a4_gemm_f6_warm)."""
     _dev(X6, torch.uint8, "X6"); _dev(W6, torch.uint8, "W6")
     if X6.numel() < sr_f6_tiles_bytes(M, K) or W6.numel() < sr_f6_tiles_bytes(N, K):
         raise ValueError("tile buffers are smaller than sr_f6_tiles_bytes says")
     if Y is None:
         Y = torch.empty((M, N), dtype=torch.float16 if out_dtype == SR_F16 else torch.int32, device=X6.device)
     ldy = Y.stride(0) if M > 1 else N
+    if warm is not None:
+        if not (warm.is_cuda and warm.is_contiguous()):
+            raise ValueError("warm must be a contiguous device tensor")
+        _check(raw().sr_w4a4_gemm_f6_warm(_ptr(X6), _ptr(x_scale), _ptr(W6), _ptr(w_scale), M, N, K, _ptr(Y), ldy,
+                                          out_dtype, _ptr(warm), warm.numel() * warm.element_size(), None, 0, _stream()),
+               "sr_w4a4_gemm_f6_warm")
+        return Y
     _check(raw().sr_w4a4_gemm_f6(_ptr(X6), _ptr(x_scale), _ptr(W6), _ptr(w_scale), M, N, K, _ptr(Y), ldy,
                                  out_dtype, None, 0, _stream()), "sr_w4a4_gemm_f6")
     return Y
+
+
+def sr_w4a4_gemm_f6_warm(X6, x_scale, W6, w_scale, M: int, N: int, K: int, warm, out_dtype: int = SR_F16, Y=None):
+    """sr_w4a4_gemm_f6 with the cache-warming hint (same outputs)."""
+    return sr_w4a4_gemm_f6(X6, x_scale, W6, w_scale, M, N, K, out_dtype, Y, warm)
 
 
 def sr_fwht_quant_act_f6(X, inv_s, clip: float = 0.9, X6=None, x_scale=None, warm=None):

@@ -64,12 +64,18 @@ __device__ __forceinline__ void dma4(const void *base, uint32_t lane_off, uint32
 
 // The work of one workgroup: tiles v0, v0 + vstep, ... (< total) of the tile grid tiles_m x tiles_n that starts
 // at output channel n_off.  CG = MFMA column tiles staged at a time by the epilogue.
-template <int BM, int BN, int WGM, int WGN, int SLOTS, int CG>
+// WARM: the workgroup has one wave more than the tile needs.  That wave computes nothing: it reads one word of
+// every 128-byte line of the workgroup's share of [warm, warm + 128 warm_lines), a few lines per K stage, so that
+// the memory-side cache holds that region when the next kernel asks for it -- the matrix waves are short of L2
+// delivery and LDS bandwidth, not of HBM bandwidth, and cannot issue such loads themselves (a wave's loads
+// complete in order: a slow load from HBM between the LDS-DMA loads would hold up their counted completion).
+// The extra wave joins every barrier of the workgroup, so its loop mirrors the barrier count of the tile loop.
+template <int BM, int BN, int WGM, int WGN, int SLOTS, int CG, bool WARM = false>
 __device__ __forceinline__ void f6_tiles(
     const uint8_t *__restrict__ X6, const float *__restrict__ xs, const uint8_t *__restrict__ W6,
     const float *__restrict__ ws, const int M, const int N, const int K, void *__restrict__ Yv, const int64_t ldy,
     const int out_i32, const int tiles_m, const int tiles_n, const int xcd_m, const int n_off, const int v0,
-    const int vstep, const int total)
+    const int vstep, const int total, const uint32_t *__restrict__ warm = nullptr, const int64_t warm_lines = 0)
 {
     constexpr int NWAVE = WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN;      // wave tile
@@ -92,6 +98,35 @@ __device__ __forceinline__ void f6_tiles(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WGM, wn = wave / WGM;
     const int nc = K >> 7;                           // 128-code chunks per row = stages
+    if constexpr (WARM) {
+        if (wave == NWAVE) {
+            // load instruction j of this wave touches lines (j * vstep + v0) * 64 + lane: the workgroups of the
+            // launch sweep the region front to back together
+            const int64_t per_wg = (warm_lines + (int64_t)vstep * 64 - 1) / ((int64_t)vstep * 64);   // instructions of this wave
+            const int my_tiles = (total - v0 + vstep - 1) / vstep;
+            // spread evenly over the K stages of this workgroup's tiles (measured inside the benchmark's step, 44 MB
+            // behind the M = 2048, N = 4096 GEMM: all loads up front costs the step 2.5 % against one per stage;
+            // non-temporal loads are not kept by the memory-side cache; the scope bits make no difference)
+            const int per_stage = (int)((per_wg + (int64_t)my_tiles * nc - 1) / ((int64_t)my_tiles * nc));
+            int64_t l = (int64_t)v0 * 64 + lane;
+            uint32_t word = 0;
+            for (int v = v0; v < total; v += vstep) {
+                barrier_nofence();
+                for (int s = 0; s < nc; ++s) {
+                    for (int i = 0; i < per_stage; ++i) {
+                        if (l < warm_lines) asm volatile("global_load_dword %0, %1, off" : "=v"(word) : "v"(warm + l * 32) : "memory");
+                        l += (int64_t)vstep * 64;
+                    }
+                    barrier_nofence();
+                }
+                barrier_nofence();
+                if (v + vstep < total) barrier_nofence();
+            }
+            wait_vmcnt<0>();
+            asm volatile("" ::"v"(word));
+            return;
+        }
+    }
     const uint32_t cx_bytes = (uint32_t)((M + 7) >> 3) * BLK, cw_bytes = (uint32_t)((N + 7) >> 3) * BLK;   // one chunk of X / W
 
     // ---- DMA sources: X instruction q copies bytes [1024 q, 1024 q + 1024) of the stage's X run, W instruction q
@@ -302,9 +337,23 @@ __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN * WG_PER_CU / 4) void gem
                                                      (int)blockIdx.x, (int)gridDim.x, tiles_m * tiles_n);
 }
 
-template <int BM, int BN, int WGM, int WGN, int SLOTS, int WG_PER_CU>
+// The same with a ninth wave that warms the memory-side cache (one workgroup per CU: three waves then share the
+// first SIMD, which the register budget of the 64 x 64 wave tile allows and that of the 128 x 64 one does not).
+template <int BM, int BN, int WGM, int WGN, int SLOTS>
+__global__ __launch_bounds__((WGM * WGN + 1) * 64) void gemm_f6_warm_kernel(
+    const uint8_t *__restrict__ X6, const float *__restrict__ xs, const uint8_t *__restrict__ W6,
+    const float *__restrict__ ws, int M, int N, int K, void *__restrict__ Yv, int64_t ldy, int out_i32,
+    int tiles_m, int tiles_n, int xcd_m, const uint32_t *__restrict__ warm, int64_t warm_lines)
+{
+    f6_tiles<BM, BN, WGM, WGN, SLOTS, BN / WGN / 32, true>(X6, xs, W6, ws, M, N, K, Yv, ldy, out_i32, tiles_m, tiles_n, xcd_m,
+                                                           0, (int)blockIdx.x, (int)gridDim.x, tiles_m * tiles_n, warm,
+                                                           warm_lines);
+}
+
+template <int BM, int BN, int WGM, int WGN, int SLOTS, int WG_PER_CU, bool CAN_WARM = false>
 hipError_t launch_f6(const uint8_t *X6, const float *xs, const uint8_t *W6, const float *ws, int64_t M, int64_t N,
-                     int64_t K, void *Y, int64_t ldy, int out_i32, hipStream_t st)
+                     int64_t K, void *Y, int64_t ldy, int out_i32, hipStream_t st, const void *warm = nullptr,
+                     size_t warm_bytes = 0)
 {
     auto kern = gemm_f6_kernel<BM, BN, WGM, WGN, SLOTS, WG_PER_CU>;
     constexpr int lds = f6_lds_bytes(BM, BN, SLOTS);
@@ -313,6 +362,17 @@ hipError_t launch_f6(const uint8_t *X6, const float *xs, const uint8_t *W6, cons
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
+    }
+    bool warms = false;
+    if constexpr (CAN_WARM) {
+        static_assert(WG_PER_CU == 1, "the extra wave is budgeted for one workgroup per CU");
+        warms = warm && warm_bytes >= 128;
+        if (int64_t w; tuned(kTuneGemmWarm, w) && w == 0) warms = false;
+        if (warms && lds > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_f6_warm_kernel<BM, BN, WGM, WGN, SLOTS>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            if (e != hipSuccess) return e;
+        }
     }
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
     int xcd_m = choose_xcd_split(tiles_m, tiles_n, BM, BN);
@@ -329,6 +389,14 @@ hipError_t launch_f6(const uint8_t *X6, const float *xs, const uint8_t *W6, cons
     if (out_i32) {
         xs = reinterpret_cast<const float *>(X6);
         ws = reinterpret_cast<const float *>(W6);
+    }
+    if constexpr (CAN_WARM) {
+        if (warms) {
+            hipLaunchKernelGGL((gemm_f6_warm_kernel<BM, BN, WGM, WGN, SLOTS>), dim3((unsigned)grid), dim3((WGM * WGN + 1) * 64),
+                               lds, st, X6, xs, W6, ws, (int)M, (int)N, (int)K, Y, ldy, out_i32, tiles_m, tiles_n, xcd_m,
+                               static_cast<const uint32_t *>(warm), (int64_t)(warm_bytes / 128));
+            return hipGetLastError();
+        }
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WGM * WGN * 64), lds, st, X6, xs, W6, ws,
                        (int)M, (int)N, (int)K, Y, ldy, out_i32, tiles_m, tiles_n, xcd_m);
@@ -383,7 +451,7 @@ hipError_t launch_pack_f6(const uint8_t *Q4, int64_t rows, int64_t K, uint8_t *T
 }
 
 hipError_t launch_gemm_f6(const uint8_t *X6, const float *xs, const uint8_t *W6, const float *ws, int64_t M, int64_t N,
-                          int64_t K, void *Y, int64_t ldy, int out_i32, hipStream_t st)
+                          int64_t K, void *Y, int64_t ldy, int out_i32, hipStream_t st, const void *warm, size_t warm_bytes)
 {
     // the tile knob selects a tile configuration by number; not set = heuristic
     int variant = 0;
@@ -392,7 +460,7 @@ hipError_t launch_gemm_f6(const uint8_t *X6, const float *xs, const uint8_t *W6,
         case 61: return launch_f6<256, 256, 2, 4, 3, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
         case 63: return launch_f6<256, 128, 2, 2, 2, 2>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
         case 64: return launch_f6<256, 256, 2, 4, 2, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
-        case 65: return launch_f6<256, 128, 4, 2, 4, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
+        case 65: return launch_f6<256, 128, 4, 2, 4, 1, true>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st, warm, warm_bytes);
         case 66: return launch_f6<256, 128, 4, 2, 3, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
         default: break;
     }
@@ -409,7 +477,7 @@ hipError_t launch_gemm_f6(const uint8_t *X6, const float *xs, const uint8_t *W6,
     const int64_t cost_big = rounds(tm * ((N + 255) / 256)) * 256 * 256 * 85;
     const int64_t cost_small = rounds(tm * ((N + 127) / 128)) * 256 * 128 * 100;
     if (cost_big <= cost_small) return launch_f6<256, 256, 2, 4, 3, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
-    return launch_f6<256, 128, 4, 2, 4, 1>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st);
+    return launch_f6<256, 128, 4, 2, 4, 1, true>(X6, xs, W6, ws, M, N, K, Y, ldy, out_i32, st, warm, warm_bytes);
 }
 
 }  // namespace sr

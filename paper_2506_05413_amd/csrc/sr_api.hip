@@ -374,9 +374,9 @@ int sr_pack_f6_tiles(const uint8_t *Q4, int64_t rows, int64_t K, uint8_t *T6, vo
     return dev(sr::launch_pack_f6(Q4, rows, K, T6, static_cast<hipStream_t>(stream)));
 }
 
-int sr_w4a4_gemm_f6(const uint8_t *X6, const float *x_scale, const uint8_t *W6, const float *w_scale,
-                    int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_dtype,
-                    void *workspace, size_t workspace_bytes, void *stream)
+int sr_w4a4_gemm_f6_warm(const uint8_t *X6, const float *x_scale, const uint8_t *W6, const float *w_scale,
+                         int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_dtype,
+                         const void *next_operand, size_t next_bytes, void *workspace, size_t workspace_bytes, void *stream)
 {
     (void)workspace; (void)workspace_bytes;
     if (M < 0 || N <= 0 || K <= 0 || N % 16 != 0 || ldy < N) return SR_ERR_SHAPE;
@@ -384,12 +384,22 @@ int sr_w4a4_gemm_f6(const uint8_t *X6, const float *x_scale, const uint8_t *W6, 
     if ((double)M * (double)K >= 4294967296.0 || (double)N * (double)K >= 4294967296.0) return SR_ERR_SHAPE;
     if (K % 128 != 0 || K >= 131072) return SR_ERR_UNSUPPORTED_K;
     if (out_dtype != SR_F16 && out_dtype != SR_I32) return SR_ERR_ARG;
+    if (next_bytes && !next_operand) return SR_ERR_NULL;
+    if (next_bytes && !aligned16(next_operand)) return SR_ERR_ALIGN;
     if (M == 0) return SR_OK;
     if (!X6 || !W6 || !Y) return SR_ERR_NULL;
     if (out_dtype == SR_F16 && (!x_scale || !w_scale)) return SR_ERR_NULL;
     if (ldy % 8 != 0 || !aligned16(X6) || !aligned16(W6) || !aligned16(Y)) return SR_ERR_ALIGN;
     return dev(sr::launch_gemm_f6(X6, x_scale, W6, w_scale, M, N, K, Y, ldy, out_dtype == SR_I32,
-                                  static_cast<hipStream_t>(stream)));
+                                  static_cast<hipStream_t>(stream), next_operand, next_bytes));
+}
+
+int sr_w4a4_gemm_f6(const uint8_t *X6, const float *x_scale, const uint8_t *W6, const float *w_scale,
+                    int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_dtype,
+                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    return sr_w4a4_gemm_f6_warm(X6, x_scale, W6, w_scale, M, N, K, Y, ldy, out_dtype, nullptr, 0, workspace,
+                                workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -64,7 +64,7 @@ __device__ __forceinline__ float max_of_wave(float v)
 // use them to run every kernel on every shape, tuning runs to compare variants inside one process.  A knob that
 // is not set (kTuneAuto) leaves the measured choice in place.  Relaxed atomics: a launch reads each knob once.
 enum { kTuneGemmTile = 0, kTuneGemmGrid, kTuneGemmXcdM, kTuneDecodeKernel, kTuneFwht4096, kTuneFwhtStream,
-       kTuneGemmSplitK, kTuneCount };
+       kTuneGemmWarm, kTuneCount };
 constexpr int64_t kTuneAuto = INT64_MIN;
 int64_t tune(int knob);                                  // sr_api.hip
 inline bool tuned(int knob, int64_t &v) { v = tune(knob); return v != kTuneAuto; }
@@ -140,9 +140,11 @@ hipError_t launch_gemm_prefill(const uint8_t *Xq, const float *xs, const uint8_t
 
 // f6 tiles (see gemm_f6.hip): repacking of canonical INT4 codes, and the GEMM on the FP6 matrix pipe
 hipError_t launch_pack_f6(const uint8_t *Q4, int64_t rows, int64_t K, uint8_t *T6, hipStream_t st);
+// warm / warm_bytes: a region whose 128-byte lines the launch reads on the side where its tile configuration has a
+// wave to spare (256 x 128 tiles); ignored elsewhere
 hipError_t launch_gemm_f6(const uint8_t *X6, const float *xs, const uint8_t *W6, const float *ws,
                           int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_i32,
-                          hipStream_t st);
+                          hipStream_t st, const void *warm = nullptr, size_t warm_bytes = 0);
 
 hipError_t launch_gemm_decode(const uint8_t *Xq, const float *xs, const uint8_t *Wq, const float *ws,
                               int64_t M, int64_t N, int64_t K, void *Y, int64_t ldy, int out_i32,

@@ -23,7 +23,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = declared_symbols()
-    assert len(names) == 29 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
+    assert len(names) == 30 and "sr_w4a4_gemm" in names and "sr_calib_absmax" in names
     lib = ctypes.CDLL(sr.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -376,5 +376,25 @@ def test_cache_warming_quantiser_rejects_bad_hints():
     assert call(clip=0.0) == sr.SR_ERR_ARG
     assert call(ldx=100) == sr.SR_ERR_SHAPE
     assert call(X=None) == sr.SR_ERR_NULL
+    assert call(M=0) == sr.SR_OK
+    assert call(M=0, nxt=None, nbytes=0) == sr.SR_OK
+
+
+
+def test_cache_warming_gemm_rejects_bad_hints():
+    raw = sr.raw()
+
+    def call(X6=A, xs=A, W6=A, ws=A, M=32, N=64, K=256, Y=A, ldy=64, dt=None, nxt=A, nbytes=4096):
+        return raw.sr_w4a4_gemm_f6_warm(X6, xs, W6, ws, M, N, K, Y, ldy, sr.SR_F16 if dt is None else dt, nxt, nbytes,
+                                        None, 0, None)
+    assert call(nxt=None) == sr.SR_ERR_NULL
+    assert call(nxt=A + 4) == sr.SR_ERR_ALIGN
+    assert call(K=192) == sr.SR_ERR_UNSUPPORTED_K
+    assert call(N=60) == sr.SR_ERR_SHAPE
+    assert call(ldy=32) == sr.SR_ERR_SHAPE
+    assert call(dt=7) == sr.SR_ERR_ARG
+    assert call(X6=None) == sr.SR_ERR_NULL
+    assert call(xs=None) == sr.SR_ERR_NULL
+    assert call(ldy=68) == sr.SR_ERR_ALIGN
     assert call(M=0) == sr.SR_OK
     assert call(M=0, nxt=None, nbytes=0) == sr.SR_OK

@@ -253,6 +253,46 @@ def test_cache_warming_changes_nothing(gpu, M, K):
     assert torch.equal(Ya, Yb)
 
 
+@pytest.mark.parametrize("M,N,K,grid", [(2048, 4096, 4096, None), (700, 1040, 640, None), (700, 1040, 640, 8), (300, 528, 1024, 16),
+                                          (1, 16, 128, None), (2048, 14336, 4096, None)])
+def test_gemm_cache_warming_changes_nothing(gpu, tune, M, N, K, grid):
+    """sr_w4a4_gemm_f6_warm: where the 256 x 128 tile configuration runs (forced here except for the two full-size
+    shapes, where the dispatcher's own choice is taken: N = 4096 honours the hint, N = 14336 ignores it) a ninth
+    wave per workgroup reads the hinted region and joins every barrier of the tile loop -- one tile per workgroup,
+    several tiles per workgroup (small forced grids: the barrier between tiles), regions shorter than a line, with a
+    ragged tail, larger than the workgroups' first sweep.  Accumulators and fp16 outputs must be exactly those of
+    sr_w4a4_gemm_f6, the region untouched, nothing written past the outputs; the knob that switches the hint off
+    gives the same again."""
+    print("case", M, N, K, grid, flush=True)
+    if (M, N) != (2048, 4096) and (M, N) != (2048, 14336):
+        tune(gpu.SR_TUNE_GEMM_TILE, 65)
+    if grid:
+        tune(gpu.SR_TUNE_GEMM_GRID, grid)
+    cx, cw = wl.random_codes(51 + M, M, K), wl.random_codes(52 + N, N, K)
+    X6, W6 = tiles(gpu, cx), tiles(gpu, cw)
+    rng = np.random.default_rng(N)
+    xs = torch.from_numpy((np.exp(rng.standard_normal(M) * 0.5) * 0.05).astype(np.float32)).cuda()
+    ws = torch.from_numpy((np.exp(rng.standard_normal(N) * 0.3) * 1e-3).astype(np.float32)).cuda()
+    acc0 = gpu.sr_w4a4_gemm_f6(X6, None, W6, None, M, N, K, gpu.SR_I32)
+    Y0 = gpu.sr_w4a4_gemm_f6(X6, xs, W6, ws, M, N, K, gpu.SR_F16)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc0.cpu().numpy().astype(np.int64), o.gemm_i32_c(cx, cw))
+    big = torch.randint(0, 255, (5 * 1024 * 1024 + 52,), dtype=torch.uint8, device="cuda")
+    big_before = big.clone()
+    for region in (big, big[:100], big[: 128 * 37 + 52], big[: 64 * 128 * 300 + 128], W6):
+        acc = torch.full((M + 3, N + 8), -7, dtype=torch.int32, device="cuda")
+        Y = torch.full((M + 3, N + 8), -7.0, dtype=torch.float16, device="cuda")
+        gpu.sr_w4a4_gemm_f6_warm(X6, None, W6, None, M, N, K, region, gpu.SR_I32, acc[:M, :N])
+        gpu.sr_w4a4_gemm_f6_warm(X6, xs, W6, ws, M, N, K, region, gpu.SR_F16, Y[:M, :N])
+        torch.cuda.synchronize()
+        assert torch.equal(acc[:M, :N], acc0) and torch.equal(Y[:M, :N], Y0)
+        assert bool((acc[M:] == -7).all()) and bool((acc[:, N:] == -7).all())
+        assert bool((Y[M:] == -7.0).all()) and bool((Y[:, N:] == -7.0).all())
+    assert torch.equal(big, big_before)
+    tune(gpu.SR_TUNE_GEMM_WARM, 0)
+    assert torch.equal(gpu.sr_w4a4_gemm_f6_warm(X6, xs, W6, ws, M, N, K, big), Y0)
+
+
 @pytest.mark.parametrize("M", [700, 1100])
 def test_row_kernel_walking_over_rows(gpu, tune, M):
     """K = 14336 with many rows: as many workgroups as the chip holds, each walking over several rows and

@@ -2,8 +2,9 @@
 
 configs[1] (M = 2048, K = 4096 -> N = 4096 and N = 14336) and configs[2] (K = 14336 -> N = 4096), in the launch
 configuration bench.py times: activations rotated and quantised by sr_fwht_quant_act_f6_warm with the GEMM's
-weights as the warming operand, then sr_w4a4_gemm_f6; and the same layer through the canonical-nibble quantiser and
-the int8-MFMA GEMM.  ALL M x K activation codes are held to the rounding-boundary rule, ALL M x N INT32 accumulators
+weights as the warming operand (N = 4096) or by sr_fwht_quant_act_f6 (N = 14336), then sr_w4a4_gemm_f6_warm with
+44 MB to warm (N = 4096: the launch that carries the extra wave) or sr_w4a4_gemm_f6; and the same layer through the
+canonical-nibble quantiser and the int8-MFMA GEMM.  ALL M x K activation codes are held to the rounding-boundary rule, ALL M x N INT32 accumulators
 must equal the oracle's triple loop on the GPU's own codes, ALL fp16 outputs must lie within 1e-2 * rms and within
 half an fp16 ulp (+ the two fp32 roundings of the epilogue) of the oracle's dequantised product."""
 import numpy as np
@@ -46,9 +47,14 @@ def test_benchmarked_launches_every_output(gpu, name, K, N):
     ref = o.fwht_quant_act(X, inv_s.cpu().numpy(), 0.9)                 # oracle on the GPU's fp32 factors
 
     # ---- tile path, as bench.py calls it
-    X6, xs6 = gpu.sr_fwht_quant_act_f6_warm(Xd, inv_s, 0.9, W6)
-    acc6 = gpu.sr_w4a4_gemm_f6(X6, None, W6, None, M, N, K, gpu.SR_I32)
-    Y6 = gpu.sr_w4a4_gemm_f6(X6, xs6, W6, ws, M, N, K, gpu.SR_F16)
+    if (K, N) == (4096, 14336):
+        X6, xs6 = gpu.sr_fwht_quant_act_f6(Xd, inv_s, 0.9)
+        nxt = None
+    else:
+        X6, xs6 = gpu.sr_fwht_quant_act_f6_warm(Xd, inv_s, 0.9, W6)
+        nxt = torch.randint(0, 255, (gpu.sr_f6_tiles_bytes(14336, 4096),), dtype=torch.uint8, device="cuda")   # the next linear's weights
+    acc6 = gpu.sr_w4a4_gemm_f6(X6, None, W6, None, M, N, K, gpu.SR_I32, warm=nxt)
+    Y6 = gpu.sr_w4a4_gemm_f6(X6, xs6, W6, ws, M, N, K, gpu.SR_F16, warm=nxt)
     torch.cuda.synchronize()
     cx6 = fc.f6_codes(fc.f6_tiles_unpack(X6.cpu().numpy(), M, K))
     check_scales(xs6.cpu().numpy(), ref["x_scale"])
