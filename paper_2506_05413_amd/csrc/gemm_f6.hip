@@ -70,6 +70,9 @@ __device__ __forceinline__ void dma4(const void *base, uint32_t lane_off, uint32
 // delivery and LDS bandwidth, not of HBM bandwidth, and cannot issue such loads themselves (a wave's loads
 // complete in order: a slow load from HBM between the LDS-DMA loads would hold up their counted completion).
 // The extra wave joins every barrier of the workgroup, so its loop mirrors the barrier count of the tile loop.
+// (Also built and measured for the 256 x 256 configuration, which has no registers for a ninth wave: the
+// workgroups that run out of tiles before the last round reading the region instead.  With the 12.6 MB of the
+// benchmark's N = 4096 weights behind its N = 14336 launch the step got 2 % slower, not faster; dropped.)
 template <int BM, int BN, int WGM, int WGN, int SLOTS, int CG, bool WARM = false>
 __device__ __forceinline__ void f6_tiles(
     const uint8_t *__restrict__ X6, const float *__restrict__ xs, const uint8_t *__restrict__ W6,
