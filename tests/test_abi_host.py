@@ -398,3 +398,26 @@ def test_cache_warming_gemm_rejects_bad_hints():
     assert call(ldy=68) == sr.SR_ERR_ALIGN
     assert call(M=0) == sr.SR_OK
     assert call(M=0, nxt=None, nbytes=0) == sr.SR_OK
+
+
+def test_header_is_plain_c_and_cpp():
+    """include/smoothrot.h is the boundary: it must compile on its own as C99 and as C++ (no HIP, no torch types),
+    and a C program must be able to link a call against the library."""
+    import subprocess, tempfile
+    inc = os.path.join(ROOT, "include")
+    with tempfile.TemporaryDirectory() as d:
+        c = os.path.join(d, "t.c")
+        with open(c, "w") as f:
+            f.write('#include "smoothrot.h"\nint main(void) { return sr_hadamard_supported(14336) == 1 && '
+                    'sr_hadamard_supported(100) == 0 && sr_f6_tiles_bytes(8, 128) == 768 ? 0 : 1; }\n')
+        r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", inc, "-fsyntax-only", c], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+        r = subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-I", inc, "-x", "c++", "-fsyntax-only", c], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+        exe = os.path.join(d, "t")
+        lib_dir = os.path.dirname(sr.LIB_PATH)
+        r = subprocess.run(["gcc", "-std=c99", "-I", inc, c, "-o", exe, "-L", lib_dir, "-lsmoothrot", "-Wl,-rpath," + lib_dir],
+                           capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+        r = subprocess.run([exe], capture_output=True, text=True)
+        assert r.returncode == 0, (r.returncode, r.stderr)
