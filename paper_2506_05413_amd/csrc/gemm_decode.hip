@@ -27,7 +27,6 @@
 //           in registers while the workgroup's weights stream past.
 #include "gemm_common.h"
 
-#include <cstdlib>
 
 namespace sr {
 namespace {

@@ -48,7 +48,6 @@
 #include "gemm_common.h"
 
 #include <hip/hip_fp16.h>
-#include <stdlib.h>
 #include <type_traits>
 
 namespace sr {

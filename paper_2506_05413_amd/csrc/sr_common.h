@@ -6,6 +6,7 @@
 #include <hip/hip_fp16.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <atomic>
 
 namespace sr {
 
@@ -73,15 +74,15 @@ inline bool tuned(int knob, int64_t &v) { v = tune(knob); return v != kTuneAuto;
 // compute units of the current device (asked once per process and device)
 inline int compute_units()
 {
-    static int cached[64] = {};
+    static std::atomic<int> cached[64];                  // zero-initialised; concurrent first calls store the same value
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
+        cached[dev].store(n, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return n;
 }
 
 // ---- launchers (each returns hipGetLastError() of its launches) ------------------
