@@ -79,7 +79,8 @@ SR_API const char *sr_status_str(int status);
  *   SR_TUNE_GEMM_GRID      persistent workgroups of the prefill GEMMs (rounded down to a multiple of 8)
  *   SR_TUNE_GEMM_XCDM      split of the tile grid over the 8 XCDs in m: 0 (none), 1, 2, 4, 8
  *   SR_TUNE_DECODE_KERNEL  M <= 16 GEMM: 1 dot product (M <= 2), 2 MFMA per 16 channels, 3 streaming MFMA
- *   SR_TUNE_FWHT4096       K = 4096 rotation: 1 wave per row, 2 workgroup per row
+ *   SR_TUNE_FWHT4096       K = 4096 rotation: 1 wave per row (factors staged in LDS), 4 wave per row (factors
+ *                          loaded per lane), 2 general workgroup-per-row kernel, 5 workgroup per row in two passes
  *   SR_TUNE_FWHT_STREAM    K = 14336 rotation: 1 workgroups walk over rows, 0 one workgroup per row
  *   SR_TUNE_GEMM_WARM      sr_w4a4_gemm_f6_warm: 0 = ignore the hint (the launch of sr_w4a4_gemm_f6)
  * sr_tune_set returns SR_ERR_ARG for an unknown knob; sr_tune_get returns SR_TUNE_AUTO for one.

@@ -490,6 +490,163 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
     asm volatile("" ::"v"(warm_acc));                    // keeps the warming loads; they returned long ago
 }
 
+// ------------------------------------------------------------------------------------------
+// K = 4096, one row per workgroup of four waves, two passes of SIX index bits each: four bits in registers
+// (16 values per thread) and two across neighbouring lanes by DPP.  A single wave of this chip issues a vector
+// instruction every ~5 cycles however independent its instructions are, and two waves per SIMD double that: the
+// wave-per-row kernel above leaves a row's ~1150 instructions to ONE wave (2.5 us after the row has arrived, with
+// two waves per SIMD at 2048 rows), this one to four waves of ~300 each, eight waves per SIMD -- with the same LDS
+// traffic (the row goes through LDS twice), where the general workgroup-per-row kernel needs three passes of four
+// bits and three round trips.
+//
+// Thread t holds x[16 t .. 16 t + 15]: index bits 0..3 in registers, bits 4, 5 in lane bits 0, 1.  A butterfly
+// across lanes is ONE instruction per value, v <- v + c * v[partner] (v_fmac_f32 with a DPP source, c = +1 in
+// the lane whose bit is clear, -1 in the other): the lane with the bit clear gets a + b, the other b - a -- the
+// difference with its sign flipped.  The flip is not undone on the spot: every later step is linear and pairs
+// only lanes with equal flips, so a value simply carries the sign (-1)^(number of set bits among the lane bits
+// used so far); row maxima ignore it, and the quantiser multiplies by 1/Delta anyway, so it multiplies by
+// -1/Delta where the sign is -1 (exact).  Pass 2 reads c + 64 r + 1024 q for r = 0..15 (c = t >> 2: index bits
+// 0..5, q = t & 3: bits 10, 11 in lane bits 0, 1; registers: bits 6..9), all written by threads with lane bits
+// 0, 1 = (t >> 6) & 3 -- one sign per thread from pass 1 -- and writes them back where it read them.
+// LDS layout: element i at i + 4 (i >> 5) + 16 (i >> 10) floats: the 16-byte writes of pass 1, the 4-byte
+// accesses of pass 2 (16 consecutive c and four q per wave: banks c + 16 q) and the 16-byte reads of the
+// quantiser are all free of bank conflicts.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ int wg4096_pos(int i) { return i + ((i >> 5) << 2) + ((i >> 10) << 4); }
+constexpr int kWg4096Floats = 4096 + 4 * 128 + 16 * 4;
+
+// v[e] += c * v[e] of the lane with lane bit 0 (QP = 0xB1) or lane bit 1 (QP = 0x4E) flipped, for 16 values.
+// (Inline assembly: the two wait states a DPP read needs after a vector write of the same register are given
+// by the s_nop in front; inside the block no instruction reads what its predecessor wrote.)
+template <int QP>
+__device__ __forceinline__ void lane_butterfly16(float (&v)[16], float c)
+{
+    static_assert(QP == 0xB1 || QP == 0x4E, "quad permutations [1,0,3,2] and [2,3,0,1]");
+#define SR_DPP_FMAC(i) "v_fmac_f32_dpp %" #i ", %" #i ", %16 quad_perm:[%17,%18,%19,%20] row_mask:0xf bank_mask:0xf\n\t"
+    asm("s_nop 1\n\t"
+        SR_DPP_FMAC(0) SR_DPP_FMAC(1) SR_DPP_FMAC(2) SR_DPP_FMAC(3) SR_DPP_FMAC(4) SR_DPP_FMAC(5) SR_DPP_FMAC(6) SR_DPP_FMAC(7)
+        SR_DPP_FMAC(8) SR_DPP_FMAC(9) SR_DPP_FMAC(10) SR_DPP_FMAC(11) SR_DPP_FMAC(12) SR_DPP_FMAC(13) SR_DPP_FMAC(14) SR_DPP_FMAC(15)
+        : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7]),
+          "+v"(v[8]), "+v"(v[9]), "+v"(v[10]), "+v"(v[11]), "+v"(v[12]), "+v"(v[13]), "+v"(v[14]), "+v"(v[15])
+        : "v"(c), "n"(QP & 3), "n"((QP >> 2) & 3), "n"((QP >> 4) & 3), "n"((QP >> 6) & 3));
+#undef SR_DPP_FMAC
+}
+
+// (Measured and dropped: 2, 4 or 8 rows per workgroup, one after the other, all loads issued up front and two LDS
+// buffers taking turns, so that a row would arrive while the one before it is computed -- 9.7 / 10.8 / 13.8 us
+// against 9.0 us at 2048 rows, worse at every row count below 16384.)
+template <bool HAS_PRE, bool F6>
+__global__ __launch_bounds__(256) void fwht4096_wg_kernel(const __half *__restrict__ X, int64_t ldx, int64_t rows,
+                                                          const float *__restrict__ pre, float clip, float post_scale,
+                                                          uint8_t *__restrict__ Q, float *__restrict__ scale_out,
+                                                          const uint32_t *__restrict__ warm, int64_t warm_lines)
+{
+    constexpr int K = 4096;
+    extern __shared__ __attribute__((aligned(16))) float smem_rows[];
+    __shared__ float red[4];
+    float *row = smem_rows;
+    const int t = threadIdx.x, lane = t & 63;
+    int64_t m = blockIdx.x;
+    if constexpr (F6) {
+        // the eight rows of a tile block from the same XCD: workgroup w = 8 a + x (XCD x) takes row a % 8 of
+        // block 8 (a / 8) + x
+        const int64_t w = blockIdx.x, x = w & 7, a = w >> 3;
+        m = 8 * (8 * (a >> 3) + x) + (a & 7);
+    }
+    if (m >= rows) return;                               // the whole workgroup: no barrier is left behind
+    const __half *x = X + m * ldx;
+
+    // ---- pass 1: index bits 0..5 ------------------------------------------------------------------
+    uint4 rx[2];
+    float4 rs[4];
+    rx[0] = *reinterpret_cast<const uint4 *>(x + 16 * t);
+    rx[1] = *reinterpret_cast<const uint4 *>(x + 16 * t + 8);
+    if (HAS_PRE) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) rs[q] = *reinterpret_cast<const float4 *>(pre + 16 * t + 4 * q);
+    }
+    const float c0 = (lane & 1) ? -1.f : 1.f, c1 = (lane & 2) ? -1.f : 1.f;
+    float v[16];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        union { uint4 u; half2v h[4]; } raw;
+        raw.u = rx[j];
+        if (HAS_PRE) {
+            const float4 s0 = rs[2 * j], s1 = rs[2 * j + 1];
+            pair_level(raw.h[0], s0.x, s0.y, v[8 * j], v[8 * j + 1]);
+            pair_level(raw.h[1], s0.z, s0.w, v[8 * j + 2], v[8 * j + 3]);
+            pair_level(raw.h[2], s1.x, s1.y, v[8 * j + 4], v[8 * j + 5]);
+            pair_level(raw.h[3], s1.z, s1.w, v[8 * j + 6], v[8 * j + 7]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) pair_level(raw.h[e], v[8 * j + 2 * e], v[8 * j + 2 * e + 1]);
+        }
+    }
+    butterflies_from<4, 2>(v);
+    lane_butterfly16<0xB1>(v, c0);
+    lane_butterfly16<0x4E>(v, c1);
+    {
+        float *d = row + wg4096_pos(16 * t);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<float4 *>(d + 4 * q) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+    }
+    // (barriers without the fence of __syncthreads: that would also wait for the warming loads below)
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    barrier_nofence();
+    // warming the memory-side cache for the kernel that follows (see fwht4096_wave_kernel): one word of every
+    // 128-byte line of the region, shared among the threads of the launch, ordinary loads, never looked at
+    uint32_t warm_acc = 0;
+    if (warm) {
+        const int64_t nthreads = (int64_t)gridDim.x * 256;
+        for (int64_t l = (int64_t)blockIdx.x * 256 + t; l < warm_lines; l += nthreads) warm_acc ^= warm[l * 32];
+    }
+
+    // ---- pass 2: index bits 6..11 -----------------------------------------------------------------
+    float *col = row + wg4096_pos((t >> 2) + 1024 * (t & 3));
+#pragma unroll
+    for (int r = 0; r < 16; ++r) v[r] = col[72 * r];     // element + 64 r sits 64 r + 4 * 2 r floats further
+    butterflies<4>(v);
+    lane_butterfly16<0xB1>(v, c0);
+    lane_butterfly16<0x4E>(v, c1);
+    float amax = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) amax = fmaxf(fmaxf(amax, fabsf(v[r])), fabsf(v[r + 1]));
+#pragma unroll
+    for (int r = 0; r < 16; ++r) col[72 * r] = v[r];     // the same thread read these: nothing to wait for
+    amax = max_of_wave(amax);
+    if (lane == 0) red[t >> 6] = amax;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    barrier_nofence();
+    amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const float delta = (amax == 0.f) ? 1.f : (clip * amax) / 7.f;
+    const float inv_delta = 1.f / delta;
+    if (t == 0) scale_out[m] = (amax == 0.f) ? 1.f : delta * post_scale;
+
+    // ---- quantise.  The 16 values of group g = i >> 4 carry the sign (-1)^(popcount(g & 3) + popcount(g >> 6)):
+    // lane bits 0, 1 of their writer in pass 1 were g & 3, in pass 2 g >> 6.
+    auto signed_inv = [&](int g) { return (__builtin_popcount((g & 3) | ((g >> 6) << 2)) & 1) ? -inv_delta : inv_delta; };
+    if constexpr (F6) {
+        if (t < K / 32) {
+            const float *s32 = row + 36 * t + 16 * (t >> 5);
+            quant_store_f6_piece(s32, signed_inv(2 * t), signed_inv(2 * t + 1), Q, (rows + 7) >> 3, m, t);
+        }
+    } else {
+        const float *s16 = row + wg4096_pos(16 * t);
+        const float sd = signed_inv(t);
+        uint32_t *q = reinterpret_cast<uint32_t *>(Q + m * (int64_t)(K / 2));
+        uint32_t w2[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const float4 a = *reinterpret_cast<const float4 *>(s16 + 8 * h);
+            const float4 b = *reinterpret_cast<const float4 *>(s16 + 8 * h + 4);
+            const float y[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+            w2[h] = quant_pack8(y, sd);
+        }
+        *reinterpret_cast<uint2 *>(q + 2 * t) = make_uint2(w2[0], w2[1]);
+    }
+    asm volatile("" ::"v"(warm_acc));                    // keeps the warming loads; they returned long ago
+}
+
 __global__ __launch_bounds__(256) void fill_f32_kernel(float *__restrict__ dst, int64_t n, float value)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -602,6 +759,7 @@ hipError_t launch_one_ex(const void *X, int64_t rows, int64_t ldx, const float *
 // K = 4096: below this many rows the wave-per-row kernel leaves most of the chip idle (4 rows per workgroup)
 // and the workgroup-per-row kernel has the shorter critical path.
 constexpr int64_t kWaveKernelMinRows = 1024;   // measured: 3.3 - 4.8 us against 4.2 - 5.9 us up to 512 rows, equal at 1024
+constexpr int64_t kWgKernelMaxRows = 3072;     // the two-pass workgroup-per-row kernel up to here (see launch_fwht_quant)
 
 template <bool HAS_PRE, bool F6, bool MASKED = false, bool STAGED = false>
 hipError_t launch_wave4096(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip, float post_scale,
@@ -619,12 +777,36 @@ hipError_t launch_wave4096(const void *X, int64_t rows, int64_t ldx, const float
     return hipGetLastError();
 }
 
+template <bool HAS_PRE, bool F6>
+hipError_t launch_wg4096(const void *X, int64_t rows, int64_t ldx, const float *pre, float clip, float post_scale,
+                         uint8_t *Q, float *scale_out, hipStream_t st, const void *warm, size_t warm_bytes)
+{
+    constexpr size_t lds = kWg4096Floats * sizeof(float);
+    const unsigned blocks = F6 ? (unsigned)((rows + 63) / 64 * 64) : (unsigned)rows;
+    const bool warms = warm && warm_bytes >= 128 && blocks >= 256;
+    hipLaunchKernelGGL((fwht4096_wg_kernel<HAS_PRE, F6>), dim3(blocks), dim3(256), lds, st, static_cast<const __half *>(X), ldx,
+                       rows, pre, clip, post_scale, Q, scale_out, warms ? static_cast<const uint32_t *>(warm) : nullptr,
+                       (int64_t)(warm_bytes / 128));
+    return hipGetLastError();
+}
+
 hipError_t launch_fwht_quant(const void *X, int64_t rows, int64_t K, int64_t ldx, const float *pre,
                              float clip, float post_scale, uint8_t *Q, float *scale_out, hipStream_t st, bool f6,
                              const void *warm, size_t warm_bytes)
 {
     int pick = 0;
     if (int64_t f; tuned(kTuneFwht4096, f)) pick = (int)f;
+    // K = 4096: a workgroup of four waves per row in two passes of six bits up to kWgKernelMaxRows rows (every row
+    // count measured from 1 to 3072: 3.1 / 3.4 / 4.7 / 6.1 / 9.0 / 12.5 us for 1 / 64 / 512 / 1024 / 2048 / 3072 rows
+    // against 3.5 / 3.7 / 5.3 / 6.8 / 9.5 / 13.4 for the general workgroup-per-row kernel and 4.4 / 5.4 / 6.3 / 7.2 /
+    // 9.4 / 14.0 for a wave per row); a wave per row beyond (16384 rows: 52 against 57 us)
+    const bool wg_ok = !pre || (reinterpret_cast<uintptr_t>(pre) & 15u) == 0;
+    if (K == 4096 && wg_ok && (pick == 5 || (pick == 0 && rows <= kWgKernelMaxRows))) {
+        if (pre) return f6 ? launch_wg4096<true, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, warm, warm_bytes)
+                           : launch_wg4096<true, false>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, warm, warm_bytes);
+        return f6 ? launch_wg4096<false, true>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, warm, warm_bytes)
+                  : launch_wg4096<false, false>(X, rows, ldx, pre, clip, post_scale, Q, scale_out, st, warm, warm_bytes);
+    }
     if (K == 4096 && (pick == 1 || pick == 3 || pick == 4 || (pick == 0 && rows > kWaveKernelMinRows))) {
         constexpr uint32_t all = 0xFFFFFFFFu;
         // factors through LDS (one copy per workgroup) unless the knob asks for per-wave vector loads (4)

@@ -274,13 +274,16 @@ __device__ __forceinline__ uint32_t quant_pack8(const float (&y)[8], float inv_d
 // 32 p + 31) and stores its 24 bytes: the first 16 and the last 8 go to different places of the tile block.
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef unsigned int v6u __attribute__((ext_vector_type(6)));
-__device__ __forceinline__ void quant_store_f6_piece(const float *s32, float inv_delta, uint8_t *__restrict__ T6,
+// (inv_lo for the first 16 values, inv_hi for the last 16: callers whose values carry a sign per group of 16
+// pass +-1/Delta; the others the same factor twice)
+__device__ __forceinline__ void quant_store_f6_piece(const float *s32, float inv_lo, float inv_hi, uint8_t *__restrict__ T6,
                                                      int64_t row_blocks, int64_t m, int p)
 {
     v16f ev, od;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
         const float4 q = *reinterpret_cast<const float4 *>(s32 + 4 * k);
+        const float inv_delta = k < 4 ? inv_lo : inv_hi;
         ev[2 * k] = __builtin_amdgcn_fmed3f(q.x * inv_delta, -8.f, 7.f);
         od[2 * k] = __builtin_amdgcn_fmed3f(q.y * inv_delta, -8.f, 7.f);
         ev[2 * k + 1] = __builtin_amdgcn_fmed3f(q.z * inv_delta, -8.f, 7.f);
@@ -293,6 +296,11 @@ __device__ __forceinline__ void quant_store_f6_piece(const float *s32, float inv
     uint8_t *blk = T6 + ((int64_t)C * row_blocks + R) * 768;
     *reinterpret_cast<uint4 *>(blk + 256 * t + 128 * (g ^ swz) + 16 * r) = make_uint4(f[0], f[1], f[2], f[3]);
     *reinterpret_cast<uint2 *>(blk + 512 + 128 * (g ^ swz) + 16 * r + 8 * t) = make_uint2(f[4], f[5]);
+}
+__device__ __forceinline__ void quant_store_f6_piece(const float *s32, float inv_delta, uint8_t *__restrict__ T6,
+                                                     int64_t row_blocks, int64_t m, int p)
+{
+    quant_store_f6_piece(s32, inv_delta, inv_delta, T6, row_blocks, m, p);
 }
 
 // ---- rotation of one row by a whole workgroup -----------------------------------------------

@@ -197,6 +197,47 @@ def test_quantiser_tiles_wave_kernel(gpu, M, smooth):
         assert codes.min() >= -8 and codes.max() <= 7
 
 
+# K = 4096 has four kernels; the knob forces each one on row counts on both sides of the dispatcher's switch
+# (1 = a wave per row with the factors staged in LDS, 4 = a wave per row with per-lane factor loads,
+#  2 = the general workgroup-per-row kernel, 5 = a workgroup of four waves per row in two passes of six bits).
+@pytest.mark.parametrize("kernel", [1, 4, 2, 5])
+@pytest.mark.parametrize("M", [1, 7, 64, 300, 1030, 2048, 3080])
+def test_every_k4096_kernel(gpu, tune, kernel, M):
+    """Tiles and nibbles of every K = 4096 kernel against the oracle (scales to 1e-6, codes under the boundary rule),
+    with and without factors, with a padded leading dimension, and with the cache-warming hint (outputs unchanged).
+    The rotations differ in the order of their fp32 additions, so the kernels are held to the oracle, not to each
+    other; only the two output formats of ONE kernel share a rotation: identical scales."""
+    print("case", kernel, M, flush=True)
+    K = 4096
+    tune(gpu.SR_TUNE_FWHT4096, kernel)
+    X = wl.gauss_acts(500 + M, M, K, 5, 300.0)
+    rng = np.random.default_rng(M)
+    for inv_s in (rng.uniform(0.25, 4.0, K).astype(np.float32), None):
+        ref = o.fwht_quant_act(X, inv_s, 0.9)
+        inv = None if inv_s is None else torch.from_numpy(inv_s).cuda()
+        buf = torch.zeros((M, K + 24), dtype=torch.float16, device="cuda")
+        buf[:, :K] = torch.from_numpy(X).cuda()
+        for Xd in (torch.from_numpy(X).cuda(), buf[:, :K]):
+            X6, xs6 = gpu.sr_fwht_quant_act_f6(Xd, inv, 0.9)
+            Xq, xs4 = gpu.sr_fwht_quant_act(Xd, inv, 0.9)
+            torch.cuda.synchronize()
+            codes6 = fc.f6_codes(fc.f6_tiles_unpack(X6.cpu().numpy(), M, K))
+            codes4 = o.unpack_int4(Xq.cpu().numpy())
+            check_scales(xs6.cpu().numpy(), ref["x_scale"])
+            assert torch.equal(xs6, xs4)
+            check_codes(codes6, ref["codes"], ref["t"], "tiles, kernel %d" % kernel)
+            check_codes(codes4, ref["codes"], ref["t"], "nibbles, kernel %d" % kernel)
+        region = torch.randint(0, 255, (3 * 1024 * 1024 + 52,), dtype=torch.uint8, device="cuda")
+        X6w, xsw = gpu.sr_fwht_quant_act_f6(torch.from_numpy(X).cuda(), inv, 0.9, warm=region)
+        X6p, xsp = gpu.sr_fwht_quant_act_f6(torch.from_numpy(X).cuda(), inv, 0.9)
+        torch.cuda.synchronize()
+        assert torch.equal(X6w, X6p) and torch.equal(xsw, xsp)
+    Z = np.zeros((M, K), np.float16)                                     # all-zero rows: Delta = 1, codes 0
+    X6, xs = gpu.sr_fwht_quant_act_f6(torch.from_numpy(Z).cuda(), None, 0.9)
+    torch.cuda.synchronize()
+    assert bool((xs == 1.0).all()) and not fc.f6_codes(fc.f6_tiles_unpack(X6.cpu().numpy(), M, K)).any()
+
+
 @pytest.mark.parametrize("M,K", [(13, 512), (1027, 4096), (33, 14336)])
 def test_padding_rows_of_the_activation_tiles_cannot_leak(gpu, M, K):
     """The quantiser leaves the rows that pad the last block of 8 unwritten, so the GEMM multiplies whatever the
