@@ -508,12 +508,12 @@ __global__ __launch_bounds__(256) void fwht4096_wave_kernel(const __half *__rest
 // -1/Delta where the sign is -1 (exact).  Pass 2 reads c + 64 r + 1024 q for r = 0..15 (c = t >> 2: index bits
 // 0..5, q = t & 3: bits 10, 11 in lane bits 0, 1; registers: bits 6..9), all written by threads with lane bits
 // 0, 1 = (t >> 6) & 3 -- one sign per thread from pass 1 -- and writes them back where it read them.
-// LDS layout: element i at i + 4 (i >> 5) + 16 (i >> 10) floats: the 16-byte writes of pass 1, the 4-byte
-// accesses of pass 2 (16 consecutive c and four q per wave: banks c + 16 q) and the 16-byte reads of the
-// quantiser are all free of bank conflicts.
+// LDS layout: element i at i + 4 (i >> 5) + 8 (i >> 10) floats: the 16-byte writes of pass 1, the 4-byte
+// accesses of pass 2 (a half-wave covers eight consecutive c and four q: banks c + 8 q, all 32) and the 16-byte
+// reads of the quantiser are all free of bank conflicts.
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ int wg4096_pos(int i) { return i + ((i >> 5) << 2) + ((i >> 10) << 4); }
-constexpr int kWg4096Floats = 4096 + 4 * 128 + 16 * 4;
+__device__ __forceinline__ int wg4096_pos(int i) { return i + ((i >> 5) << 2) + ((i >> 10) << 3); }
+constexpr int kWg4096Floats = 4096 + 4 * 128 + 8 * 4;
 
 // v[e] += c * v[e] of the lane with lane bit 0 (QP = 0xB1) or lane bit 1 (QP = 0x4E) flipped, for 16 values.
 // (Inline assembly: the two wait states a DPP read needs after a vector write of the same register are given
@@ -627,7 +627,7 @@ __global__ __launch_bounds__(256) void fwht4096_wg_kernel(const __half *__restri
     auto signed_inv = [&](int g) { return (__builtin_popcount((g & 3) | ((g >> 6) << 2)) & 1) ? -inv_delta : inv_delta; };
     if constexpr (F6) {
         if (t < K / 32) {
-            const float *s32 = row + 36 * t + 16 * (t >> 5);
+            const float *s32 = row + 36 * t + 8 * (t >> 5);
             quant_store_f6_piece(s32, signed_inv(2 * t), signed_inv(2 * t + 1), Q, (rows + 7) >> 3, m, t);
         }
     } else {
