@@ -165,8 +165,8 @@ def test_quantiser_tiles_agree_with_the_nibble_path(gpu):
     """Same rotation, two output formats.  The tile fields are rounded by the hardware FP6 conversion of the
     fp32 product y * (1 / Delta), the nibbles by a fused multiply-add with the rounding constant: each is held to
     the rounding-boundary rule against the oracle, the scales are identical, and the two sets of codes may differ
-    only at such boundaries (a handful per million).  M = 2048, K = 4096 runs the wave-per-row kernel, the others
-    the workgroup-per-row kernel."""
+    only at such boundaries (a handful per million).  K = 4096 runs the two-pass workgroup-per-row kernel, K = 14336
+    the general workgroup-per-row kernel."""
     for M, K in ((2048, 4096), (40, 4096), (24, 14336)):
         X = wl.cfg2_X(M, K) if K == 4096 else wl.cfg3_X(M, K)
         inv_s = np.random.default_rng(M).uniform(0.5, 2.0, K).astype(np.float32)
@@ -183,9 +183,10 @@ def test_quantiser_tiles_agree_with_the_nibble_path(gpu):
 
 @pytest.mark.parametrize("M", [1025, 1030, 1100])
 @pytest.mark.parametrize("smooth", [True, False])
-def test_quantiser_tiles_wave_kernel(gpu, M, smooth):
-    """K = 4096 with more than 1024 rows: the wave-per-row kernel (tile fields from the hardware FP6 conversion)
-    against the oracle, with row counts that leave the last 8-row block and the last 64-row group ragged."""
+def test_quantiser_tiles_ragged_row_counts(gpu, M, smooth):
+    """K = 4096 with row counts that leave the last 8-row block and the last 64-row group ragged (the dispatcher's
+    own kernel: a workgroup per row in two passes; the other K = 4096 kernels are forced in
+    test_every_k4096_kernel): tile fields from the hardware FP6 conversion against the oracle."""
     K = 4096
     X = wl.gauss_acts(11 + M, M, K, 5, 300.0)
     inv_s = np.random.default_rng(M).uniform(0.25, 4.0, K).astype(np.float32) if smooth else None

@@ -105,9 +105,12 @@ def test_edge_rows_and_strides(gpu):
     compare(gpu, X[:1], None, 1.0, what="M=1")
 
 
-def test_wave_per_row_kernel_edges(gpu):
-    """K = 4096 above 1024 rows runs on the wave-per-row kernel: ragged row count (1027 = 4 * 256 + 3),
-    degenerate rows, padded leading dimension, with and without smoothing factors."""
+@pytest.mark.parametrize("kernel", [5, 1, 4])
+def test_k4096_many_row_kernels_edges(gpu, tune, kernel):
+    """The K = 4096 kernels for many rows (5: a workgroup per row in two passes, the default up to 3072 rows;
+    1 / 4: a wave per row, the default beyond): ragged row count (1027 = 4 * 256 + 3), degenerate rows, padded
+    leading dimension, with and without smoothing factors."""
+    tune(gpu.SR_TUNE_FWHT4096, kernel)
     K, M = 4096, 1027
     X = wl.cfg2_X(M=M).copy()
     X[2] = 0
